@@ -1,0 +1,434 @@
+"""Pins of the CPU oracle against things other than itself (CPU only).
+
+Each test cites what fixes the expected value: a definition of the paper, a closed form,
+a library routine on a special case, brute force in exact arithmetic, or an invariant.
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle.definition import DefinitionMAC, bf16_bits_to_f64, exact_sq_dist, unshifted_summary
+from oracle.mac_oracle import Oracle
+from paper_2604_00235_amd.workload import Workload, WorkloadConfig, bf16_bits
+from tests.helpers import dense_kv, host_inputs, make_oracle, rel_l2
+
+
+def small_cfg(**kw) -> WorkloadConfig:
+    base = dict(name="small", batch=2, num_q_heads=4, num_kv_heads=2, context=37, steps=14, window=4, band=3,
+                threshold=3.0, rho=0.9, head_dim=16, page_size=4, seed=11)
+    base.update(kw)
+    return WorkloadConfig(**base)
+
+
+# ----------------------------------------------------------------------------- full attention
+def test_full_decode_matches_torch_softmax():
+    """Sec. 2 "Notation": o = softmax(q.K/sqrt(d)) V; torch.softmax in fp64 is the library routine."""
+    cfg = small_cfg(context=53, steps=3, head_dim=32, page_size=8)
+    wl = Workload(cfg)
+    orc = make_oracle(cfg, wl)
+    kvp, bt, _ = host_inputs(wl)
+    for q_pre, q_rope, kv_lens in wl:
+        out, lse = orc.full_decode(kv_lens.numpy(), bf16_bits(q_rope), kvp, bt)
+        for b in range(cfg.batch):
+            n = int(kv_lens[b])
+            K, V = dense_kv(wl, b, n)
+            for h in range(cfg.num_q_heads):
+                g = h // cfg.group
+                q = q_rope[b, h].double()
+                logits = torch.from_numpy(K[:, g]) @ q * orc.sm_scale
+                ref = torch.softmax(logits, 0) @ torch.from_numpy(V[:, g])
+                np.testing.assert_allclose(out[b, h], ref.numpy(), rtol=1e-12, atol=1e-14)
+                np.testing.assert_allclose(lse[b, h], torch.logsumexp(logits, 0).item(), rtol=1e-13)
+
+
+def test_full_decode_closed_forms():
+    """q = 0 or all keys equal => uniform weights => out = mean of V over [0, n);
+    one key with a huge logit => out = that value row."""
+    cfg = small_cfg(batch=1, context=29, steps=1, head_dim=16)
+    wl = Workload(cfg)
+    orc = make_oracle(cfg, wl)
+    kvp, bt, _ = host_inputs(wl)
+    q_pre, q_rope, kv_lens = wl.next_step()
+    n = int(kv_lens[0])
+    K, V = dense_kv(wl, 0, n)
+    # q = 0
+    out, lse = orc.full_decode(kv_lens.numpy(), np.zeros_like(bf16_bits(q_rope)), kvp, bt)
+    for h in range(cfg.num_q_heads):
+        np.testing.assert_allclose(out[0, h], V[:, h // cfg.group].mean(0), rtol=1e-13, atol=1e-15)
+        assert abs(lse[0, h] - math.log(n)) < 1e-13
+    # all keys equal
+    wl2 = Workload(cfg)
+    wl2.kv_pages[:, 0] = wl2.kv_pages[0, 0, 0, 0]
+    out, _ = orc.full_decode(kv_lens.numpy(), bf16_bits(q_rope), bf16_bits(wl2.kv_pages), bt)
+    K2, V2 = dense_kv(wl2, 0, n)
+    for h in range(cfg.num_q_heads):
+        np.testing.assert_allclose(out[0, h], V2[:, h // cfg.group].mean(0), rtol=1e-12, atol=1e-15)
+    # one dominant key: key t* = 64 * q direction
+    wl3 = Workload(cfg)
+    tstar = 17
+    page, within = int(wl3.block_table[0, tstar // cfg.page_size]), tstar % cfg.page_size
+    qv = q_rope[0, 0].float()
+    wl3.kv_pages[page, 0, 0, within] = (qv * 64.0).to(torch.bfloat16)
+    out, _ = orc.full_decode(kv_lens.numpy(), bf16_bits(q_rope), bf16_bits(wl3.kv_pages), bt)
+    K3, V3 = dense_kv(wl3, 0, n)
+    np.testing.assert_allclose(out[0, 0], V3[tstar, 0], atol=1e-9)
+
+
+def test_shifted_equals_unshifted_definition():
+    """The (O, LSE) form equals the unshifted S/Z of Sec. 3.1 on small logits."""
+    cfg = small_cfg(batch=1, context=21, steps=1)
+    wl = Workload(cfg)
+    orc = make_oracle(cfg, wl)
+    kvp, bt, _ = host_inputs(wl)
+    _, q_rope, kv_lens = wl.next_step()
+    n = int(kv_lens[0])
+    K, V = dense_kv(wl, 0, n)
+    for h in range(cfg.num_q_heads):
+        for lo, hi in [(0, n), (3, 9), (n - 1, n), (5, 5)]:
+            O, lse = orc.summary(bf16_bits(q_rope), kvp, bt, 0, h, lo, hi)
+            S, Z = unshifted_summary(q_rope[0, h].double().numpy(), K[:, h // cfg.group], V[:, h // cfg.group],
+                                     lo, hi, orc.sm_scale)
+            if hi > lo:
+                np.testing.assert_allclose(O, S / Z, rtol=1e-12, atol=1e-15)
+                assert abs(lse - math.log(Z)) < 1e-12
+            else:
+                assert lse == -np.inf and np.all(O == 0)
+
+
+# ----------------------------------------------------------------------------- merge
+def test_merge_of_arbitrary_partition_equals_unsplit():
+    """Sec. 3.1: summaries over disjoint sets merge by addition, at any split point, in any order."""
+    cfg = small_cfg(batch=1, context=61, steps=1)
+    wl = Workload(cfg)
+    orc = make_oracle(cfg, wl)
+    kvp, bt, _ = host_inputs(wl)
+    _, q_rope, kv_lens = wl.next_step()
+    qb = bf16_bits(q_rope)
+    n = int(kv_lens[0])
+    rng = np.random.default_rng(5)
+    for h in range(cfg.num_q_heads):
+        whole, whole_l = orc.summary(qb, kvp, bt, 0, h, 0, n)
+        for trial in range(6):
+            cuts = np.sort(rng.choice(np.arange(1, n), size=rng.integers(1, 7), replace=False))
+            edges = [0, *cuts.tolist(), n]
+            parts = [orc.summary(qb, kvp, bt, 0, h, a, b) for a, b in zip(edges[:-1], edges[1:])]
+            order = rng.permutation(len(parts))
+            O, l = np.zeros(cfg.head_dim), -np.inf       # identity element
+            for i in order:
+                O, l = Oracle.merge(O, l, parts[i][0], parts[i][1])
+            np.testing.assert_allclose(O, whole, rtol=1e-12, atol=1e-15)
+            assert abs(l - whole_l) < 1e-12
+
+
+def test_merge_identity_and_inverse():
+    """(0, -inf) is the identity; removing b from merge(a, b) by subtraction of (S, Z) gives back a."""
+    rng = np.random.default_rng(0)
+    a, b = rng.normal(size=8), rng.normal(size=8)
+    la, lb = 0.7, -1.3
+    O, l = Oracle.merge(a, la, np.zeros(8), -np.inf)
+    np.testing.assert_array_equal(O, a)
+    assert l == la
+    O, l = Oracle.merge(np.zeros(8), -np.inf, b, lb)
+    np.testing.assert_array_equal(O, b)
+    O, l = Oracle.merge(np.zeros(8), -np.inf, np.zeros(8), -np.inf)
+    assert l == -np.inf and np.all(O == 0)
+    O, l = Oracle.merge(a, la, b, lb)
+    S, Z = O * math.exp(l), math.exp(l)
+    Sa, Za = S - b * math.exp(lb), Z - math.exp(lb)
+    np.testing.assert_allclose(Sa / Za, a, rtol=1e-12)
+    assert abs(math.log(Za) - la) < 1e-12
+    # closed form with two one-element sets: weights e^{la}/(e^{la}+e^{lb})
+    wa = 1.0 / (1.0 + math.exp(lb - la))
+    np.testing.assert_allclose(O, wa * a + (1 - wa) * b, rtol=1e-13)
+
+
+# ----------------------------------------------------------------------------- match
+def _fill_ring(orc: Oracle, rng, n_now: int, count: int):
+    """Put `count` random entries created at lengths n_now-count .. n_now-1 into slot 0."""
+    W, Hq, d = orc.W, orc.Hq, orc.d
+    for n_p in range(n_now - count, n_now):
+        j = (n_p - 1) % W
+        vals = torch.from_numpy(rng.normal(size=(Hq, d)).astype(np.float32)).to(torch.bfloat16)
+        orc.ring_q[0, j] = bf16_bits(vals)
+        orc.ring_npos[0, j] = n_p
+
+
+def test_match_brute_force_exact_rationals():
+    """Eq. (accept) with exact rational arithmetic on the bf16 inputs: exact argmin and decision."""
+    rng = np.random.default_rng(3)
+    for trial in range(20):
+        orc = Oracle(num_q_heads=3, num_kv_heads=1, head_dim=8, page_size=4, window=6, band=2,
+                     threshold=float(rng.uniform(2.0, 5.0)), strides=(1, 1, 1, 1), max_slots=1)
+        n = 40 + trial
+        count = int(rng.integers(0, 7))
+        _fill_ring(orc, rng, n, count)
+        q = torch.from_numpy(rng.normal(size=(1, 3, 8)).astype(np.float32)).to(torch.bfloat16)
+        pos, idx, d2 = orc.match(np.array([0]), np.array([n]), bf16_bits(q))
+        qf = bf16_bits_to_f64(bf16_bits(q))[0]
+        for h in range(3):
+            best, best_np = None, None
+            for j in range(orc.W):
+                n_p = int(orc.ring_npos[0, j])
+                if n_p < 1 or not (n - orc.W <= n_p <= n - 1):
+                    continue
+                dist = exact_sq_dist(qf[h], bf16_bits_to_f64(orc.ring_q[0, j, h]))
+                if best is None or dist < best or (dist == best and n_p > best_np):
+                    best, best_np = dist, n_p
+            from fractions import Fraction
+            hit = best is not None and best < Fraction(orc.T) ** 2
+            assert pos[0, h] == (best_np if hit else -1)
+            if best is not None:
+                assert abs(d2[0, h] - float(best)) <= 1e-14 * float(best)
+            else:
+                assert d2[0, h] == np.inf
+
+
+def test_match_window_bounds_and_ties():
+    """Candidates are n_p in [n-W, n-1]; stale and empty entries are ignored; equal distances -> most recent;
+    T = 0 never hits (strict <), even for an identical query; a huge T always hits once the ring is non-empty."""
+    W, Hq, d = 4, 2, 8
+    mk = lambda T: Oracle(num_q_heads=Hq, num_kv_heads=1, head_dim=d, page_size=4, window=W, band=1,
+                          threshold=T, strides=(1, 1, 1, 1), max_slots=1)
+    q = torch.arange(Hq * d, dtype=torch.float32).view(1, Hq, d).to(torch.bfloat16)
+    qb = bf16_bits(q)
+    n = 100
+    # empty ring
+    orc = mk(1e6)
+    pos, _, d2 = orc.match(np.array([0]), np.array([n]), qb)
+    assert np.all(pos == -1) and np.all(np.isinf(d2))
+    # duplicates at n_p = 97 and 99 -> picks 99; a stale copy at n_p = 95 (outside [96, 99]) is ignored
+    for n_p in (97, 99):
+        orc.ring_q[0, (n_p - 1) % W] = qb[0]
+        orc.ring_npos[0, (n_p - 1) % W] = n_p
+    pos, _, d2 = orc.match(np.array([0]), np.array([n]), qb)
+    assert np.all(pos == 99) and np.all(d2 == 0)
+    orc0 = mk(0.0)
+    orc0.ring_q[:] = orc.ring_q
+    orc0.ring_npos[:] = orc.ring_npos
+    pos, _, _ = orc0.match(np.array([0]), np.array([n]), qb)
+    assert np.all(pos == -1)
+    # window edge: entry at n_p = n - W is a candidate, n_p = n - W - 1 is not
+    orc = mk(1e6)
+    orc.ring_q[0, 0] = qb[0]
+    orc.ring_npos[0, 0] = n - W
+    assert np.all(orc.match(np.array([0]), np.array([n]), qb)[0] == n - W)
+    orc.ring_npos[0, 0] = n - W - 1
+    assert np.all(orc.match(np.array([0]), np.array([n]), qb)[0] == -1)
+    orc.ring_npos[0, 0] = n          # an entry "from the future" (n_p > n-1) is not a candidate either
+    assert np.all(orc.match(np.array([0]), np.array([n]), qb)[0] == -1)
+
+
+def test_match_rate_follows_chi_square_null():
+    """App. B.1: under the isotropic Gaussian null ||q_m - q_p||^2 = 2 chi^2_d, so with one candidate the
+    acceptance rate is F_{chi^2_d}(T^2 / 2) = F(d (1 - tau)^2).  Pins '<', the sqrt(2d) scale and that the
+    distance (not its square) is compared with T."""
+    from scipy.stats import chi2
+    d, trials = 32, 4000
+    tau = 0.12
+    T = math.sqrt(2 * d) * (1 - tau)
+    orc = Oracle(num_q_heads=1, num_kv_heads=1, head_dim=d, page_size=4, window=1, band=1,
+                 threshold=T, strides=(1, 1, 1, 1), max_slots=1)
+    rng = np.random.default_rng(7)
+    hits = 0
+    for t in range(trials):
+        a = rng.normal(size=(1, 1, d)).astype(np.float32)
+        b = rng.normal(size=(1, 1, d)).astype(np.float32)
+        orc.ring_q[0, 0] = bf16_bits(torch.from_numpy(b[0]).to(torch.bfloat16))
+        orc.ring_npos[0, 0] = 9
+        pos, _, _ = orc.match(np.array([0]), np.array([10]), bf16_bits(torch.from_numpy(a).to(torch.bfloat16)))
+        hits += int(pos[0, 0] == 9)
+    p = chi2.cdf(d * (1 - tau) ** 2, d)
+    sigma = math.sqrt(p * (1 - p) / trials)
+    assert abs(hits / trials - p) < 4 * sigma + 2e-3, (hits / trials, p)
+
+
+# ----------------------------------------------------------------------------- MAC step
+def _run_mac(cfg: WorkloadConfig, wl: Workload, orc: Oracle):
+    kvp, bt, slots = host_inputs(wl)
+    res = []
+    for q_pre, q_rope, kv_lens in wl:
+        r = orc.mac_step(slots, kv_lens.numpy(), bf16_bits(q_pre), bf16_bits(q_rope), kvp, bt)
+        full, full_lse = orc.full_decode(kv_lens.numpy(), bf16_bits(q_rope), kvp, bt)
+        r["full"], r["full_lse"], r["n"] = full, full_lse, kv_lens.numpy().copy()
+        res.append(r)
+    return res
+
+
+def test_threshold_zero_is_exact_full_attention():
+    """Sec. 3.2.1: with no match the method falls back to full attention; outputs identical to baseline."""
+    cfg = small_cfg(threshold=0.0)
+    wl = Workload(cfg)
+    orc = make_oracle(cfg, wl)
+    for r in _run_mac(cfg, wl, orc):
+        assert np.all(r["match_pos"] == -1)
+        np.testing.assert_allclose(r["out"], r["full"], rtol=1e-12, atol=1e-15)
+        np.testing.assert_allclose(r["lse"], r["full_lse"], rtol=1e-13)
+    assert orc.stats.hits == 0 and orc.stats.kv_tokens_read == orc.stats.kv_tokens_full
+
+
+def test_band_covering_everything_is_exact_full_attention():
+    """B >= n: the reused prefix [0, n_p - B) is empty, so even on hits the output is full attention."""
+    cfg = small_cfg(threshold=1e6, band=1000)
+    wl = Workload(cfg)
+    orc = make_oracle(cfg, wl)
+    res = _run_mac(cfg, wl, orc)
+    assert all(np.all(r["match_pos"] >= 0) for r in res[1:])
+    for r in res:
+        np.testing.assert_allclose(r["out"], r["full"], rtol=1e-12, atol=1e-15)
+
+
+def test_repeated_identical_query_has_zero_reuse_error():
+    """Sec. 3.1: reuse is exact when the logits under Q_m and Q_p agree on the reused prefix.  With RoPE off
+    and the same (q_pre, q_rope) at every step, every step after the first hits and equals full attention."""
+    cfg = small_cfg(use_rope=False, rho=1.0, threshold=0.5, band=2, window=5, steps=17)
+    wl = Workload(cfg)
+    orc = make_oracle(cfg, wl)
+    res = _run_mac(cfg, wl, orc)
+    assert np.all(res[0]["match_pos"] == -1)
+    for i, r in enumerate(res[1:], 1):
+        assert np.all(r["match_pos"] == r["n"][:, None] - 1)          # most recent duplicate
+        assert np.all(r["d2"] == 0)
+        np.testing.assert_allclose(r["out"], r["full"], rtol=1e-11, atol=1e-14)
+    assert orc.stats.hits == (cfg.steps - 1) * cfg.batch * cfg.num_q_heads
+
+
+def test_zero_keys_give_mean_of_values_whatever_is_reused():
+    """All keys zero => every logit is 0 under every query => uniform weights => MAC == full == mean(V) over
+    [0, n), hits included (the reused and the fresh parts then carry weights proportional to their sizes).
+    Keys that are merely equal would not do: the common logit differs between the cached and the current
+    query, which shifts the relative weight of the reused part -- the method's inherent error."""
+    cfg = small_cfg(threshold=1e6)
+    wl = Workload(cfg)
+    wl.kv_pages[:, 0] = 0
+    orc = make_oracle(cfg, wl)
+    res = _run_mac(cfg, wl, orc)
+    assert any(np.any(r["match_pos"] >= 0) for r in res)
+    for r in res:
+        for b in range(cfg.batch):
+            K, V = dense_kv(wl, b, int(r["n"][b]))
+            for h in range(cfg.num_q_heads):
+                np.testing.assert_allclose(r["out"][b, h], V[:, h // cfg.group].mean(0), rtol=1e-11, atol=1e-14)
+
+
+@pytest.mark.parametrize("band,window,threshold", [(3, 4, 3.0), (0, 3, 4.0), (5, 7, 2.2), (1, 1, 6.0)])
+def test_against_literal_definition_with_full_history(band, window, threshold):
+    """The C oracle (ring modulo W, shifted (O, LSE), add-only rectification, paged KV) equals the literal
+    version (all history filtered by n_p in [n-W, n-1], unshifted (S, Z), rectification by subtraction,
+    dense KV, exact rational distances): decisions identical, outputs to rounding.  Runs > 2W steps, so the
+    ring wraps several times (Sec. 4.1), and mixes hits and misses."""
+    cfg = small_cfg(band=band, window=window, threshold=threshold, steps=max(14, 3 * window), rho=0.93)
+    wl = Workload(cfg)
+    orc = make_oracle(cfg, wl)
+    kvp, bt, slots = host_inputs(wl)
+    Kd = [dense_kv(wl, b, cfg.max_kv_len) for b in range(cfg.batch)]
+    lit = [DefinitionMAC(Kd[b][0], Kd[b][1], cfg.num_q_heads, window, band, threshold, orc.sm_scale)
+           for b in range(cfg.batch)]
+    n_hit = n_miss = 0
+    for q_pre, q_rope, kv_lens in wl:
+        r = orc.mac_step(slots, kv_lens.numpy(), bf16_bits(q_pre), bf16_bits(q_rope), kvp, bt)
+        for b in range(cfg.batch):
+            out, pos = lit[b].step(int(kv_lens[b]), q_pre[b].double().numpy(), q_rope[b].double().numpy())
+            np.testing.assert_array_equal(r["match_pos"][b], pos)
+            np.testing.assert_allclose(r["out"][b], out, rtol=1e-10, atol=1e-13)
+            n_hit += int((pos >= 0).sum())
+            n_miss += int((pos < 0).sum())
+    assert n_hit > 0 and n_miss > 0, (n_hit, n_miss)
+
+
+def test_writeback_holds_rectified_summary_of_this_step():
+    """Fig. 1(c) / Sec. 4.2 K3: the entry inserted at length n is prefix (+) fresh[s, n-B) -- checked by
+    recomputing it from the pre-step ring and the exported summary/merge; and it sits in slot (n-1) mod W."""
+    cfg = small_cfg(threshold=3.5, band=3, window=4, steps=12)
+    wl = Workload(cfg)
+    orc = make_oracle(cfg, wl)
+    kvp, bt, slots = host_inputs(wl)
+    for q_pre, q_rope, kv_lens in wl:
+        ring_O, ring_l, ring_n = orc.ring_O.copy(), orc.ring_lse.copy(), orc.ring_npos.copy()
+        r = orc.mac_step(slots, kv_lens.numpy(), bf16_bits(q_pre), bf16_bits(q_rope), kvp, bt)
+        for b in range(cfg.batch):
+            n = int(kv_lens[b])
+            j = (n - 1) % cfg.window
+            assert orc.ring_npos[b, j] == n
+            np.testing.assert_array_equal(orc.ring_q[b, j], bf16_bits(q_pre)[b])
+            for h in range(cfg.num_q_heads):
+                n_p = int(r["match_pos"][b, h])
+                if n_p >= 0:
+                    jj = int(np.where(ring_n[b] == n_p)[0][0])
+                    pre, pre_l, s = ring_O[b, jj, h], ring_l[b, jj, h], max(0, n_p - cfg.band)
+                else:
+                    pre, pre_l, s = np.zeros(cfg.head_dim), -np.inf, 0
+                mid, mid_l = orc.summary(bf16_bits(q_rope), kvp, bt, b, h, s, max(s, n - cfg.band))
+                exp_O, exp_l = Oracle.merge(pre, pre_l, mid, mid_l)
+                np.testing.assert_allclose(orc.ring_O[b, j, h], exp_O, rtol=1e-13, atol=1e-16)
+                assert orc.ring_lse[b, j, h] == pytest.approx(exp_l, rel=1e-13) or (exp_l == -np.inf and orc.ring_lse[b, j, h] == -np.inf)
+
+
+def test_error_falls_as_band_widens():
+    """Sec. 5.2 "Insights" (sanity trend, not a pin): with recency-biased logits the error of reuse falls
+    as the band grows, and vanishes once the band covers the context."""
+    errs = []
+    for band in (0, 4, 16, 64, 400):
+        cfg = small_cfg(batch=1, num_q_heads=2, num_kv_heads=1, context=200, steps=10, window=8, band=band,
+                        threshold=1e6, rho=0.8, head_dim=16, seed=3)
+        wl = Workload(cfg)
+        # recency bias: scale key t by a factor growing with t so late keys carry most mass
+        n_tot = cfg.max_kv_len
+        for t in range(n_tot):
+            page, within = int(wl.block_table[0, t // cfg.page_size]), t % cfg.page_size
+            wl.kv_pages[page, 0, :, within] = (wl.kv_pages[page, 0, :, within].float() * (0.2 + 2.5 * t / n_tot)).to(torch.bfloat16)
+        orc = make_oracle(cfg, wl)
+        res = _run_mac(cfg, wl, orc)
+        errs.append(np.mean([rel_l2(r["out"], r["full"]) for r in res[1:]]))
+    assert errs[-1] < 1e-12
+    assert errs[0] > errs[2] > errs[-1], errs
+    assert errs[1] >= errs[3], errs
+
+
+def test_stats_definitions():
+    """Acceptance rate and skip ratio E[(p - r)_+ / m] with misses as zero (Sec. 5.3), reuse gap, and KV tokens
+    streamed per KV group from the smallest start among its heads (Sec. 5.8) -- recomputed in Python."""
+    cfg = small_cfg(threshold=3.2, steps=20, window=6)
+    wl = Workload(cfg)
+    orc = make_oracle(cfg, wl)
+    kvp, bt, slots = host_inputs(wl)
+    hits = gap = read = full = 0
+    skip = 0.0
+    for q_pre, q_rope, kv_lens in wl:
+        r = orc.mac_step(slots, kv_lens.numpy(), bf16_bits(q_pre), bf16_bits(q_rope), kvp, bt)
+        for b in range(cfg.batch):
+            n = int(kv_lens[b])
+            starts = []
+            for h in range(cfg.num_q_heads):
+                n_p = int(r["match_pos"][b, h])
+                s = max(0, n_p - cfg.band) if n_p >= 0 else 0
+                starts.append(s)
+                if n_p >= 0:
+                    hits += 1
+                    gap += n - n_p
+                    skip += s / n
+            for g in range(cfg.num_kv_heads):
+                read += n - min(starts[g * cfg.group:(g + 1) * cfg.group])
+                full += n
+    st = orc.stats
+    assert (st.steps, st.head_steps) == (cfg.steps, cfg.steps * cfg.batch * cfg.num_q_heads)
+    assert (st.hits, st.misses, st.sum_gap) == (hits, st.head_steps - hits, gap)
+    assert (st.kv_tokens_read, st.kv_tokens_full) == (read, full)
+    assert st.sum_skip_frac == pytest.approx(skip, rel=1e-12)
+    assert 0 < hits < st.head_steps
+
+
+def test_aux_memory_matches_paper_overhead_table():
+    """Sec. 5.9: rings cost about 5 % of the KV cache at K=1024, L=120K and 1.2 / 2.3 / 4.7 / 9.4 % at 128K for
+    K = 256 / 512 / 1024 / 2048 (Llama-3.1-8B geometry).  One ring entry per head = bf16 query (256 B) +
+    fp32 summary row (512 B) + fp32 ln-LSE (4 B) = 772 B; KV = 2 * 8 heads * 128 * 2 B = 4096 B per token."""
+    entry = 128 * 2 + 128 * 4 + 4
+    kv_per_token = 2 * 8 * 128 * 2
+    assert entry == 772
+    assert round(100 * 1024 * 32 * entry / (120 * 1024 * kv_per_token), 1) == 5.0
+    for K, pct in [(256, 1.2), (512, 2.4), (1024, 4.7), (2048, 9.4)]:
+        got = 100 * K * 32 * entry / (128 * 1024 * kv_per_token)
+        assert abs(got - pct) < 0.06, (K, got)     # the paper prints 2.3 for K=512 (its own rounding of 2.36)
