@@ -1,0 +1,147 @@
+/*
+ * mac_attn.h -- C ABI of the MAC-Attention decode-attention operator for AMD MI355X (gfx950).
+ *
+ * One decode step of the operator, per (request, query head) (paper Sec. 3.5, Fig. 1, Sec. 4.2):
+ *   match    : pre-RoPE squared-L2 nearest neighbour of the current query among the last W cached
+ *              queries of the request, accepted iff distance < T (Eq. (accept), Sec. 3.2.3);
+ *   amend    : on a hit at entry n_p, recompute attention over the band and tail [max(0, n_p - B), n)
+ *              under the current post-RoPE query (Eq. (rect-recomp));
+ *   complete : merge it with the cached rectified prefix summary in the log domain (Eq. (rect-merge));
+ *              on a miss run full attention over [0, n) (Sec. 3.2.1: outputs identical to the baseline);
+ *   append   : store the pre-RoPE query and this step's rectified summary (its total without the last B
+ *              keys) into ring slot (n - 1) mod W (Fig. 1(c), Sec. 4.1, Sec. 4.2 "K3").
+ *
+ * Conventions
+ *   - All pointers named "device" are HIP device pointers on the context's GPU; "host" pointers are
+ *     ordinary host memory.  No torch types cross this boundary.
+ *   - n = kv_len of a request INCLUDING the current token: the caller has already appended the current
+ *     token's post-RoPE K and V to the paged cache (the attention sum runs over t <= m, Sec. 2).
+ *   - bf16 tensors are passed as raw 16-bit patterns.
+ *   - Every entry point returns 0 on success or a negative MAC_ATTN_ERR_* code; nothing throws or aborts.
+ *   - mac_attn_decode_step / mac_attn_full_decode only enqueue work on the given stream: no host
+ *     synchronisation, no device-to-host copy.  The library borrows the argument buffers until the stream
+ *     has executed the enqueued work.  One context must not be used from two streams/threads at once.
+ *   - Device-resident values (kv_lens, slot_ids, block_table) cannot be validated by the host; kv_len is
+ *     clamped to [0, max_kv_len] on the device, slot ids and page ids must be in range.
+ */
+#ifndef MAC_ATTN_H
+#define MAC_ATTN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MAC_ATTN_OK               0
+#define MAC_ATTN_ERR_INVALID_ARG (-1)   /* null pointer, out-of-range size, inconsistent geometry        */
+#define MAC_ATTN_ERR_UNSUPPORTED (-2)   /* valid request this build cannot serve (e.g. head_dim != 128) */
+#define MAC_ATTN_ERR_HIP         (-3)   /* a HIP runtime call failed; see mac_attn_last_hip_error        */
+#define MAC_ATTN_ERR_OOM         (-4)   /* device allocation failed                                      */
+
+typedef struct mac_attn_ctx mac_attn_ctx;   /* opaque: owns rings, split-K workspace and counters */
+
+/* Geometry and hyper-parameters, fixed for the life of a context (one context per layer). */
+typedef struct mac_attn_config {
+    int32_t device;        /* HIP device ordinal                                                          */
+    int32_t max_slots;     /* number of per-request ring sets (>= 1)                                      */
+    int32_t max_batch;     /* largest batch of one call (1 .. max_slots)                                  */
+    int32_t num_q_heads;   /* Hq                                                                          */
+    int32_t num_kv_heads;  /* Hkv; Hq % Hkv == 0, group size G = Hq/Hkv in {1..16, 32}                    */
+    int32_t head_dim;      /* must be 128                                                                 */
+    int32_t page_size;     /* tokens per KV page: a multiple of 16                                        */
+    int32_t window;        /* W >= 1 (paper's K), at most 4096                                            */
+    int32_t band;          /* B >= 0 (paper's r)                                                          */
+    float   threshold;     /* T: absolute pre-RoPE L2 distance (paper: sqrt(2d)(1 - tau));
+                              hit iff d^2 < (double)T * (double)T, strict                                 */
+    float   sm_scale;      /* softmax scale, 1/sqrt(head_dim) in the paper; <= 0 selects that default     */
+    int32_t max_kv_len;    /* upper bound of kv_len; sizes the split-K workspace and the launch grids     */
+    int32_t chunk_tokens;  /* tokens per split-K work item: multiple of 32 in [32, 4096]; 0 = default     */
+} mac_attn_config;
+
+/* Arguments of one decode step for a batch of requests. */
+typedef struct mac_attn_step_args {
+    int32_t        batch;              /* host value, 1 .. max_batch                                      */
+    const int32_t* slot_ids;           /* device [batch]: request -> ring set, distinct, in [0, max_slots) */
+    const int32_t* kv_lens;            /* device [batch]: n, including the current token                  */
+    const void*    q_pre;              /* device bf16 [batch, Hq, d]: pre-RoPE query (match + ring);
+                                          ignored by mac_attn_full_decode (may be null there)             */
+    const void*    q_rope;             /* device bf16 [batch, Hq, d]: post-RoPE query (attention)         */
+    const void*    kv_pages;           /* device bf16, caller-owned paged cache holding post-RoPE K and V.
+                                          Element (page p, kv in {0=K,1=V}, kv head g, token r, dim i) is
+                                          at p*stride_page + kv*stride_kv + g*stride_head + r*stride_tok + i */
+    int64_t        stride_page, stride_kv, stride_head, stride_tok;   /* in elements; multiples of 8;
+                                                                          the d elements of a row are contiguous */
+    const int32_t* block_table;        /* device [batch, block_table_stride]: physical page of logical page */
+    int32_t        block_table_stride; /* >= ceil(max_kv_len / page_size)                                 */
+    float*         out;                /* device fp32 [batch, Hq, d]: attention output                    */
+    float*         out_lse;            /* optional device fp32 [batch, Hq]: natural-log LSE of the output */
+    int32_t*       match_pos;          /* optional device [batch, Hq]: matched n_p, or -1 on a miss
+                                          (written by mac_attn_decode_step only)                          */
+    double*        match_d2;           /* optional device [batch, Hq]: nearest squared distance, +inf when
+                                          the window is empty (mac_attn_decode_step only)                 */
+} mac_attn_step_args;
+
+/* Counters since init or the last reset (definitions: Sec. 5.3 "Setup and metrics", Sec. 5.8, App. B.3). */
+typedef struct mac_attn_stats_t {
+    uint64_t steps;            /* calls of mac_attn_decode_step                                            */
+    uint64_t head_steps;       /* sum of batch * Hq over those calls                                       */
+    uint64_t hits, misses;     /* per (request, head) match decisions                                      */
+    uint64_t sum_gap;          /* sum over hits of n - n_p                                                 */
+    uint64_t kv_tokens_read;   /* sum over (request, kv head) of n - min over the group's heads of start   */
+    uint64_t kv_tokens_full;   /* sum over (request, kv head) of n: what full attention would stream       */
+    double   sum_skip_frac;    /* sum over (request, head) of (n_p - B)_+ / n, misses counted as 0         */
+} mac_attn_stats_t;
+
+/* Create a context: allocates the rings (empty), the split-K workspace and the counters on cfg->device.
+ * Sec. 4.1 (per-request rings of capacity W).  *out_ctx is set only on success. */
+int mac_attn_init(const mac_attn_config* cfg /*host*/, mac_attn_ctx** out_ctx /*host*/);
+
+/* One MAC decode step (match -> band+tail or full attention -> merge -> ring append), Sec. 3.5 / Sec. 4.2.
+ * hip_stream is a hipStream_t (null = the default stream). */
+int mac_attn_decode_step(mac_attn_ctx* ctx, const mac_attn_step_args* args /*host*/, void* hip_stream);
+
+/* Plain full decode attention over [0, n) with the same split-K kernels (the miss path, and the baseline
+ * the speed-up is reported against); reads and changes no ring state.  Sec. 2, Sec. 3.2.1. */
+int mac_attn_full_decode(mac_attn_ctx* ctx, const mac_attn_step_args* args /*host*/, void* hip_stream);
+
+/* Wait for the stream last used with ctx, then read the counters into *out; reset != 0 clears them. */
+int mac_attn_stats(mac_attn_ctx* ctx, mac_attn_stats_t* out /*host*/, int reset);
+
+/* Empty the rings of the given ring sets (a new request takes over the slot); null/n <= 0 = all sets.
+ * Synchronous with respect to the stream last used with ctx. */
+int mac_attn_reset(mac_attn_ctx* ctx, const int32_t* slot_ids /*host*/, int32_t n);
+
+/* Test/diagnostic accessor: copy ring entry j (0 <= j < W) of ring set `slot`, head h, to host buffers
+ * (any may be null): q_pre bf16 bits [d], summary row fp32 [d], ln-LSE, and the entry's n_p (0 = empty).
+ * Synchronises the stream last used with ctx. */
+int mac_attn_ring_peek(mac_attn_ctx* ctx, int32_t slot, int32_t j, int32_t h,
+                       uint16_t* q_pre /*host*/, float* summary /*host*/, float* lse /*host*/, int32_t* n_p /*host*/);
+
+/* Bytes of ring state per (ring set, head, entry): bf16 query + fp32 summary row + fp32 ln-LSE
+ * (Sec. 5.9 "Auxiliary HBM overhead").  Pure host arithmetic. */
+int64_t mac_attn_ring_entry_bytes(int32_t head_dim);
+
+/* Device bytes a context with this configuration allocates (rings + workspace + counters), or a negative
+ * error code.  Pure host arithmetic; needs no GPU. */
+int64_t mac_attn_device_bytes(const mac_attn_config* cfg /*host*/);
+
+/* Per-kernel timing with HIP events recorded on the call's own stream.  While enabled, every
+ * decode_step/full_decode call brackets each of its kernels with events.  mac_attn_kernel_us waits for
+ * the stream, adds up the elapsed times of all calls recorded since the previous query into
+ * sum_us[0]=match, [1]=attention, [2]=merge, [3]=write-back (microseconds), stores the number of calls in
+ * *n_calls, and forgets them.  Off by default (the events add a little work to the stream). */
+int mac_attn_set_timing(mac_attn_ctx* ctx, int enable);
+int mac_attn_kernel_us(mac_attn_ctx* ctx, double sum_us[4] /*host*/, int64_t* n_calls /*host*/);
+
+void mac_attn_destroy(mac_attn_ctx* ctx);
+
+/* Static description of an error code; and the text of the last HIP error seen by this library in the
+ * calling thread ("" if none). */
+const char* mac_attn_strerror(int code);
+const char* mac_attn_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MAC_ATTN_H */

@@ -1,0 +1,298 @@
+// Band+tail / full split-K decode attention over a paged bf16 KV cache (gfx950, wave64, MFMA).
+//
+// What it computes (paper Sec. 2 "Notation", Sec. 3.1, Eq. (rect-recomp)): for one KV group (request b,
+// kv head g) and one work item = a token range [lo, hi), for every query head h of the group the attention
+// summary of the keys [max(lo, s_h), hi) under the post-RoPE query:  O = sum_t p_t V_t / sum_t p_t,
+// LSE = ln sum_t e^{scale q.K_t}.  The summaries of all work items are merged by the merge kernel.
+// KV is streamed once per KV group, from the smallest start among the group's heads (Sec. 5.8); heads that
+// start later mask the tokens before their own start.
+//
+// Work items.  The fresh range [gs, n) of a group is cut at n - B (the last-B band, whose summary must stay
+// separate because the stored rectified summary excludes it, Fig. 1(c)) and on a global grid of `chunk`
+// tokens.  blockIdx.x < n_mid_slots : "mid" chunk x  = [x*chunk, (x+1)*chunk) clipped to [gs, n-B)
+// blockIdx.x >= n_mid_slots: "band" chunk k = x - n_mid_slots, chunk index floor((n-B)/chunk) + k,
+//                            clipped to [n-B, n).  Empty work items exit at once.
+//
+// Mapping to the hardware.  A work-group is 4 waves; wave w takes the 32-token tiles w, w+4, ... of the work
+// item and keeps its own online-softmax state; the 4 states are merged through LDS at the end.
+// Per tile and wave, with lane l = (r = l%16, kg = l/16):
+//   S = K Q^T by v_mfma_f32_16x16x32_bf16:  A = K rows (lane: token r of a 16-token sub-tile, 8 contiguous d
+//       elements 32c+8kg.. of k-step c), B = Q^T (lane: head r, same d elements).  Output: lane holds head r,
+//       tokens 4kg+i (i<4) of the sub-tile.  K is loaded from global memory directly in this layout
+//       (16 rows x 64 contiguous bytes per instruction; the four k-steps cover each 256-byte row once).
+//   O += P V by the same MFMA:  A = P (lane: head r, 8 tokens = its own 2x4 scores, so the QK output is
+//       used in place), B = V (lane: 8 d-columns 8r..8r+7 of the same 8 tokens; loaded as 8 rows x 16 bytes,
+//       each quarter-wave reading one full 256-byte row, then transposed in registers with v_perm_b32 into
+//       8 operands, one per column offset j; operand j produces output columns d = 8r + j).
+//   P is fp32 on the VALU (max, exp2, sum) and enters the MFMA as two bf16 terms hi + lo (truncation split,
+//       relative error 2^-16), because a single bf16 P would cost ~1e-3 relative output error.
+// Heads beyond G in the 16-row head tile carry zero queries; their results are never stored.
+#pragma once
+#include "common.hpp"
+
+namespace mac {
+
+struct AttnParams {
+    const int32_t* kv_lens;      // [batch]
+    const int32_t* start;        // [batch*Hq] per-head start s_h (match kernel), or nullptr = all 0 (full decode)
+    const uint16_t* q_rope;      // [batch, Hq, 128] bf16
+    const uint16_t* kv_pages;    // paged cache, bf16
+    int64_t stride_page, stride_kv, stride_head, stride_tok;   // elements
+    const int32_t* block_table;  // [batch, bt_stride]
+    int32_t bt_stride;
+    float* part_O;               // [batch*Hq, n_slots, 128] normalised partial outputs
+    float* part_lse;             // [batch*Hq, n_slots]      natural-log LSE of each partial
+    int32_t Hq, G;
+    int32_t page_shift;          // log2(page_size)
+    int32_t band;                // B; 0 for full decode (no band work items)
+    int32_t chunk;               // tokens per work item, multiple of 32, <= 4096
+    int32_t n_mid_slots, n_slots;
+    int32_t max_kv_len;
+    float scale_log2;            // sm_scale * log2(e)
+};
+
+struct KVTile {
+    u32x4 k[2][4];   // [sub-tile][k-step]  A operands of S = K Q^T
+    u32x4 v[8];      // [e = 4*sub-tile + i] 8 d-columns of token 16*sub + 4kg + i
+};
+
+template <int HT>   // number of 16-head tiles: 1 (G <= 16) or 2 (G <= 32)
+__global__ __launch_bounds__(256, (HT == 1 ? 2 : 1)) void attn_kernel(const AttnParams p) {
+    const int b = blockIdx.z, g = blockIdx.y, x = blockIdx.x;
+    const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
+    const int r16 = l & 15, kg = l >> 4;
+    const int G = p.G;
+    const int n = clampi(p.kv_lens[b], 0, p.max_kv_len);
+    const int nb = n - p.band > 0 ? n - p.band : 0;          // the band is [nb, n)
+    const int hbase = b * p.Hq + g * G;
+
+    // smallest and largest start among the group's heads (wave-uniform scalar loop)
+    int gs = 0, gmax = 0;
+    if (p.start != nullptr) {
+        gs = nb;
+        for (int i = 0; i < G; ++i) {
+            const int s = clampi(p.start[hbase + i], 0, nb);
+            gs = s < gs ? s : gs;
+            gmax = s > gmax ? s : gmax;
+        }
+    }
+    const int C = p.chunk;
+    int lo, hi;
+    if (x < p.n_mid_slots) {
+        lo = max(gs, x * C);
+        hi = min(nb, (x + 1) * C);
+    } else {
+        const int c = nb / C + (x - p.n_mid_slots);
+        lo = max(nb, c * C);
+        hi = min(n, (c + 1) * C);
+    }
+    if (lo >= hi) return;
+    const int maxstart = max(gmax, lo);                       // tiles at or above it need no start mask
+
+    // per-lane head data for each head tile: first token this head attends to, and its query (B operand)
+    int hstart[HT];
+    bf16x8 qreg[HT][4];
+#pragma unroll
+    for (int ht = 0; ht < HT; ++ht) {
+        const int hh = ht * 16 + r16;
+        const bool valid = hh < G;
+        int s = lo;
+        if (valid && p.start != nullptr) s = max(lo, clampi(p.start[hbase + hh], 0, nb));
+        hstart[ht] = s;
+        const uint16_t* qp = p.q_rope + (int64_t)(hbase + (valid ? hh : 0)) * kHeadDim + 8 * kg;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            u32x4 v = *reinterpret_cast<const u32x4*>(qp + 32 * c);
+            if (!valid) v = u32x4{0u, 0u, 0u, 0u};
+            qreg[ht][c] = __builtin_bit_cast(bf16x8, v);
+        }
+    }
+
+    // this wave's tiles: tt_lo + w + 4k, k = 0 .. nk-1
+    const int tt_lo = lo >> 5, tt_hi = (hi - 1) >> 5;
+    const int ntile = tt_hi - tt_lo + 1;
+    const int nk = ntile > w ? (ntile - w + 3) >> 2 : 0;      // <= 32 because chunk <= 4096
+
+    // page ids of all of this wave's 16-token sub-tiles, one per lane: lane i <-> (k = i/2, sub-tile i%2)
+    int mypid = 0;
+    {
+        const int k = l >> 1, u = l & 1;
+        const int tok = (tt_lo + w + 4 * k) * kTileTokens + 16 * u;
+        if (k < nk && tok < n) mypid = p.block_table[(int64_t)b * p.bt_stride + (tok >> p.page_shift)];
+    }
+    const int page_mask = (1 << p.page_shift) - 1;
+    const uint16_t* kv_g = p.kv_pages + (int64_t)g * p.stride_head;
+
+    auto load_tile = [&](int k, KVTile& T) {
+        const int t0 = (tt_lo + w + 4 * k) * kTileTokens;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int tb = t0 + 16 * u;
+            const int pid = __builtin_amdgcn_readlane(mypid, 2 * k + u);
+            if (tb < n) {                                      // wave-uniform
+                const int lim = n - 1 - tb;                    // rows past the end re-read the last valid row
+                const uint16_t* base = kv_g + (int64_t)pid * p.stride_page + (int64_t)(tb & page_mask) * p.stride_tok;
+                const uint16_t* kp = base + (int64_t)min(r16, lim) * p.stride_tok + 8 * kg;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) T.k[u][c] = *reinterpret_cast<const u32x4*>(kp + 32 * c);
+                const uint16_t* vp = base + p.stride_kv + 8 * r16;
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    T.v[4 * u + i] = *reinterpret_cast<const u32x4*>(vp + (int64_t)min(4 * kg + i, lim) * p.stride_tok);
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) T.k[u][c] = u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) T.v[4 * u + i] = u32x4{0u, 0u, 0u, 0u};
+            }
+        }
+    };
+
+    // online-softmax state of this wave: running max (log2 domain), this lane's share of the running sum,
+    // and the unnormalised output: acc[ht][j][i] = O[head ht*16 + 4kg + i][d = 8*r16 + j]
+    float m_run[HT], l_run[HT];
+    f32x4 acc[HT][8];
+#pragma unroll
+    for (int ht = 0; ht < HT; ++ht) {
+        m_run[ht] = -INFINITY;
+        l_run[ht] = 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[ht][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    auto compute_tile = [&](int k, const KVTile& T) {
+        const int t0 = (tt_lo + w + 4 * k) * kTileTokens;
+        const bool need_mask = (t0 < maxstart) || (t0 + kTileTokens > hi);   // wave-uniform
+        u32x4 a_hi[HT], a_lo[HT];
+#pragma unroll
+        for (int ht = 0; ht < HT; ++ht) {
+            float sc[8];
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, T.k[u][c]), qreg[ht][c], s, 0, 0, 0);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) sc[4 * u + i] = s[i] * p.scale_log2;
+            }
+            if (need_mask) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int tok = t0 + 16 * (e >> 2) + 4 * kg + (e & 3);
+                    if (tok < hstart[ht] || tok >= hi) sc[e] = -INFINITY;
+                }
+            }
+            float tmax = sc[0];
+#pragma unroll
+            for (int e = 1; e < 8; ++e) tmax = fmaxf(tmax, sc[e]);
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+            const float m_new = fmaxf(m_run[ht], tmax);
+            const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+            const float alpha = exp2_fast(m_run[ht] - m_safe);
+            float pv[8];
+            float psum = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                pv[e] = exp2_fast(sc[e] - m_safe);
+                psum += pv[e];
+            }
+            l_run[ht] = l_run[ht] * alpha + psum;
+            if (__builtin_amdgcn_ballot_w64(m_new > m_run[ht]) != 0) {     // some head's max moved: rescale O
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float a = __shfl(alpha, 4 * kg + i);             // lane 4kg+i holds head 4kg+i
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) acc[ht][j][i] *= a;
+                }
+            }
+            m_run[ht] = m_new;
+            // P = hi + lo, both bf16 by truncation
+            uint32_t hb[8], lb[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t bits = float_to_bits(pv[e]);
+                hb[e] = bits;
+                lb[e] = float_to_bits(pv[e] - bits_to_float(bits & 0xffff0000u));
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                a_hi[ht][q] = pack_hi16(hb[2 * q], hb[2 * q + 1]);
+                a_lo[ht][q] = pack_hi16(lb[2 * q], lb[2 * q + 1]);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int c = j >> 1;
+            u32x4 bj;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                bj[q] = (j & 1) ? pack_hi16(T.v[2 * q][c], T.v[2 * q + 1][c]) : pack_lo16(T.v[2 * q][c], T.v[2 * q + 1][c]);
+            const bf16x8 bop = __builtin_bit_cast(bf16x8, bj);
+#pragma unroll
+            for (int ht = 0; ht < HT; ++ht) {
+                acc[ht][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a_hi[ht]), bop, acc[ht][j], 0, 0, 0);
+                acc[ht][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a_lo[ht]), bop, acc[ht][j], 0, 0, 0);
+            }
+        }
+    };
+
+    // two-deep software pipeline: the next tile's loads are in flight while the current one is computed
+    KVTile ta, tb;
+    if (nk > 0) load_tile(0, ta);
+    for (int k = 0; k < nk; k += 2) {
+        if (k + 1 < nk) load_tile(k + 1, tb);
+        compute_tile(k, ta);
+        if (k + 1 < nk) {
+            if (k + 2 < nk) load_tile(k + 2, ta);
+            compute_tile(k + 1, tb);
+        }
+    }
+
+    // merge the 4 waves' states through LDS and write the normalised partial of every real head
+    __shared__ float s_O[4][HT * 16][kHeadDim];
+    __shared__ float s_m[4][HT * 16];
+    __shared__ float s_l[4][HT * 16];
+#pragma unroll
+    for (int ht = 0; ht < HT; ++ht) {
+        float lsum = l_run[ht];
+        lsum += __shfl_xor(lsum, 16);
+        lsum += __shfl_xor(lsum, 32);
+        if (kg == 0) {
+            s_m[w][ht * 16 + r16] = m_run[ht];
+            s_l[w][ht * 16 + r16] = lsum;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int head = ht * 16 + 4 * kg + i;
+            if (head < G) {
+                float* dst = &s_O[w][head][8 * r16];
+                *reinterpret_cast<f32x4*>(dst) = f32x4{acc[ht][0][i], acc[ht][1][i], acc[ht][2][i], acc[ht][3][i]};
+                *reinterpret_cast<f32x4*>(dst + 4) = f32x4{acc[ht][4][i], acc[ht][5][i], acc[ht][6][i], acc[ht][7][i]};
+            }
+        }
+    }
+    __syncthreads();
+    for (int idx = tid; idx < G * kHeadDim; idx += 256) {
+        const int h = idx >> 7, dd = idx & (kHeadDim - 1);
+        float M = fmaxf(fmaxf(s_m[0][h], s_m[1][h]), fmaxf(s_m[2][h], s_m[3][h]));
+        float o = 0.f, lse = -INFINITY;
+        if (M != -INFINITY) {
+            float L = 0.f, a = 0.f;
+#pragma unroll
+            for (int ww = 0; ww < 4; ++ww) {
+                const float f = exp2_fast(s_m[ww][h] - M);
+                L += s_l[ww][h] * f;
+                a += s_O[ww][h][dd] * f;
+            }
+            o = a / L;
+            lse = (M + __log2f(L)) * kLn2;
+        }
+        const int64_t slot = (int64_t)(hbase + h) * p.n_slots + x;
+        p.part_O[slot * kHeadDim + dd] = o;
+        if (dd == 0) p.part_lse[slot] = lse;
+    }
+}
+
+}  // namespace mac

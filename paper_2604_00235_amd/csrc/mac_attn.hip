@@ -1,0 +1,522 @@
+// Host side of libmacattn: context, argument validation, kernel launches, counters.  C ABI in include/mac_attn.h.
+#include "../../include/mac_attn.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "attn_kernel.hpp"
+#include "match_kernel.hpp"
+#include "merge_kernel.hpp"
+
+namespace {
+
+thread_local std::string g_last_hip_error;
+
+int hip_fail(hipError_t e, const char* what) {
+    g_last_hip_error = std::string(what) + ": " + hipGetErrorString(e);
+    return e == hipErrorOutOfMemory ? MAC_ATTN_ERR_OOM : MAC_ATTN_ERR_HIP;
+}
+
+#define HIP_TRY(expr)                                        \
+    do {                                                     \
+        hipError_t e_ = (expr);                              \
+        if (e_ != hipSuccess) return hip_fail(e_, #expr);    \
+    } while (0)
+
+constexpr int kDefaultChunk = 1024;
+
+struct Layout {            // derived sizes, pure host arithmetic
+    int G, chunk, n_mid_slots, n_band_slots, n_slots, page_shift;
+    int64_t ring_q_bytes, ring_O_bytes, ring_lse_bytes, ring_npos_bytes;
+    int64_t part_O_bytes, part_lse_bytes, match_bytes, rect_bytes, stats_bytes;
+    int64_t total() const {
+        return ring_q_bytes + ring_O_bytes + ring_lse_bytes + ring_npos_bytes + part_O_bytes + part_lse_bytes +
+               match_bytes + rect_bytes + stats_bytes;
+    }
+};
+
+int validate_config(const mac_attn_config* c, Layout* L) {
+    if (c == nullptr) return MAC_ATTN_ERR_INVALID_ARG;
+    if (c->device < 0 || c->max_slots < 1 || c->max_batch < 1 || c->max_batch > c->max_slots) return MAC_ATTN_ERR_INVALID_ARG;
+    if (c->num_q_heads < 1 || c->num_kv_heads < 1 || c->num_q_heads % c->num_kv_heads != 0) return MAC_ATTN_ERR_INVALID_ARG;
+    if (c->window < 1 || c->band < 0 || c->max_kv_len < 1 || c->page_size < 1) return MAC_ATTN_ERR_INVALID_ARG;
+    if (!(c->threshold >= 0.f) || !std::isfinite(c->sm_scale)) return MAC_ATTN_ERR_INVALID_ARG;   // rejects NaN; +inf T is legal
+    if (c->chunk_tokens < 0) return MAC_ATTN_ERR_INVALID_ARG;
+    if (c->head_dim != mac::kHeadDim) return MAC_ATTN_ERR_UNSUPPORTED;
+    const int G = c->num_q_heads / c->num_kv_heads;
+    if (G > 32) return MAC_ATTN_ERR_UNSUPPORTED;
+    if (c->page_size < 16 || (c->page_size & (c->page_size - 1)) != 0) return MAC_ATTN_ERR_UNSUPPORTED;
+    if (c->window > 4096) return MAC_ATTN_ERR_UNSUPPORTED;
+    const int chunk = c->chunk_tokens == 0 ? kDefaultChunk : c->chunk_tokens;
+    if (chunk % mac::kTileTokens != 0 || chunk < 32 || chunk > 4096) return MAC_ATTN_ERR_INVALID_ARG;
+    if ((int64_t)c->max_batch * c->num_q_heads > (1 << 24)) return MAC_ATTN_ERR_INVALID_ARG;
+    L->G = G;
+    L->chunk = chunk;
+    L->n_mid_slots = (c->max_kv_len + chunk - 1) / chunk;
+    const int band_span = c->band < c->max_kv_len ? c->band : c->max_kv_len;
+    L->n_band_slots = band_span == 0 ? 0 : (band_span + chunk - 1) / chunk + 1;
+    L->n_slots = L->n_mid_slots + L->n_band_slots;
+    int sh = 0;
+    while ((1 << sh) < c->page_size) ++sh;
+    L->page_shift = sh;
+    const int64_t entries = (int64_t)c->max_slots * c->num_q_heads * c->window;
+    const int64_t bh = (int64_t)c->max_batch * c->num_q_heads;
+    L->ring_q_bytes = entries * mac::kHeadDim * 2;
+    L->ring_O_bytes = entries * mac::kHeadDim * 4;
+    L->ring_lse_bytes = entries * 4;
+    L->ring_npos_bytes = (int64_t)c->max_slots * c->window * 4;
+    L->part_O_bytes = bh * L->n_slots * mac::kHeadDim * 4;
+    L->part_lse_bytes = bh * L->n_slots * 4;
+    L->match_bytes = bh * 3 * 4;
+    L->rect_bytes = bh * (mac::kHeadDim + 1) * 4;
+    L->stats_bytes = bh * 3 * 8 + (int64_t)c->max_batch * c->num_kv_heads * 2 * 8;
+    return MAC_ATTN_OK;
+}
+
+struct TimedCall {
+    hipEvent_t ev[5];
+    bool ran[4];
+};
+
+}  // namespace
+
+struct mac_attn_ctx {
+    mac_attn_config cfg;
+    Layout L;
+    float sm_scale;
+    double T2;
+    // rings
+    uint16_t* ring_q = nullptr;
+    float* ring_O = nullptr;
+    float* ring_lse = nullptr;
+    int32_t* ring_npos = nullptr;
+    // per-step scratch
+    float* part_O = nullptr;
+    float* part_lse = nullptr;
+    int32_t* m_np = nullptr;      // [bh] x3: n_p, entry, start
+    float* rect = nullptr;        // [bh*128] rows then [bh] lse
+    // counters
+    unsigned long long* stats = nullptr;
+    uint64_t steps = 0, head_steps = 0;
+    hipStream_t last_stream = nullptr;
+    // timing
+    bool timing = false;
+    std::vector<TimedCall> timed;
+    std::vector<hipEvent_t> event_pool;
+};
+
+namespace {
+
+int ensure_device(const mac_attn_ctx* ctx) {
+    int cur = -1;
+    HIP_TRY(hipGetDevice(&cur));
+    if (cur != ctx->cfg.device) HIP_TRY(hipSetDevice(ctx->cfg.device));
+    return MAC_ATTN_OK;
+}
+
+int validate_args(const mac_attn_ctx* ctx, const mac_attn_step_args* a, bool need_pre) {
+    if (ctx == nullptr || a == nullptr) return MAC_ATTN_ERR_INVALID_ARG;
+    if (a->batch < 1 || a->batch > ctx->cfg.max_batch) return MAC_ATTN_ERR_INVALID_ARG;
+    if (a->kv_lens == nullptr || a->q_rope == nullptr || a->kv_pages == nullptr || a->block_table == nullptr ||
+        a->out == nullptr)
+        return MAC_ATTN_ERR_INVALID_ARG;
+    if (need_pre && (a->q_pre == nullptr || a->slot_ids == nullptr)) return MAC_ATTN_ERR_INVALID_ARG;
+    const int64_t need_pages = ((int64_t)ctx->cfg.max_kv_len + ctx->cfg.page_size - 1) / ctx->cfg.page_size;
+    if (a->block_table_stride < need_pages) return MAC_ATTN_ERR_INVALID_ARG;
+    const int64_t st[4] = {a->stride_page, a->stride_kv, a->stride_head, a->stride_tok};
+    for (int64_t s : st)
+        if (s <= 0 || (s % 8) != 0) return MAC_ATTN_ERR_INVALID_ARG;
+    if (a->stride_tok < mac::kHeadDim) return MAC_ATTN_ERR_INVALID_ARG;
+    // 16-byte vector loads: base pointers must be 16-byte aligned
+    if ((reinterpret_cast<uintptr_t>(a->kv_pages) & 15u) || (reinterpret_cast<uintptr_t>(a->q_rope) & 15u)) return MAC_ATTN_ERR_INVALID_ARG;
+    if (need_pre && (reinterpret_cast<uintptr_t>(a->q_pre) & 15u)) return MAC_ATTN_ERR_INVALID_ARG;
+    return MAC_ATTN_OK;
+}
+
+hipEvent_t take_event(mac_attn_ctx* ctx, int* rc) {
+    if (!ctx->event_pool.empty()) {
+        hipEvent_t e = ctx->event_pool.back();
+        ctx->event_pool.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    hipError_t err = hipEventCreate(&e);
+    if (err != hipSuccess) *rc = hip_fail(err, "hipEventCreate");
+    return e;
+}
+
+struct Timer {          // brackets the kernels of one call with events when timing is on
+    mac_attn_ctx* ctx;
+    hipStream_t stream;
+    TimedCall tc{};
+    bool on;
+    int rc = MAC_ATTN_OK;
+    Timer(mac_attn_ctx* c, hipStream_t s) : ctx(c), stream(s), on(c->timing) {
+        if (!on) return;
+        for (int i = 0; i < 5 && rc == MAC_ATTN_OK; ++i) tc.ev[i] = take_event(ctx, &rc);
+        for (bool& r : tc.ran) r = false;
+        if (rc == MAC_ATTN_OK) mark(0);
+    }
+    void mark(int i) {
+        if (!on || rc != MAC_ATTN_OK) return;
+        hipError_t e = hipEventRecord(tc.ev[i], stream);
+        if (e != hipSuccess) rc = hip_fail(e, "hipEventRecord");
+    }
+    void done(int kernel) {   // kernel 0..3 just launched
+        if (!on) return;
+        tc.ran[kernel] = true;
+        mark(kernel + 1);
+    }
+    void skip(int kernel) {
+        if (!on) return;
+        mark(kernel + 1);
+    }
+    void finish() {
+        if (on && rc == MAC_ATTN_OK) ctx->timed.push_back(tc);
+    }
+};
+
+int launch_attention(mac_attn_ctx* ctx, const mac_attn_step_args* a, bool mac_mode, hipStream_t stream) {
+    const mac_attn_config& c = ctx->cfg;
+    const Layout& L = ctx->L;
+    mac::AttnParams p;
+    p.kv_lens = a->kv_lens;
+    p.start = mac_mode ? ctx->m_np + 2 * (int64_t)c.max_batch * c.num_q_heads : nullptr;
+    p.q_rope = static_cast<const uint16_t*>(a->q_rope);
+    p.kv_pages = static_cast<const uint16_t*>(a->kv_pages);
+    p.stride_page = a->stride_page;
+    p.stride_kv = a->stride_kv;
+    p.stride_head = a->stride_head;
+    p.stride_tok = a->stride_tok;
+    p.block_table = a->block_table;
+    p.bt_stride = a->block_table_stride;
+    p.part_O = ctx->part_O;
+    p.part_lse = ctx->part_lse;
+    p.Hq = c.num_q_heads;
+    p.G = L.G;
+    p.page_shift = L.page_shift;
+    p.band = mac_mode ? c.band : 0;
+    p.chunk = L.chunk;
+    p.n_mid_slots = L.n_mid_slots;
+    p.n_slots = L.n_slots;
+    p.max_kv_len = c.max_kv_len;
+    p.scale_log2 = ctx->sm_scale * mac::kLog2e;
+    const int gx = mac_mode ? L.n_slots : L.n_mid_slots;
+    dim3 grid(gx, c.num_kv_heads, a->batch), block(256);
+    if (L.G <= 16)
+        hipLaunchKernelGGL(mac::attn_kernel<1>, grid, block, 0, stream, p);
+    else
+        hipLaunchKernelGGL(mac::attn_kernel<2>, grid, block, 0, stream, p);
+    HIP_TRY(hipGetLastError());
+    return MAC_ATTN_OK;
+}
+
+int launch_merge(mac_attn_ctx* ctx, const mac_attn_step_args* a, bool mac_mode, hipStream_t stream) {
+    const mac_attn_config& c = ctx->cfg;
+    const Layout& L = ctx->L;
+    const int64_t bh = (int64_t)c.max_batch * c.num_q_heads;
+    mac::MergeParams p;
+    p.kv_lens = a->kv_lens;
+    p.slot_ids = mac_mode ? a->slot_ids : nullptr;
+    p.m_j = mac_mode ? ctx->m_np + bh : nullptr;
+    p.m_start = mac_mode ? ctx->m_np + 2 * bh : nullptr;
+    p.ring_O = ctx->ring_O;
+    p.ring_lse = ctx->ring_lse;
+    p.part_O = ctx->part_O;
+    p.part_lse = ctx->part_lse;
+    p.out = a->out;
+    p.out_lse = a->out_lse;
+    p.rect_O = mac_mode ? ctx->rect : nullptr;
+    p.rect_lse = mac_mode ? ctx->rect + bh * mac::kHeadDim : nullptr;
+    p.st_read = mac_mode ? ctx->stats + 3 * bh : nullptr;
+    p.st_full = mac_mode ? ctx->stats + 3 * bh + (int64_t)c.max_batch * c.num_kv_heads : nullptr;
+    p.Hq = c.num_q_heads;
+    p.G = L.G;
+    p.W = c.window;
+    p.band = mac_mode ? c.band : 0;
+    p.chunk = L.chunk;
+    p.n_mid_slots = L.n_mid_slots;
+    p.n_slots = L.n_slots;
+    p.max_kv_len = c.max_kv_len;
+    dim3 grid(c.num_q_heads, a->batch), block(128);
+    hipLaunchKernelGGL(mac::merge_kernel, grid, block, 0, stream, p);
+    HIP_TRY(hipGetLastError());
+    return MAC_ATTN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* mac_attn_strerror(int code) {
+    switch (code) {
+        case MAC_ATTN_OK: return "ok";
+        case MAC_ATTN_ERR_INVALID_ARG: return "invalid argument";
+        case MAC_ATTN_ERR_UNSUPPORTED: return "unsupported configuration";
+        case MAC_ATTN_ERR_HIP: return "HIP runtime error";
+        case MAC_ATTN_ERR_OOM: return "out of device memory";
+        default: return "unknown error code";
+    }
+}
+
+const char* mac_attn_last_hip_error(void) { return g_last_hip_error.c_str(); }
+
+int64_t mac_attn_ring_entry_bytes(int32_t head_dim) {
+    if (head_dim < 1) return MAC_ATTN_ERR_INVALID_ARG;
+    return (int64_t)head_dim * 2 + (int64_t)head_dim * 4 + 4;
+}
+
+int64_t mac_attn_device_bytes(const mac_attn_config* cfg) {
+    Layout L;
+    const int rc = validate_config(cfg, &L);
+    if (rc != MAC_ATTN_OK) return rc;
+    return L.total();
+}
+
+void mac_attn_destroy(mac_attn_ctx* ctx) {
+    if (ctx == nullptr) return;
+    int cur = -1;
+    if (hipGetDevice(&cur) == hipSuccess && cur != ctx->cfg.device) (void)hipSetDevice(ctx->cfg.device);
+    if (ctx->last_stream != nullptr || ctx->steps > 0) (void)hipStreamSynchronize(ctx->last_stream);
+    void* bufs[] = {ctx->ring_q, ctx->ring_O, ctx->ring_lse, ctx->ring_npos, ctx->part_O, ctx->part_lse,
+                    ctx->m_np, ctx->rect, ctx->stats};
+    for (void* b : bufs)
+        if (b != nullptr) (void)hipFree(b);
+    for (TimedCall& t : ctx->timed)
+        for (hipEvent_t e : t.ev) (void)hipEventDestroy(e);
+    for (hipEvent_t e : ctx->event_pool) (void)hipEventDestroy(e);
+    delete ctx;
+}
+
+int mac_attn_init(const mac_attn_config* cfg, mac_attn_ctx** out_ctx) {
+    if (out_ctx == nullptr) return MAC_ATTN_ERR_INVALID_ARG;
+    Layout L;
+    int rc = validate_config(cfg, &L);
+    if (rc != MAC_ATTN_OK) return rc;
+    int ndev = 0;
+    HIP_TRY(hipGetDeviceCount(&ndev));
+    if (cfg->device >= ndev) return MAC_ATTN_ERR_INVALID_ARG;
+    HIP_TRY(hipSetDevice(cfg->device));
+    mac_attn_ctx* ctx = new (std::nothrow) mac_attn_ctx();
+    if (ctx == nullptr) return MAC_ATTN_ERR_OOM;
+    ctx->cfg = *cfg;
+    ctx->L = L;
+    ctx->sm_scale = cfg->sm_scale > 0.f ? cfg->sm_scale : 1.0f / std::sqrt((float)cfg->head_dim);
+    ctx->T2 = (double)cfg->threshold * (double)cfg->threshold;
+    struct { void** p; int64_t bytes; bool zero; } allocs[] = {
+        {reinterpret_cast<void**>(&ctx->ring_q), L.ring_q_bytes, true},
+        {reinterpret_cast<void**>(&ctx->ring_O), L.ring_O_bytes, true},
+        {reinterpret_cast<void**>(&ctx->ring_lse), L.ring_lse_bytes, true},
+        {reinterpret_cast<void**>(&ctx->ring_npos), L.ring_npos_bytes, true},
+        {reinterpret_cast<void**>(&ctx->part_O), L.part_O_bytes, false},
+        {reinterpret_cast<void**>(&ctx->part_lse), L.part_lse_bytes, false},
+        {reinterpret_cast<void**>(&ctx->m_np), L.match_bytes, true},
+        {reinterpret_cast<void**>(&ctx->rect), L.rect_bytes, true},
+        {reinterpret_cast<void**>(&ctx->stats), L.stats_bytes, true},
+    };
+    for (auto& a : allocs) {
+        hipError_t e = hipMalloc(a.p, (size_t)a.bytes);
+        if (e == hipSuccess && a.zero) e = hipMemset(*a.p, 0, (size_t)a.bytes);
+        if (e != hipSuccess) {
+            rc = hip_fail(e, "hipMalloc/hipMemset");
+            mac_attn_destroy(ctx);
+            return rc;
+        }
+    }
+    hipError_t e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+        rc = hip_fail(e, "hipDeviceSynchronize");
+        mac_attn_destroy(ctx);
+        return rc;
+    }
+    *out_ctx = ctx;
+    return MAC_ATTN_OK;
+}
+
+int mac_attn_full_decode(mac_attn_ctx* ctx, const mac_attn_step_args* args, void* hip_stream) {
+    int rc = validate_args(ctx, args, /*need_pre=*/false);
+    if (rc != MAC_ATTN_OK) return rc;
+    if ((rc = ensure_device(ctx)) != MAC_ATTN_OK) return rc;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    ctx->last_stream = stream;
+    Timer t(ctx, stream);
+    if (t.rc != MAC_ATTN_OK) return t.rc;
+    t.skip(0);
+    if ((rc = launch_attention(ctx, args, false, stream)) != MAC_ATTN_OK) return rc;
+    t.done(1);
+    if ((rc = launch_merge(ctx, args, false, stream)) != MAC_ATTN_OK) return rc;
+    t.done(2);
+    t.skip(3);
+    t.finish();
+    return t.rc;
+}
+
+int mac_attn_decode_step(mac_attn_ctx* ctx, const mac_attn_step_args* args, void* hip_stream) {
+    int rc = validate_args(ctx, args, /*need_pre=*/true);
+    if (rc != MAC_ATTN_OK) return rc;
+    if ((rc = ensure_device(ctx)) != MAC_ATTN_OK) return rc;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    ctx->last_stream = stream;
+    const mac_attn_config& c = ctx->cfg;
+    const int64_t bh = (int64_t)c.max_batch * c.num_q_heads;
+    Timer t(ctx, stream);
+    if (t.rc != MAC_ATTN_OK) return t.rc;
+
+    // 1. match
+    {
+        mac::MatchParams p;
+        p.slot_ids = args->slot_ids;
+        p.kv_lens = args->kv_lens;
+        p.q_pre = static_cast<const uint16_t*>(args->q_pre);
+        p.ring_q = ctx->ring_q;
+        p.ring_npos = ctx->ring_npos;
+        p.m_np = ctx->m_np;
+        p.m_j = ctx->m_np + bh;
+        p.m_start = ctx->m_np + 2 * bh;
+        p.out_match_pos = args->match_pos;
+        p.out_match_d2 = args->match_d2;
+        p.st_hits = ctx->stats;
+        p.st_gap = ctx->stats + bh;
+        p.st_skip = reinterpret_cast<double*>(ctx->stats + 2 * bh);
+        p.Hq = c.num_q_heads;
+        p.W = c.window;
+        p.B = c.band;
+        p.max_kv_len = c.max_kv_len;
+        p.T2 = ctx->T2;
+        dim3 grid(c.num_q_heads, args->batch), block(256);
+        hipLaunchKernelGGL(mac::match_kernel, grid, block, 0, stream, p);
+        HIP_TRY(hipGetLastError());
+        t.done(0);
+    }
+    // 2. band + tail (or full) attention, split-K partials
+    if ((rc = launch_attention(ctx, args, true, stream)) != MAC_ATTN_OK) return rc;
+    t.done(1);
+    // 3. complete: log-domain merge with the reused prefix
+    if ((rc = launch_merge(ctx, args, true, stream)) != MAC_ATTN_OK) return rc;
+    t.done(2);
+    // 4. rectify-append
+    {
+        mac::WritebackParams p;
+        p.kv_lens = args->kv_lens;
+        p.slot_ids = args->slot_ids;
+        p.q_pre = static_cast<const uint16_t*>(args->q_pre);
+        p.rect_O = ctx->rect;
+        p.rect_lse = ctx->rect + bh * mac::kHeadDim;
+        p.ring_q = ctx->ring_q;
+        p.ring_O = ctx->ring_O;
+        p.ring_lse = ctx->ring_lse;
+        p.ring_npos = ctx->ring_npos;
+        p.Hq = c.num_q_heads;
+        p.W = c.window;
+        p.max_kv_len = c.max_kv_len;
+        dim3 grid(c.num_q_heads, args->batch), block(128);
+        hipLaunchKernelGGL(mac::writeback_kernel, grid, block, 0, stream, p);
+        HIP_TRY(hipGetLastError());
+        t.done(3);
+    }
+    t.finish();
+    ctx->steps += 1;
+    ctx->head_steps += (uint64_t)args->batch * c.num_q_heads;
+    return t.rc;
+}
+
+int mac_attn_stats(mac_attn_ctx* ctx, mac_attn_stats_t* out, int reset) {
+    if (ctx == nullptr || out == nullptr) return MAC_ATTN_ERR_INVALID_ARG;
+    int rc = ensure_device(ctx);
+    if (rc != MAC_ATTN_OK) return rc;
+    HIP_TRY(hipStreamSynchronize(ctx->last_stream));
+    const mac_attn_config& c = ctx->cfg;
+    const int64_t bh = (int64_t)c.max_batch * c.num_q_heads, bg = (int64_t)c.max_batch * c.num_kv_heads;
+    std::vector<unsigned long long> host((size_t)(3 * bh + 2 * bg));
+    HIP_TRY(hipMemcpy(host.data(), ctx->stats, (size_t)ctx->L.stats_bytes, hipMemcpyDeviceToHost));
+    mac_attn_stats_t s;
+    std::memset(&s, 0, sizeof(s));
+    s.steps = ctx->steps;
+    s.head_steps = ctx->head_steps;
+    for (int64_t i = 0; i < bh; ++i) {          // fixed order: the double sum is reproducible
+        s.hits += host[(size_t)i];
+        s.sum_gap += host[(size_t)(bh + i)];
+        double f;
+        std::memcpy(&f, &host[(size_t)(2 * bh + i)], 8);
+        s.sum_skip_frac += f;
+    }
+    s.misses = s.head_steps - s.hits;
+    for (int64_t i = 0; i < bg; ++i) {
+        s.kv_tokens_read += host[(size_t)(3 * bh + i)];
+        s.kv_tokens_full += host[(size_t)(3 * bh + bg + i)];
+    }
+    *out = s;
+    if (reset) {
+        HIP_TRY(hipMemset(ctx->stats, 0, (size_t)ctx->L.stats_bytes));
+        ctx->steps = 0;
+        ctx->head_steps = 0;
+    }
+    return MAC_ATTN_OK;
+}
+
+int mac_attn_reset(mac_attn_ctx* ctx, const int32_t* slot_ids, int32_t n) {
+    if (ctx == nullptr) return MAC_ATTN_ERR_INVALID_ARG;
+    int rc = ensure_device(ctx);
+    if (rc != MAC_ATTN_OK) return rc;
+    HIP_TRY(hipStreamSynchronize(ctx->last_stream));
+    const int W = ctx->cfg.window;
+    if (slot_ids == nullptr || n <= 0) {
+        HIP_TRY(hipMemset(ctx->ring_npos, 0, (size_t)ctx->L.ring_npos_bytes));
+    } else {
+        for (int i = 0; i < n; ++i)
+            if (slot_ids[i] < 0 || slot_ids[i] >= ctx->cfg.max_slots) return MAC_ATTN_ERR_INVALID_ARG;
+        for (int i = 0; i < n; ++i) HIP_TRY(hipMemset(ctx->ring_npos + (int64_t)slot_ids[i] * W, 0, (size_t)W * 4));
+    }
+    HIP_TRY(hipDeviceSynchronize());
+    return MAC_ATTN_OK;
+}
+
+int mac_attn_ring_peek(mac_attn_ctx* ctx, int32_t slot, int32_t j, int32_t h, uint16_t* q_pre, float* summary,
+                       float* lse, int32_t* n_p) {
+    if (ctx == nullptr) return MAC_ATTN_ERR_INVALID_ARG;
+    const mac_attn_config& c = ctx->cfg;
+    if (slot < 0 || slot >= c.max_slots || j < 0 || j >= c.window || h < 0 || h >= c.num_q_heads) return MAC_ATTN_ERR_INVALID_ARG;
+    int rc = ensure_device(ctx);
+    if (rc != MAC_ATTN_OK) return rc;
+    HIP_TRY(hipStreamSynchronize(ctx->last_stream));
+    const int64_t e = ((int64_t)slot * c.num_q_heads + h) * c.window + j;
+    if (q_pre) HIP_TRY(hipMemcpy(q_pre, ctx->ring_q + e * mac::kHeadDim, mac::kHeadDim * 2, hipMemcpyDeviceToHost));
+    if (summary) HIP_TRY(hipMemcpy(summary, ctx->ring_O + e * mac::kHeadDim, mac::kHeadDim * 4, hipMemcpyDeviceToHost));
+    if (lse) HIP_TRY(hipMemcpy(lse, ctx->ring_lse + e, 4, hipMemcpyDeviceToHost));
+    if (n_p) HIP_TRY(hipMemcpy(n_p, ctx->ring_npos + (int64_t)slot * c.window + j, 4, hipMemcpyDeviceToHost));
+    return MAC_ATTN_OK;
+}
+
+int mac_attn_set_timing(mac_attn_ctx* ctx, int enable) {
+    if (ctx == nullptr) return MAC_ATTN_ERR_INVALID_ARG;
+    ctx->timing = enable != 0;
+    return MAC_ATTN_OK;
+}
+
+int mac_attn_kernel_us(mac_attn_ctx* ctx, double sum_us[4], int64_t* n_calls) {
+    if (ctx == nullptr || sum_us == nullptr || n_calls == nullptr) return MAC_ATTN_ERR_INVALID_ARG;
+    int rc = ensure_device(ctx);
+    if (rc != MAC_ATTN_OK) return rc;
+    HIP_TRY(hipStreamSynchronize(ctx->last_stream));
+    for (int k = 0; k < 4; ++k) sum_us[k] = 0.0;
+    *n_calls = (int64_t)ctx->timed.size();
+    for (TimedCall& t : ctx->timed) {
+        for (int k = 0; k < 4; ++k) {
+            if (t.ran[k]) {
+                float ms = 0.f;
+                HIP_TRY(hipEventElapsedTime(&ms, t.ev[k], t.ev[k + 1]));
+                sum_us[k] += 1000.0 * ms;
+            }
+        }
+        for (hipEvent_t e : t.ev) ctx->event_pool.push_back(e);
+    }
+    ctx->timed.clear();
+    return MAC_ATTN_OK;
+}
+
+}  // extern "C"

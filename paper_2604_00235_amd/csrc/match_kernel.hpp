@@ -1,0 +1,134 @@
+// Match: pre-RoPE squared-L2 nearest neighbour over the query ring, argmin and threshold (gfx950, wave64).
+//
+// Paper: Eq. (accept) and Sec. 3.2.3 (single streaming pass over the last W queries), Sec. 3.5 step 1,
+// Sec. 4.2 "K1" (at most one reuse point per (request, head), then the threshold).
+// For request b (ring set slot_ids[b]) and query head h, over the ring entries created at lengths
+// n_p in [max(1, n - W), n - 1]:  d2_j = sum_i (q_i - ring_j,i)^2,  j* = argmin (ties -> larger n_p),
+// hit iff d2_j* < T^2.  On a hit the head's fresh range starts at s_h = max(0, n_p - B), else at 0.
+//
+// Arithmetic.  The decision has to agree with an fp64 evaluation of the exact bf16 inputs, so each
+// difference is formed in fp64 (exact) and squared/accumulated with fp64 FMAs; the result is within a few
+// ulp(fp64) of the true real value, so decisions differ from any other fp64 evaluation only for candidates
+// that tie to ~1e-15 relative.  v_fma_f64 is full rate on this chip and the kernel stays bandwidth-bound.
+//
+// Mapping.  One work-group (256 threads) per (head, request).  The head's window is contiguous in the ring
+// ([slot][head][entry][d]).  A quad of 4 lanes owns one 256-byte row per iteration, lane `sub` reading the
+// 16-byte chunks sub, sub+4, sub+8, sub+12, so each load instruction of a wave fetches 16 rows x 64
+// contiguous bytes; the 4 partial sums are combined with two cross-lane adds, the per-lane running
+// (d2, n_p) minimum with a shuffle butterfly and one LDS exchange between the 4 waves.
+#pragma once
+#include "common.hpp"
+
+namespace mac {
+
+struct MatchParams {
+    const int32_t* slot_ids;     // [batch]
+    const int32_t* kv_lens;      // [batch]
+    const uint16_t* q_pre;       // [batch, Hq, 128] bf16
+    const uint16_t* ring_q;      // [slots, Hq, W, 128] bf16
+    const int32_t* ring_npos;    // [slots, W]; 0 = empty entry
+    int32_t* m_np;               // [batch*Hq] matched n_p or -1
+    int32_t* m_j;                // [batch*Hq] matched ring entry or -1
+    int32_t* m_start;            // [batch*Hq] s_h
+    int32_t* out_match_pos;      // optional caller outputs
+    double* out_match_d2;
+    unsigned long long* st_hits; // per (b, h) accumulators, touched only by that (b, h)'s work-group
+    unsigned long long* st_gap;
+    double* st_skip;
+    int32_t Hq, W, B, max_kv_len;
+    double T2;                   // (double)T * (double)T
+};
+
+__device__ __forceinline__ double bf16_lo_to_f64(uint32_t pair) { return (double)bits_to_float(pair << 16); }
+__device__ __forceinline__ double bf16_hi_to_f64(uint32_t pair) { return (double)bits_to_float(pair & 0xffff0000u); }
+
+__device__ __forceinline__ bool better(double d2, int np, double od2, int onp) {
+    return d2 < od2 || (d2 == od2 && np > onp);
+}
+
+__global__ __launch_bounds__(256) void match_kernel(const MatchParams p) {
+    const int h = blockIdx.x, b = blockIdx.y;
+    const int tid = threadIdx.x, quad = tid >> 2, sub = tid & 3;
+    const int bh = b * p.Hq + h;
+    const int n = clampi(p.kv_lens[b], 0, p.max_kv_len);
+    const int64_t slot = p.slot_ids[b];
+    const int W = p.W;
+
+    // this lane's 32 query elements (chunks sub + 4i), widened once
+    double q[32];
+    {
+        const uint16_t* qp = p.q_pre + (int64_t)bh * kHeadDim + 8 * sub;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const u32x4 v = *reinterpret_cast<const u32x4*>(qp + 32 * i);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                q[8 * i + 2 * e] = bf16_lo_to_f64(v[e]);
+                q[8 * i + 2 * e + 1] = bf16_hi_to_f64(v[e]);
+            }
+        }
+    }
+    const uint16_t* ring = p.ring_q + ((slot * p.Hq + h) * W) * (int64_t)kHeadDim + 8 * sub;
+    const int32_t* npos = p.ring_npos + slot * W;
+    const int np_lo = max(1, n - W), np_hi = n - 1;
+
+    double best_d2 = INFINITY;
+    int best_np = -1, best_j = -1;
+    for (int j0 = 0; j0 < W; j0 += 64) {
+        const int j = j0 + quad;
+        const int np = j < W ? npos[j] : 0;
+        const bool valid = np >= np_lo && np <= np_hi;
+        double s0 = 0.0, s1 = 0.0;
+        if (valid) {
+            const uint16_t* rp = ring + (int64_t)j * kHeadDim;
+            u32x4 v[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v[i] = *reinterpret_cast<const u32x4*>(rp + 32 * i);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const double d0 = q[8 * i + 2 * e] - bf16_lo_to_f64(v[i][e]);
+                    const double d1 = q[8 * i + 2 * e + 1] - bf16_hi_to_f64(v[i][e]);
+                    s0 = fma(d0, d0, s0);
+                    s1 = fma(d1, d1, s1);
+                }
+            }
+        }
+        double d2 = s0 + s1;
+        d2 += __shfl_xor(d2, 1);
+        d2 += __shfl_xor(d2, 2);
+        if (valid && better(d2, np, best_d2, best_np)) { best_d2 = d2; best_np = np; best_j = j; }
+    }
+    // wave butterfly over the 16 quads (all 4 lanes of a quad hold the same triple)
+#pragma unroll
+    for (int off = 4; off < 64; off <<= 1) {
+        const double od2 = __shfl_xor(best_d2, off);
+        const int onp = __shfl_xor(best_np, off);
+        const int oj = __shfl_xor(best_j, off);
+        if (better(od2, onp, best_d2, best_np)) { best_d2 = od2; best_np = onp; best_j = oj; }
+    }
+    __shared__ double s_d2[4];
+    __shared__ int s_np[4], s_j[4];
+    if ((tid & 63) == 0) { s_d2[tid >> 6] = best_d2; s_np[tid >> 6] = best_np; s_j[tid >> 6] = best_j; }
+    __syncthreads();
+    if (tid == 0) {
+#pragma unroll
+        for (int w = 1; w < 4; ++w)
+            if (better(s_d2[w], s_np[w], best_d2, best_np)) { best_d2 = s_d2[w]; best_np = s_np[w]; best_j = s_j[w]; }
+        const bool hit = best_np >= 1 && best_d2 < p.T2;
+        const int s = hit ? max(best_np - p.B, 0) : 0;
+        p.m_np[bh] = hit ? best_np : -1;
+        p.m_j[bh] = hit ? best_j : -1;
+        p.m_start[bh] = s;
+        if (p.out_match_pos) p.out_match_pos[bh] = hit ? best_np : -1;
+        if (p.out_match_d2) p.out_match_d2[bh] = best_d2;
+        if (hit) {
+            p.st_hits[bh] += 1ull;
+            p.st_gap[bh] += (unsigned long long)(n - best_np);
+            p.st_skip[bh] += (double)s / (double)n;
+        }
+    }
+}
+
+}  // namespace mac

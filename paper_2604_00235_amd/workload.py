@@ -46,6 +46,7 @@ class WorkloadConfig:
     rope_theta: float = 1.0e4
     regime_shift_every: int = 0     # >0: add a fresh random mean every this many steps
     use_rope: bool = True
+    ragged: int = 0                 # >0: request b is `ragged * b` tokens shorter than request 0
 
     @property
     def group(self) -> int:
@@ -181,13 +182,15 @@ class Workload:
             self._mu = torch.randn(self._x.shape, generator=self._gen, device=self.device, dtype=torch.float32)
         x = self._x + self._mu if cfg.regime_shift_every > 0 else self._x
         n = cfg.context + s + 1
+        kv_lens = torch.full((cfg.batch,), n, device=self.device, dtype=torch.int32)
+        if cfg.ragged > 0:
+            kv_lens = torch.clamp(kv_lens - cfg.ragged * torch.arange(cfg.batch, device=self.device, dtype=torch.int32), min=1)
         q_pre = x.to(torch.bfloat16)
         if cfg.use_rope:
-            pos = torch.full((cfg.batch, cfg.num_q_heads), n - 1, device=self.device)
+            pos = (kv_lens - 1).view(cfg.batch, 1).expand(cfg.batch, cfg.num_q_heads)
             q_rope = _rope(x, pos, cfg.rope_theta).to(torch.bfloat16)
         else:
             q_rope = q_pre.clone()
-        kv_lens = torch.full((cfg.batch,), n, device=self.device, dtype=torch.int32)
         self._step += 1
         return q_pre, q_rope, kv_lens
 

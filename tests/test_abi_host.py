@@ -1,0 +1,100 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the header declares,
+and its pure-host entry points (size arithmetic, argument validation, error strings) behave."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2604_00235_amd import binding as mb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(mb.LIB_PATH):
+        from paper_2604_00235_amd.build import build_library
+        build_library()
+    return mb.load_library()
+
+
+def _cfg(**kw):
+    base = dict(device=0, max_slots=4, max_batch=4, num_q_heads=32, num_kv_heads=8, head_dim=128, page_size=16,
+                window=256, band=128, threshold=2.7, sm_scale=0.0, max_kv_len=131200, chunk_tokens=0)
+    base.update(kw)
+    return mb.mac_attn_config(**base)
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "mac_attn.h")).read()
+    declared = set(re.findall(r"\b(mac_attn_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(mb.EXPORTS), declared ^ set(mb.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_struct_layouts_match_header():
+    """Field order/size of the ctypes mirrors: int32/float fields packed as in the C structs."""
+    assert C.sizeof(mb.mac_attn_config) == 13 * 4
+    assert C.sizeof(mb.mac_attn_stats_t) == 8 * 8
+    a = mb.mac_attn_step_args
+    assert a.stride_page.offset % 8 == 0 and a.block_table_stride.offset == a.block_table.offset + 8
+    assert C.sizeof(a) == 8 + 5 * 8 + 4 * 8 + 8 + 8 + 4 * 8
+
+
+def test_ring_entry_bytes_and_paper_overhead(lib):
+    """Sec. 5.9: about 5 % of the KV cache at K=1024, L=120K; 4.7 % at 128K (32 q heads, 8 KV heads, d=128)."""
+    e = mb.mac_attn_ring_entry_bytes(128)
+    assert e == 772
+    kv_per_token = 2 * 8 * 128 * 2
+    assert round(100 * 1024 * 32 * e / (120 * 1024 * kv_per_token), 1) == 5.0
+    assert round(100 * 1024 * 32 * e / (128 * 1024 * kv_per_token), 1) == 4.7
+
+
+def test_device_bytes_accounts_rings_and_workspace(lib):
+    cfg = _cfg()
+    total = mb.mac_attn_device_bytes(cfg)
+    rings = 4 * 32 * 256 * 772 + 4 * 256 * 4
+    assert total > rings
+    n_slots = (131200 + 1023) // 1024 + (128 + 1023) // 1024 + 1
+    work = 4 * 32 * n_slots * (128 + 1) * 4
+    assert total - rings - work < 200_000          # match results, staging, counters: small
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(head_dim=64), mb.MAC_ATTN_ERR_UNSUPPORTED),
+    (dict(page_size=24), mb.MAC_ATTN_ERR_UNSUPPORTED),
+    (dict(page_size=8), mb.MAC_ATTN_ERR_UNSUPPORTED),
+    (dict(num_q_heads=66, num_kv_heads=1), mb.MAC_ATTN_ERR_UNSUPPORTED),
+    (dict(window=8192), mb.MAC_ATTN_ERR_UNSUPPORTED),
+    (dict(num_q_heads=30), mb.MAC_ATTN_ERR_INVALID_ARG),
+    (dict(window=0), mb.MAC_ATTN_ERR_INVALID_ARG),
+    (dict(band=-1), mb.MAC_ATTN_ERR_INVALID_ARG),
+    (dict(max_batch=5), mb.MAC_ATTN_ERR_INVALID_ARG),
+    (dict(threshold=float("nan")), mb.MAC_ATTN_ERR_INVALID_ARG),
+    (dict(threshold=-1.0), mb.MAC_ATTN_ERR_INVALID_ARG),
+    (dict(chunk_tokens=100), mb.MAC_ATTN_ERR_INVALID_ARG),
+    (dict(chunk_tokens=8192), mb.MAC_ATTN_ERR_INVALID_ARG),
+    (dict(max_kv_len=0), mb.MAC_ATTN_ERR_INVALID_ARG),
+])
+def test_bad_configs_are_rejected_before_any_gpu_call(lib, kw, code):
+    cfg = _cfg(**kw)
+    assert mb.mac_attn_device_bytes(cfg) == code
+    ctx = C.c_void_p()
+    assert lib.mac_attn_init(C.byref(cfg), C.byref(ctx)) == code
+    assert not ctx.value
+
+
+def test_null_arguments_and_error_strings(lib):
+    assert lib.mac_attn_init(None, None) == mb.MAC_ATTN_ERR_INVALID_ARG
+    assert lib.mac_attn_decode_step(None, None, None) == mb.MAC_ATTN_ERR_INVALID_ARG
+    assert lib.mac_attn_full_decode(None, None, None) == mb.MAC_ATTN_ERR_INVALID_ARG
+    assert lib.mac_attn_stats(None, None, 0) == mb.MAC_ATTN_ERR_INVALID_ARG
+    assert lib.mac_attn_reset(None, None, 0) == mb.MAC_ATTN_ERR_INVALID_ARG
+    lib.mac_attn_destroy(None)
+    for code in (0, -1, -2, -3, -4, -99):
+        assert lib.mac_attn_strerror(code)
+    assert lib.mac_attn_strerror(-1) == b"invalid argument"
