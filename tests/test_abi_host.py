@@ -98,3 +98,13 @@ def test_null_arguments_and_error_strings(lib):
     for code in (0, -1, -2, -3, -4, -99):
         assert lib.mac_attn_strerror(code)
     assert lib.mac_attn_strerror(-1) == b"invalid argument"
+
+
+def test_workload_thresholds_match_calibration_file():
+    """C3's thresholds in the workload module are the calibrated quantiles (tests/golden/c3_thresholds.json,
+    written by tests/golden/calibrate_thresholds.py from the oracle's matcher), rounded to 3 digits."""
+    import json
+    from paper_2604_00235_amd.workload import CONFIGS
+    cal = json.load(open(os.path.join(ROOT, "tests", "golden", "c3_thresholds.json")))
+    for name, rec in cal.items():
+        assert abs(CONFIGS[name].threshold - rec["threshold"]) < 0.006, (name, CONFIGS[name].threshold, rec)
