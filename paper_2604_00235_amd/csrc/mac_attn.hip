@@ -243,7 +243,7 @@ int launch_merge(mac_attn_ctx* ctx, const mac_attn_step_args* a, bool mac_mode, 
     p.n_mid_slots = L.n_mid_slots;
     p.n_slots = L.n_slots;
     p.max_kv_len = c.max_kv_len;
-    dim3 grid(c.num_q_heads, a->batch), block(128);
+    dim3 grid(c.num_q_heads, a->batch), block(mac::kMergeThreads);
     hipLaunchKernelGGL(mac::merge_kernel, grid, block, 0, stream, p);
     HIP_TRY(hipGetLastError());
     return MAC_ATTN_OK;
@@ -388,7 +388,7 @@ int mac_attn_decode_step(mac_attn_ctx* ctx, const mac_attn_step_args* args, void
         p.B = c.band;
         p.max_kv_len = c.max_kv_len;
         p.T2 = ctx->T2;
-        dim3 grid(c.num_q_heads, args->batch), block(256);
+        dim3 grid(c.num_q_heads, args->batch), block(mac::kMatchThreads);
         hipLaunchKernelGGL(mac::match_kernel, grid, block, 0, stream, p);
         HIP_TRY(hipGetLastError());
         t.done(0);

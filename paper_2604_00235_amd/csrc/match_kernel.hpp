@@ -11,11 +11,14 @@
 // ulp(fp64) of the true real value, so decisions differ from any other fp64 evaluation only for candidates
 // that tie to ~1e-15 relative.  v_fma_f64 is full rate on this chip and the kernel stays bandwidth-bound.
 //
-// Mapping.  One work-group (256 threads) per (head, request).  The head's window is contiguous in the ring
+// Mapping.  One work-group (1024 threads = 16 waves) per (head, request), so a window of up to 256 entries is
+// scanned in a single pass with every load in flight at once.  The head's window is contiguous in the ring
 // ([slot][head][entry][d]).  A quad of 4 lanes owns one 256-byte row per iteration, lane `sub` reading the
 // 16-byte chunks sub, sub+4, sub+8, sub+12, so each load instruction of a wave fetches 16 rows x 64
-// contiguous bytes; the 4 partial sums are combined with two cross-lane adds, the per-lane running
-// (d2, n_p) minimum with a shuffle butterfly and one LDS exchange between the 4 waves.
+// contiguous bytes.  Rows are loaded without waiting for their n_p tag (the ring memory always exists; an
+// entry outside the window is simply discarded), which removes one dependent memory round trip.  The 4
+// partial sums are combined with two cross-lane adds, the per-lane running (d2, n_p) minimum with a
+// shuffle butterfly and one LDS exchange between the 16 waves.
 #pragma once
 #include "common.hpp"
 
@@ -46,7 +49,10 @@ __device__ __forceinline__ bool better(double d2, int np, double od2, int onp) {
     return d2 < od2 || (d2 == od2 && np > onp);
 }
 
-__global__ __launch_bounds__(256) void match_kernel(const MatchParams p) {
+constexpr int kMatchThreads = 1024;
+constexpr int kMatchRowsPerPass = kMatchThreads / 4;
+
+__global__ __launch_bounds__(kMatchThreads) void match_kernel(const MatchParams p) {
     const int h = blockIdx.x, b = blockIdx.y;
     const int tid = threadIdx.x, quad = tid >> 2, sub = tid & 3;
     const int bh = b * p.Hq + h;
@@ -74,16 +80,17 @@ __global__ __launch_bounds__(256) void match_kernel(const MatchParams p) {
 
     double best_d2 = INFINITY;
     int best_np = -1, best_j = -1;
-    for (int j0 = 0; j0 < W; j0 += 64) {
+    for (int j0 = 0; j0 < W; j0 += kMatchRowsPerPass) {
         const int j = j0 + quad;
-        const int np = j < W ? npos[j] : 0;
-        const bool valid = np >= np_lo && np <= np_hi;
-        double s0 = 0.0, s1 = 0.0;
-        if (valid) {
-            const uint16_t* rp = ring + (int64_t)j * kHeadDim;
-            u32x4 v[4];
+        const int jc = j < W ? j : W - 1;                      // keep the speculative loads inside the ring
+        const int np = npos[jc];
+        const uint16_t* rp = ring + (int64_t)jc * kHeadDim;
+        u32x4 v[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) v[i] = *reinterpret_cast<const u32x4*>(rp + 32 * i);
+        for (int i = 0; i < 4; ++i) v[i] = *reinterpret_cast<const u32x4*>(rp + 32 * i);
+        const bool valid = j < W && np >= np_lo && np <= np_hi;
+        double s0 = 0.0, s1 = 0.0;
+        {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
 #pragma unroll
@@ -108,13 +115,13 @@ __global__ __launch_bounds__(256) void match_kernel(const MatchParams p) {
         const int oj = __shfl_xor(best_j, off);
         if (better(od2, onp, best_d2, best_np)) { best_d2 = od2; best_np = onp; best_j = oj; }
     }
-    __shared__ double s_d2[4];
-    __shared__ int s_np[4], s_j[4];
+    constexpr int kWaves = kMatchThreads / 64;
+    __shared__ double s_d2[kWaves];
+    __shared__ int s_np[kWaves], s_j[kWaves];
     if ((tid & 63) == 0) { s_d2[tid >> 6] = best_d2; s_np[tid >> 6] = best_np; s_j[tid >> 6] = best_j; }
     __syncthreads();
     if (tid == 0) {
-#pragma unroll
-        for (int w = 1; w < 4; ++w)
+        for (int w = 1; w < kWaves; ++w)
             if (better(s_d2[w], s_np[w], best_d2, best_np)) { best_d2 = s_d2[w]; best_np = s_np[w]; best_j = s_j[w]; }
         const bool hit = best_np >= 1 && best_d2 < p.T2;
         const int s = hit ? max(best_np - p.B, 0) : 0;

@@ -5,7 +5,7 @@
 //     rect = prefix (ring summary of the matched entry, on a hit)  (+)  partials of the mid chunks [s_h, n-B)
 //     out  = rect  (+)  partials of the band chunks [n-B, n)
 // where (O_a, L_a) (+) (O_b, L_b) = ((e^{L_a} O_a + e^{L_b} O_b)/(e^{L_a} + e^{L_b}), ln(e^{L_a} + e^{L_b})),
-// evaluated with a running maximum so no exponent overflows; the empty summary is (0, -inf).
+// evaluated relative to the largest LSE so no exponent overflows; the empty summary is (0, -inf).
 // `rect` is this step's total without the last-B band (Fig. 1(c)), built add-only so nothing cancels.
 //
 // Write-back, per (b, h) -- Sec. 4.1, Sec. 4.2 "K3": ring entry (n-1) mod W of the request's ring set gets the
@@ -34,55 +34,112 @@ struct MergeParams {
     int32_t Hq, G, W, band, chunk, n_mid_slots, n_slots, max_kv_len;
 };
 
-struct RunningMerge {
-    float M = -INFINITY, Z = 0.f, acc = 0.f;
-    __device__ __forceinline__ void add(float o, float L) {
-        if (L == -INFINITY) return;                // empty summary: identity
-        const float Mn = fmaxf(M, L);
-        const float a = expf(M - Mn), bw = expf(L - Mn);
-        acc = acc * a + o * bw;
-        Z = Z * a + bw;
-        M = Mn;
-    }
-    __device__ __forceinline__ float value() const { return Z > 0.f ? acc / Z : 0.f; }
-    __device__ __forceinline__ float lse() const { return Z > 0.f ? M + logf(Z) : -INFINITY; }
-};
+// One work-group of 256 threads per (request, head).  Thread (c = tid/32, q = tid%32) accumulates the
+// partials x = first + c, first + c + 8, ... for the four output columns 4q..4q+3; the 8 partial sums are added
+// in a fixed order through LDS, so the result is bitwise reproducible.  Weights are taken relative to the maximum
+// LSE of each part (rect part: prefix + mid chunks; band part), found in a first pass over the LSE scalars.
+constexpr int kMergeThreads = 256;
+constexpr int kMergeLanes = 8;      // chunks summed in parallel
 
-__global__ __launch_bounds__(128) void merge_kernel(const MergeParams p) {
-    const int h = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
+__device__ __forceinline__ float block_max_256(float v, float* s_red) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
+    __syncthreads();                              // s_red may still be read from a previous call
+    if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
+}
+
+__global__ __launch_bounds__(kMergeThreads) void merge_kernel(const MergeParams p) {
+    const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    const int c = tid >> 5, q = tid & 31;
     const int bh = b * p.Hq + h;
     const int n = clampi(p.kv_lens[b], 0, p.max_kv_len);
     const int nb = n - p.band > 0 ? n - p.band : 0;
     const int C = p.chunk;
     const int s = p.m_start ? clampi(p.m_start[bh], 0, nb) : 0;
+    const int64_t pbase = (int64_t)bh * p.n_slots;
 
-    RunningMerge r;
+    // chunks of this head: mid slots [x0, x1) (those with a non-empty part of [s, nb)), band slots [y0, y1)
+    const int x0 = s / C, x1 = (nb + C - 1) / C;
+    const int y0 = p.n_mid_slots, y1 = nb < n ? p.n_mid_slots + ((n + C - 1) / C - nb / C) : p.n_mid_slots;
+    int64_t pre = -1;                                    // ring entry of the reused prefix, if any
     if (p.m_j != nullptr) {
         const int j = p.m_j[bh];
-        if (j >= 0) {
-            const int64_t e = ((int64_t)p.slot_ids[b] * p.Hq + h) * p.W + j;
-            r.add(p.ring_O[e * kHeadDim + d], p.ring_lse[e]);
+        if (j >= 0) pre = ((int64_t)p.slot_ids[b] * p.Hq + h) * p.W + j;
+    }
+
+    __shared__ float s_red[4];
+    __shared__ float s_acc[2][kMergeLanes][kHeadDim];
+    __shared__ float s_z[2][kMergeLanes];
+
+    // pass 1: maxima of the LSE scalars
+    float m_r = -INFINITY, m_b = -INFINITY;
+    for (int x = x0 + tid; x < x1; x += kMergeThreads)
+        if (max(s, x * C) < min(nb, (x + 1) * C)) m_r = fmaxf(m_r, p.part_lse[pbase + x]);
+    if (tid == 0 && pre >= 0) m_r = fmaxf(m_r, p.ring_lse[pre]);
+    for (int y = y0 + tid; y < y1; y += kMergeThreads) m_b = fmaxf(m_b, p.part_lse[pbase + y]);
+    const float M_r = block_max_256(m_r, s_red);
+    const float M_b = block_max_256(m_b, s_red);
+
+    // pass 2: weighted sums; empty summaries (LSE = -inf) get weight 0
+    f32x4 a_r = f32x4{0.f, 0.f, 0.f, 0.f}, a_b = f32x4{0.f, 0.f, 0.f, 0.f};
+    float z_r = 0.f, z_b = 0.f;
+    if (M_r != -INFINITY) {
+        if (c == 0 && pre >= 0) {
+            const float wgt = expf(p.ring_lse[pre] - M_r);
+            const f32x4 o = *reinterpret_cast<const f32x4*>(p.ring_O + pre * kHeadDim + 4 * q);
+            a_r += o * wgt;
+            z_r += wgt;
+        }
+        for (int x = x0 + c; x < x1; x += kMergeLanes) {
+            if (max(s, x * C) >= min(nb, (x + 1) * C)) continue;      // nothing of this head in the chunk
+            const float wgt = expf(p.part_lse[pbase + x] - M_r);
+            const f32x4 o = *reinterpret_cast<const f32x4*>(p.part_O + (pbase + x) * kHeadDim + 4 * q);
+            a_r += o * wgt;
+            z_r += wgt;
         }
     }
-    const int64_t pbase = (int64_t)bh * p.n_slots;
-    for (int x = s / C; x * C < nb; ++x) {
-        if (max(s, x * C) >= min(nb, (x + 1) * C)) continue;     // nothing of this head in the chunk
-        r.add(p.part_O[(pbase + x) * kHeadDim + d], p.part_lse[pbase + x]);
+    if (M_b != -INFINITY) {
+        for (int y = y0 + c; y < y1; y += kMergeLanes) {
+            const float wgt = expf(p.part_lse[pbase + y] - M_b);
+            const f32x4 o = *reinterpret_cast<const f32x4*>(p.part_O + (pbase + y) * kHeadDim + 4 * q);
+            a_b += o * wgt;
+            z_b += wgt;
+        }
     }
-    if (p.rect_O != nullptr) {
-        p.rect_O[(int64_t)bh * kHeadDim + d] = r.value();
-        if (d == 0) p.rect_lse[bh] = r.lse();
+    *reinterpret_cast<f32x4*>(&s_acc[0][c][4 * q]) = a_r;
+    *reinterpret_cast<f32x4*>(&s_acc[1][c][4 * q]) = a_b;
+    if (q == 0) { s_z[0][c] = z_r; s_z[1][c] = z_b; }
+    __syncthreads();
+    if (tid < kHeadDim) {
+        const int d = tid;
+        float S_r = 0.f, Z_r = 0.f, S_b = 0.f, Z_b = 0.f;
+#pragma unroll
+        for (int k = 0; k < kMergeLanes; ++k) {
+            S_r += s_acc[0][k][d]; Z_r += s_z[0][k];
+            S_b += s_acc[1][k][d]; Z_b += s_z[1][k];
+        }
+        // rect = prefix (+) mid chunks: this step's total without the last-B band
+        if (p.rect_O != nullptr) {
+            p.rect_O[(int64_t)bh * kHeadDim + d] = Z_r > 0.f ? S_r / Z_r : 0.f;
+            if (d == 0) p.rect_lse[bh] = Z_r > 0.f ? M_r + logf(Z_r) : -INFINITY;
+        }
+        // out = rect (+) band
+        const float M_o = fmaxf(M_r, M_b);
+        float o = 0.f, lse = -INFINITY;
+        if (M_o != -INFINITY) {
+            const float fr = expf(M_r - M_o), fb = expf(M_b - M_o);     // exp(-inf) = 0 for an empty part
+            const float Z = fr * Z_r + fb * Z_b;
+            o = (fr * S_r + fb * S_b) / Z;
+            lse = M_o + logf(Z);
+        }
+        p.out[(int64_t)bh * kHeadDim + d] = o;
+        if (d == 0 && p.out_lse != nullptr) p.out_lse[bh] = lse;
     }
-    const int cb = nb / C;
-    for (int k = 0; (cb + k) * C < n && nb < n; ++k) {
-        const int x = p.n_mid_slots + k;
-        r.add(p.part_O[(pbase + x) * kHeadDim + d], p.part_lse[pbase + x]);
-    }
-    p.out[(int64_t)bh * kHeadDim + d] = r.value();
-    if (d == 0 && p.out_lse != nullptr) p.out_lse[bh] = r.lse();
 
     // KV tokens streamed by this step for the KV group (read once per group from its smallest start)
-    if (p.st_read != nullptr && d == 0 && (h % p.G) == 0) {
+    if (p.st_read != nullptr && tid == 0 && (h % p.G) == 0) {
         int gs = nb;
         for (int i = 0; i < p.G; ++i) gs = min(gs, clampi(p.m_start[bh + i], 0, nb));
         const int bg = bh / p.G;
