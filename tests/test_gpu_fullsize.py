@@ -1,0 +1,123 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times (default chunking).
+
+The oracle cannot run every head of these configs in seconds, so:
+  * hit/miss decisions and matched positions of EVERY (request, head) at every step are compared bit-exactly
+    with the oracle's matcher (cheap: it only needs the query rings);
+  * outputs are compared on sampled KV groups: heads are independent, so the oracle is run on one (request,
+    KV group) at a time with that group's rings only (all steps from the empty ring, hits and misses alike);
+  * full decode is compared on sampled heads;
+  * properties that hold at any size are checked on all heads: counters add up, LSE of MAC equals LSE of full
+    attention on misses, outputs finite.
+"""
+from __future__ import annotations
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2604_00235_amd.workload import CONFIGS, Workload, WorkloadConfig, bf16_bits, scaled
+
+pytestmark = pytest.mark.gpu
+
+
+def _group_oracle(cfg: WorkloadConfig, kvp_g: np.ndarray):
+    from oracle.mac_oracle import Oracle
+    ps, d = cfg.page_size, cfg.head_dim
+    return Oracle(num_q_heads=cfg.group, num_kv_heads=1, head_dim=d, page_size=ps, window=cfg.window,
+                  band=cfg.band, threshold=cfg.threshold, strides=(2 * ps * d, ps * d, ps * d, d), max_slots=1)
+
+
+def run_fullsize(cfg: WorkloadConfig, steps: int, groups, full_heads):
+    from oracle.mac_oracle import Oracle
+    from tests.gpu_harness import GpuRun, check_rows, say
+    say(f"[fullsize] {cfg.name}: batch={cfg.batch} Hq/Hkv={cfg.num_q_heads}/{cfg.num_kv_heads} context={cfg.context} "
+        f"steps={steps} W={cfg.window} B={cfg.band} T={cfg.threshold:.4g} groups={groups}")
+    cfg = scaled(cfg, steps=steps)
+    wl = Workload(cfg, device="cuda:0")
+    run = GpuRun(cfg, wl)                       # default chunk_tokens, as bench.py
+    kvp = bf16_bits(wl.kv_pages)
+    bt = wl.block_table.cpu().numpy()
+    slots = wl.slot_ids.cpu().numpy()
+    G = cfg.group
+    # matcher-only oracle for all heads (rings of queries only)
+    morc = Oracle(num_q_heads=cfg.num_q_heads, num_kv_heads=cfg.num_kv_heads, head_dim=cfg.head_dim,
+                  page_size=cfg.page_size, window=cfg.window, band=cfg.band, threshold=cfg.threshold,
+                  strides=wl.strides, max_slots=cfg.batch)
+    # full oracles for the sampled groups
+    gorc = {}
+    for (b, g) in groups:
+        kv_g = np.ascontiguousarray(kvp[:, :, g:g + 1])
+        gorc[(b, g)] = (_group_oracle(cfg, kv_g), kv_g, bt[b:b + 1].copy())
+    worst = 0.0
+    hits = 0
+    for s, (q_pre, q_rope, kv_lens) in enumerate(wl):
+        lens = kv_lens.cpu().numpy()
+        qp, qr = bf16_bits(q_pre), bf16_bits(q_rope)
+        # full decode on sampled heads
+        if s % 4 == 0:
+            f_out, f_lse = run.full(q_rope, kv_lens)
+            assert np.isfinite(f_out).all()
+            for (b, h) in full_heads:
+                o, l = morc.summary(qr, kvp, bt, b, h, 0, int(lens[b]))
+                check_rows(f_out[b, h][None], o[None], f"{cfg.name} step {s} full_decode b{b} h{h}")
+                assert abs(f_lse[b, h] - l) < 1e-3
+        g_out, g_lse, g_pos, g_d2 = run.mac_step(q_pre, q_rope, kv_lens)
+        assert np.isfinite(g_out).all()
+        # decisions of every head
+        o_pos, _, o_d2 = morc.match(slots, lens, qp)
+        assert np.array_equal(g_pos, o_pos), f"{cfg.name} step {s}: decisions differ at {np.argwhere(g_pos != o_pos)[:4].tolist()}"
+        fin = np.isfinite(o_d2)
+        assert np.array_equal(np.isfinite(g_d2), fin) and np.allclose(g_d2[fin], o_d2[fin], rtol=1e-13, atol=0)
+        for b in range(cfg.batch):                   # ring insert of the matcher-only oracle (plumbing)
+            j = (int(lens[b]) - 1) % cfg.window
+            morc.ring_q[slots[b], j] = qp[b]
+            morc.ring_npos[slots[b], j] = lens[b]
+        hits += int((g_pos >= 0).sum())
+        # on a miss the MAC output is full attention: its LSE equals the full-decode LSE of the same step
+        if s % 4 == 0:
+            miss = g_pos < 0
+            assert np.abs(g_lse[miss] - f_lse[miss]).max(initial=0.0) < 1e-4
+        # outputs of the sampled groups
+        for (b, g), (orc, kv_g, bt_b) in gorc.items():
+            hs = slice(g * G, (g + 1) * G)
+            ref = orc.mac_step(np.zeros(1, np.int32), lens[b:b + 1], qp[b:b + 1, hs], qr[b:b + 1, hs], kv_g, bt_b)
+            assert np.array_equal(ref["match_pos"][0], g_pos[b, hs])
+            a, r = check_rows(g_out[b, hs], ref["out"][0], f"{cfg.name} step {s} decode_step b{b} g{g}")
+            assert np.abs(g_lse[b, hs] - ref["lse"][0]).max() < 1e-3
+            worst = max(worst, r)
+    st = run.mac.stats()
+    assert st["steps"] == steps and st["head_steps"] == steps * cfg.batch * cfg.num_q_heads
+    assert st["hits"] == hits and st["hits"] + st["misses"] == st["head_steps"]
+    assert st["kv_tokens_full"] == cfg.num_kv_heads * sum(
+        int(x) for s_ in range(steps) for x in np.maximum(cfg.context + s_ + 1 - cfg.ragged * np.arange(cfg.batch), 1))
+    assert st["kv_tokens_read"] <= st["kv_tokens_full"]
+    run.mac.close()
+    say(f"[fullsize] ok: hits {hits}/{st['head_steps']}, worst rel-L2 {worst:.2e}, "
+        f"kv read {st['kv_tokens_read']}/{st['kv_tokens_full']}")
+    return hits, st
+
+
+def test_c2_llama_32k_full_size():
+    hits, st = run_fullsize(CONFIGS["C2"], steps=12, groups=[(0, 0), (7, 5)], full_heads=[(3, 17)])
+    assert hits == st["head_steps"] - 8 * 32          # every step after the first hits
+
+
+@pytest.mark.parametrize("name", ["C3_rho97", "C3_rho99"])
+def test_c3_long_context_128k_full_size(name):
+    hits, st = run_fullsize(CONFIGS[name], steps=10, groups=[(1, 2), (3, 7)], full_heads=[(2, 9)])
+    assert 0 < hits < st["head_steps"]
+
+
+def test_c4_mqa_64k_full_size_all_miss_and_matched():
+    hits, st = run_fullsize(CONFIGS["C4_miss"], steps=3, groups=[(5, 0)], full_heads=[(11, 30)])
+    assert hits == 0 and st["kv_tokens_read"] == st["kv_tokens_full"]
+    hits, st = run_fullsize(CONFIGS["C4_hit"], steps=8, groups=[(9, 0)], full_heads=[(0, 1)])
+    assert hits == st["head_steps"] - 16 * 32
+
+
+def test_c5_continuous_generation_full_batch():
+    """C5 geometry and batch as stated (32 x 64/8 heads, prompt 8192); the 16384-step run is cut to 40 steps with
+    the regime shift brought forward to every 16 steps so that it is exercised."""
+    cfg = scaled(CONFIGS["C5"], regime_shift_every=16)
+    hits, st = run_fullsize(cfg, steps=40, groups=[(0, 0), (31, 7)], full_heads=[(16, 33)])
+    assert 0 < hits < st["head_steps"]
