@@ -56,7 +56,10 @@ typedef struct mac_attn_config {
                               hit iff d^2 < (double)T * (double)T, strict                                 */
     float   sm_scale;      /* softmax scale, 1/sqrt(head_dim) in the paper; <= 0 selects that default     */
     int32_t max_kv_len;    /* upper bound of kv_len; sizes the split-K workspace and the launch grids     */
-    int32_t chunk_tokens;  /* tokens per split-K work item: multiple of 32 in [32, 4096]; 0 = default     */
+    int32_t chunk_tokens;  /* tokens per split-K work item: multiple of 32 in [32, 4096]; 0 = chosen from
+                              max_batch * Hkv * max_kv_len so that a full-length step has ~2000 work items */
+    int32_t fuse_epilogue; /* 1: the merge kernel also appends to the ring (decode_step = 3 launches);
+                              0: write-back runs as a kernel of its own (4 launches)                      */
 } mac_attn_config;
 
 /* Arguments of one decode step for a batch of requests. */

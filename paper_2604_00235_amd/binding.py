@@ -32,7 +32,7 @@ class mac_attn_config(C.Structure):
         ("num_q_heads", C.c_int32), ("num_kv_heads", C.c_int32), ("head_dim", C.c_int32),
         ("page_size", C.c_int32), ("window", C.c_int32), ("band", C.c_int32),
         ("threshold", C.c_float), ("sm_scale", C.c_float),
-        ("max_kv_len", C.c_int32), ("chunk_tokens", C.c_int32),
+        ("max_kv_len", C.c_int32), ("chunk_tokens", C.c_int32), ("fuse_epilogue", C.c_int32),
     ]
 
 
@@ -189,9 +189,11 @@ class MacAttention:
 
     def __init__(self, *, num_q_heads: int, num_kv_heads: int, window: int, band: int, threshold: float,
                  max_kv_len: int, max_slots: int, max_batch: Optional[int] = None, head_dim: int = 128,
-                 page_size: int = 16, sm_scale: float = 0.0, chunk_tokens: int = 0, device: int = 0):
+                 page_size: int = 16, sm_scale: float = 0.0, chunk_tokens: int = 0, fuse_epilogue: bool = True,
+                 device: int = 0):
         self.cfg = mac_attn_config(device, max_slots, max_batch or max_slots, num_q_heads, num_kv_heads, head_dim,
-                                   page_size, window, band, threshold, sm_scale, max_kv_len, chunk_tokens)
+                                   page_size, window, band, threshold, sm_scale, max_kv_len, chunk_tokens,
+                                   int(fuse_epilogue))
         self.ctx = mac_attn_init(self.cfg)
 
     def make_args(self, *, kv_lens, q_rope, kv_pages, strides, block_table, out, slot_ids=None, q_pre=None,

@@ -13,8 +13,9 @@
 // blockIdx.x >= n_mid_slots: "band" chunk k = x - n_mid_slots, chunk index floor((n-B)/chunk) + k,
 //                            clipped to [n-B, n).  Empty work items exit at once.
 //
-// Mapping to the hardware.  A work-group is 4 waves; wave w takes the 32-token tiles w, w+4, ... of the work
-// item and keeps its own online-softmax state; the 4 states are merged through LDS at the end.
+// Mapping to the hardware.  A work-group is 4 waves; wave w takes the 32-token tiles w, w+4, ... of the chunk
+// (those that intersect the work item) and keeps its own online-softmax state; the 4 states are merged
+// through LDS at the end.
 // Per tile and wave, with lane l = (r = l%16, kg = l/16):
 //   S = K Q^T by v_mfma_f32_16x16x32_bf16:  A = K rows (lane: token r of a 16-token sub-tile, 8 contiguous d
 //       elements 32c+8kg.. of k-step c), B = Q^T (lane: head r, same d elements).  Output: lane holds head r,
@@ -62,6 +63,24 @@ __global__ __launch_bounds__(256, (HT == 1 ? 2 : 1)) void attn_kernel(const Attn
     const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
     const int r16 = l & 15, kg = l >> 4;
     const int G = p.G;
+    const int C = p.chunk;
+    const int tiles_per_chunk = C >> 5;
+    const bool is_mid = x < p.n_mid_slots;
+
+    // Page ids of this wave's 16-token sub-tiles, one per lane: lane i <-> (k = i/2, sub-tile i%2), where the
+    // wave's k-th tile of the chunk is chunk_tile0 + w + 4k.  For a mid chunk the chunk's position follows from
+    // blockIdx alone, so the ids are requested before kv_lens arrives (one dependent memory round trip less);
+    // entries at or past the end of the request (possibly uninitialised) are discarded below.
+    const int pk = l >> 1, pu = l & 1;
+    int chunk_tile0 = x * tiles_per_chunk;
+    int mypid = 0;
+    auto fetch_pid = [&]() {
+        const int tok = (chunk_tile0 + w + 4 * pk) * kTileTokens + 16 * pu;
+        if (w + 4 * pk < tiles_per_chunk)
+            mypid = p.block_table[(int64_t)b * p.bt_stride + min(tok >> p.page_shift, p.bt_stride - 1)];
+    };
+    if (is_mid) fetch_pid();
+
     const int n = clampi(p.kv_lens[b], 0, p.max_kv_len);
     const int nb = n - p.band > 0 ? n - p.band : 0;          // the band is [nb, n)
     const int hbase = b * p.Hq + g * G;
@@ -76,17 +95,18 @@ __global__ __launch_bounds__(256, (HT == 1 ? 2 : 1)) void attn_kernel(const Attn
             gmax = s > gmax ? s : gmax;
         }
     }
-    const int C = p.chunk;
     int lo, hi;
-    if (x < p.n_mid_slots) {
+    if (is_mid) {
         lo = max(gs, x * C);
         hi = min(nb, (x + 1) * C);
     } else {
         const int c = nb / C + (x - p.n_mid_slots);
+        chunk_tile0 = c * tiles_per_chunk;
         lo = max(nb, c * C);
         hi = min(n, (c + 1) * C);
     }
     if (lo >= hi) return;
+    if (!is_mid) fetch_pid();
     const int maxstart = max(gmax, lo);                       // tiles at or above it need no start mask
 
     // per-lane head data for each head tile: first token this head attends to, and its query (B operand)
@@ -108,43 +128,35 @@ __global__ __launch_bounds__(256, (HT == 1 ? 2 : 1)) void attn_kernel(const Attn
         }
     }
 
-    // this wave's tiles: tt_lo + w + 4k, k = 0 .. nk-1
+    // this wave's tiles of the chunk that intersect [lo, hi): k = k_first .. k_last
     const int tt_lo = lo >> 5, tt_hi = (hi - 1) >> 5;
-    const int ntile = tt_hi - tt_lo + 1;
-    const int nk = ntile > w ? (ntile - w + 3) >> 2 : 0;      // <= 32 because chunk <= 4096
-
-    // page ids of all of this wave's 16-token sub-tiles, one per lane: lane i <-> (k = i/2, sub-tile i%2)
-    int mypid = 0;
-    {
-        const int k = l >> 1, u = l & 1;
-        const int tok = (tt_lo + w + 4 * k) * kTileTokens + 16 * u;
-        if (k < nk && tok < n) mypid = p.block_table[(int64_t)b * p.bt_stride + (tok >> p.page_shift)];
-    }
+    const int d_lo = tt_lo - chunk_tile0 - w, d_hi = tt_hi - chunk_tile0 - w;
+    const int k_first = d_lo > 0 ? (d_lo + 3) >> 2 : 0;
+    const int k_end = d_hi >= 0 ? (d_hi >> 2) + 1 : 0;        // one past the last; <= 32 because chunk <= 4096
+    // a sub-tile wholly past the end reads page 0 (always allocated) instead of an unknown table entry
+    if ((chunk_tile0 + w + 4 * pk) * kTileTokens + 16 * pu >= n) mypid = 0;
     const int page_mask = (1 << p.page_shift) - 1;
     const uint16_t* kv_g = p.kv_pages + (int64_t)g * p.stride_head;
 
+    // All 16 loads of a tile are issued unconditionally (rows past the end re-read the last valid row, whose
+    // scores are masked): with a fixed number of loads per tile the compiler can wait for exactly the older
+    // tile's loads and leave the prefetched tile in flight.
     auto load_tile = [&](int k, KVTile& T) {
-        const int t0 = (tt_lo + w + 4 * k) * kTileTokens;
+        const int t0 = (chunk_tile0 + w + 4 * k) * kTileTokens;
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
-            const int tb = t0 + 16 * u;
+            const bool past = t0 + 16 * u >= n;
+            const int tb = past ? 0 : t0 + 16 * u;
+            const int lim = past ? 15 : n - 1 - tb;
             const int pid = __builtin_amdgcn_readlane(mypid, 2 * k + u);
-            if (tb < n) {                                      // wave-uniform
-                const int lim = n - 1 - tb;                    // rows past the end re-read the last valid row
-                const uint16_t* base = kv_g + (int64_t)pid * p.stride_page + (int64_t)(tb & page_mask) * p.stride_tok;
-                const uint16_t* kp = base + (int64_t)min(r16, lim) * p.stride_tok + 8 * kg;
+            const uint16_t* base = kv_g + (int64_t)pid * p.stride_page + (int64_t)(tb & page_mask) * p.stride_tok;
+            const uint16_t* kp = base + (int64_t)min(r16, lim) * p.stride_tok + 8 * kg;
 #pragma unroll
-                for (int c = 0; c < 4; ++c) T.k[u][c] = *reinterpret_cast<const u32x4*>(kp + 32 * c);
-                const uint16_t* vp = base + p.stride_kv + 8 * r16;
+            for (int c = 0; c < 4; ++c) T.k[u][c] = *reinterpret_cast<const u32x4*>(kp + 32 * c);
+            const uint16_t* vp = base + p.stride_kv + 8 * r16;
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    T.v[4 * u + i] = *reinterpret_cast<const u32x4*>(vp + (int64_t)min(4 * kg + i, lim) * p.stride_tok);
-            } else {
-#pragma unroll
-                for (int c = 0; c < 4; ++c) T.k[u][c] = u32x4{0u, 0u, 0u, 0u};
-#pragma unroll
-                for (int i = 0; i < 4; ++i) T.v[4 * u + i] = u32x4{0u, 0u, 0u, 0u};
-            }
+            for (int i = 0; i < 4; ++i)
+                T.v[4 * u + i] = *reinterpret_cast<const u32x4*>(vp + (int64_t)min(4 * kg + i, lim) * p.stride_tok);
         }
     };
 
@@ -161,7 +173,7 @@ __global__ __launch_bounds__(256, (HT == 1 ? 2 : 1)) void attn_kernel(const Attn
     }
 
     auto compute_tile = [&](int k, const KVTile& T) {
-        const int t0 = (tt_lo + w + 4 * k) * kTileTokens;
+        const int t0 = (chunk_tile0 + w + 4 * k) * kTileTokens;
         const bool need_mask = (t0 < maxstart) || (t0 + kTileTokens > hi);   // wave-uniform
         u32x4 a_hi[HT], a_lo[HT];
 #pragma unroll
@@ -238,16 +250,23 @@ __global__ __launch_bounds__(256, (HT == 1 ? 2 : 1)) void attn_kernel(const Attn
         }
     };
 
-    // two-deep software pipeline: the next tile's loads are in flight while the current one is computed
+    // two-deep software pipeline: the next tile's loads are in flight while the current one is computed.
+    // The steady-state loop has no conditional loads; the last one or two tiles are peeled.
     KVTile ta, tb;
-    if (nk > 0) load_tile(0, ta);
-    for (int k = 0; k < nk; k += 2) {
-        if (k + 1 < nk) load_tile(k + 1, tb);
+    int k = k_first;
+    if (k < k_end) load_tile(k, ta);
+    for (; k + 2 < k_end; k += 2) {
+        load_tile(k + 1, tb);
         compute_tile(k, ta);
-        if (k + 1 < nk) {
-            if (k + 2 < nk) load_tile(k + 2, ta);
-            compute_tile(k + 1, tb);
-        }
+        load_tile(k + 2, ta);
+        compute_tile(k + 1, tb);
+    }
+    if (k_end - k == 2) {
+        load_tile(k + 1, tb);
+        compute_tile(k, ta);
+        compute_tile(k + 1, tb);
+    } else if (k_end - k == 1) {
+        compute_tile(k, ta);
     }
 
     // merge the 4 waves' states through LDS and write the normalised partial of every real head

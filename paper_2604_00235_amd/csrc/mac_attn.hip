@@ -28,7 +28,14 @@ int hip_fail(hipError_t e, const char* what) {
         if (e_ != hipSuccess) return hip_fail(e_, #expr);    \
     } while (0)
 
-constexpr int kDefaultChunk = 1024;
+// Default tokens per work item: a full-length step should have about 2000 work items (4 rounds of the
+// 512 work-groups the chip holds), within [512, 2048].
+int default_chunk(int64_t groups, int64_t max_kv_len) {
+    const int64_t target = groups * max_kv_len / 2048;
+    int chunk = 512;
+    while (chunk < 2048 && chunk * 2 <= target) chunk *= 2;
+    return chunk;
+}
 
 struct Layout {            // derived sizes, pure host arithmetic
     int G, chunk, n_mid_slots, n_band_slots, n_slots, page_shift;
@@ -46,13 +53,14 @@ int validate_config(const mac_attn_config* c, Layout* L) {
     if (c->num_q_heads < 1 || c->num_kv_heads < 1 || c->num_q_heads % c->num_kv_heads != 0) return MAC_ATTN_ERR_INVALID_ARG;
     if (c->window < 1 || c->band < 0 || c->max_kv_len < 1 || c->page_size < 1) return MAC_ATTN_ERR_INVALID_ARG;
     if (!(c->threshold >= 0.f) || !std::isfinite(c->sm_scale)) return MAC_ATTN_ERR_INVALID_ARG;   // rejects NaN; +inf T is legal
-    if (c->chunk_tokens < 0) return MAC_ATTN_ERR_INVALID_ARG;
+    if (c->chunk_tokens < 0 || (c->fuse_epilogue != 0 && c->fuse_epilogue != 1)) return MAC_ATTN_ERR_INVALID_ARG;
     if (c->head_dim != mac::kHeadDim) return MAC_ATTN_ERR_UNSUPPORTED;
     const int G = c->num_q_heads / c->num_kv_heads;
     if (G > 32) return MAC_ATTN_ERR_UNSUPPORTED;
     if (c->page_size < 16 || (c->page_size & (c->page_size - 1)) != 0) return MAC_ATTN_ERR_UNSUPPORTED;
     if (c->window > 4096) return MAC_ATTN_ERR_UNSUPPORTED;
-    const int chunk = c->chunk_tokens == 0 ? kDefaultChunk : c->chunk_tokens;
+    const int chunk = c->chunk_tokens == 0 ? default_chunk((int64_t)c->max_batch * c->num_kv_heads, c->max_kv_len)
+                                           : c->chunk_tokens;
     if (chunk % mac::kTileTokens != 0 || chunk < 32 || chunk > 4096) return MAC_ATTN_ERR_INVALID_ARG;
     if ((int64_t)c->max_batch * c->num_q_heads > (1 << 24)) return MAC_ATTN_ERR_INVALID_ARG;
     L->G = G;
@@ -216,7 +224,7 @@ int launch_attention(mac_attn_ctx* ctx, const mac_attn_step_args* a, bool mac_mo
     return MAC_ATTN_OK;
 }
 
-int launch_merge(mac_attn_ctx* ctx, const mac_attn_step_args* a, bool mac_mode, hipStream_t stream) {
+mac::MergeParams merge_params(mac_attn_ctx* ctx, const mac_attn_step_args* a, bool mac_mode, bool stage_rect) {
     const mac_attn_config& c = ctx->cfg;
     const Layout& L = ctx->L;
     const int64_t bh = (int64_t)c.max_batch * c.num_q_heads;
@@ -231,8 +239,8 @@ int launch_merge(mac_attn_ctx* ctx, const mac_attn_step_args* a, bool mac_mode, 
     p.part_lse = ctx->part_lse;
     p.out = a->out;
     p.out_lse = a->out_lse;
-    p.rect_O = mac_mode ? ctx->rect : nullptr;
-    p.rect_lse = mac_mode ? ctx->rect + bh * mac::kHeadDim : nullptr;
+    p.rect_O = stage_rect ? ctx->rect : nullptr;
+    p.rect_lse = stage_rect ? ctx->rect + bh * mac::kHeadDim : nullptr;
     p.st_read = mac_mode ? ctx->stats + 3 * bh : nullptr;
     p.st_full = mac_mode ? ctx->stats + 3 * bh + (int64_t)c.max_batch * c.num_kv_heads : nullptr;
     p.Hq = c.num_q_heads;
@@ -243,8 +251,39 @@ int launch_merge(mac_attn_ctx* ctx, const mac_attn_step_args* a, bool mac_mode, 
     p.n_mid_slots = L.n_mid_slots;
     p.n_slots = L.n_slots;
     p.max_kv_len = c.max_kv_len;
-    dim3 grid(c.num_q_heads, a->batch), block(mac::kMergeThreads);
-    hipLaunchKernelGGL(mac::merge_kernel, grid, block, 0, stream, p);
+    return p;
+}
+
+mac::WritebackParams writeback_params(mac_attn_ctx* ctx, const mac_attn_step_args* a) {
+    const mac_attn_config& c = ctx->cfg;
+    const int64_t bh = (int64_t)c.max_batch * c.num_q_heads;
+    mac::WritebackParams p;
+    p.kv_lens = a->kv_lens;
+    p.slot_ids = a->slot_ids;
+    p.q_pre = static_cast<const uint16_t*>(a->q_pre);
+    p.rect_O = ctx->rect;
+    p.rect_lse = ctx->rect + bh * mac::kHeadDim;
+    p.ring_q = ctx->ring_q;
+    p.ring_O = ctx->ring_O;
+    p.ring_lse = ctx->ring_lse;
+    p.ring_npos = ctx->ring_npos;
+    p.Hq = c.num_q_heads;
+    p.W = c.window;
+    p.max_kv_len = c.max_kv_len;
+    return p;
+}
+
+// with_writeback: the merge kernel also appends to the ring (one launch less), else it stages the rectified
+// summary for writeback_kernel.
+int launch_merge(mac_attn_ctx* ctx, const mac_attn_step_args* a, bool mac_mode, bool with_writeback, hipStream_t stream) {
+    const mac::MergeParams p = merge_params(ctx, a, mac_mode, /*stage_rect=*/mac_mode && !with_writeback);
+    dim3 grid(ctx->cfg.num_q_heads, a->batch), block(mac::kMergeThreads);
+    if (with_writeback) {
+        const mac::WritebackParams wb = writeback_params(ctx, a);
+        hipLaunchKernelGGL(mac::merge_writeback_kernel, grid, block, 0, stream, p, wb);
+    } else {
+        hipLaunchKernelGGL(mac::merge_kernel, grid, block, 0, stream, p);
+    }
     HIP_TRY(hipGetLastError());
     return MAC_ATTN_OK;
 }
@@ -349,7 +388,7 @@ int mac_attn_full_decode(mac_attn_ctx* ctx, const mac_attn_step_args* args, void
     t.skip(0);
     if ((rc = launch_attention(ctx, args, false, stream)) != MAC_ATTN_OK) return rc;
     t.done(1);
-    if ((rc = launch_merge(ctx, args, false, stream)) != MAC_ATTN_OK) return rc;
+    if ((rc = launch_merge(ctx, args, false, false, stream)) != MAC_ATTN_OK) return rc;
     t.done(2);
     t.skip(3);
     t.finish();
@@ -396,24 +435,17 @@ int mac_attn_decode_step(mac_attn_ctx* ctx, const mac_attn_step_args* args, void
     // 2. band + tail (or full) attention, split-K partials
     if ((rc = launch_attention(ctx, args, true, stream)) != MAC_ATTN_OK) return rc;
     t.done(1);
-    // 3. complete: log-domain merge with the reused prefix
-    if ((rc = launch_merge(ctx, args, true, stream)) != MAC_ATTN_OK) return rc;
-    t.done(2);
-    // 4. rectify-append
-    {
-        mac::WritebackParams p;
-        p.kv_lens = args->kv_lens;
-        p.slot_ids = args->slot_ids;
-        p.q_pre = static_cast<const uint16_t*>(args->q_pre);
-        p.rect_O = ctx->rect;
-        p.rect_lse = ctx->rect + bh * mac::kHeadDim;
-        p.ring_q = ctx->ring_q;
-        p.ring_O = ctx->ring_O;
-        p.ring_lse = ctx->ring_lse;
-        p.ring_npos = ctx->ring_npos;
-        p.Hq = c.num_q_heads;
-        p.W = c.window;
-        p.max_kv_len = c.max_kv_len;
+    if (c.fuse_epilogue) {
+        // 3 + 4. complete and rectify-append in one kernel
+        if ((rc = launch_merge(ctx, args, true, true, stream)) != MAC_ATTN_OK) return rc;
+        t.done(2);
+        t.skip(3);
+    } else {
+        // 3. complete: log-domain merge with the reused prefix
+        if ((rc = launch_merge(ctx, args, true, false, stream)) != MAC_ATTN_OK) return rc;
+        t.done(2);
+        // 4. rectify-append
+        const mac::WritebackParams p = writeback_params(ctx, args);
         dim3 grid(c.num_q_heads, args->batch), block(128);
         hipLaunchKernelGGL(mac::writeback_kernel, grid, block, 0, stream, p);
         HIP_TRY(hipGetLastError());

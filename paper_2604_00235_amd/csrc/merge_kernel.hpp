@@ -1,7 +1,7 @@
-// Complete (log-domain merge) and rectify-append (ring write-back) kernels (gfx950).
+// Complete (log-domain merge) and rectify-append (ring write-back) (gfx950).
 //
 // Merge, per (request b, query head h) -- paper Sec. 3.1 (summaries over disjoint sets add), Eq. (rect-merge),
-// Sec. 4.2 "K2 (3) Merge":  in fixed ascending order
+// Sec. 4.2 "K2 (3) Merge":  in a fixed order
 //     rect = prefix (ring summary of the matched entry, on a hit)  (+)  partials of the mid chunks [s_h, n-B)
 //     out  = rect  (+)  partials of the band chunks [n-B, n)
 // where (O_a, L_a) (+) (O_b, L_b) = ((e^{L_a} O_a + e^{L_b} O_b)/(e^{L_a} + e^{L_b}), ln(e^{L_a} + e^{L_b})),
@@ -10,11 +10,29 @@
 //
 // Write-back, per (b, h) -- Sec. 4.1, Sec. 4.2 "K3": ring entry (n-1) mod W of the request's ring set gets the
 // pre-RoPE query, the rectified summary row and its ln-LSE; the entry's n_p tag is set to n.  It runs after the
-// merge in stream order because the overwritten entry (n_p = n - W) is still a candidate of this step.
+// merge of the same head because the overwritten entry (n_p = n - W) is still a candidate of this step.
+//
+// Both steps exist as kernels of their own (merge_kernel, writeback_kernel: one work-group per (head, request))
+// and fused in merge_writeback_kernel (one launch less per step; the default).  Folding them further into the
+// attention kernel ("last work-group of a group merges") was tried and dropped: the device-scope release fence
+// every work-group then needs writes back the XCD's L2 and cost 25-100 % of the attention kernel's time.
 #pragma once
 #include "common.hpp"
 
 namespace mac {
+
+struct WritebackParams {
+    const int32_t* kv_lens;
+    const int32_t* slot_ids;
+    const uint16_t* q_pre;       // [batch, Hq, 128] bf16
+    const float* rect_O;         // staging [batch*Hq, 128] (separate-kernel mode only)
+    const float* rect_lse;       // [batch*Hq]
+    uint16_t* ring_q;            // [slots, Hq, W, 128]
+    float* ring_O;               // [slots, Hq, W, 128]
+    float* ring_lse;             // [slots, Hq, W]
+    int32_t* ring_npos;          // [slots, W]
+    int32_t Hq, W, max_kv_len;
+};
 
 struct MergeParams {
     const int32_t* kv_lens;
@@ -27,19 +45,25 @@ struct MergeParams {
     const float* part_lse;       // [batch*Hq, n_slots]
     float* out;                  // [batch, Hq, 128]
     float* out_lse;              // optional [batch, Hq]
-    float* rect_O;               // staging for the write-back [batch*Hq, 128]; null for full decode
+    float* rect_O;               // staging for a separate write-back kernel [batch*Hq, 128]; may be null
     float* rect_lse;             // [batch*Hq]
     unsigned long long* st_read; // per (b, kv head) accumulators; null for full decode
     unsigned long long* st_full;
     int32_t Hq, G, W, band, chunk, n_mid_slots, n_slots, max_kv_len;
 };
 
-// One work-group of 256 threads per (request, head).  Thread (c = tid/32, q = tid%32) accumulates the
-// partials x = first + c, first + c + 8, ... for the four output columns 4q..4q+3; the 8 partial sums are added
-// in a fixed order through LDS, so the result is bitwise reproducible.  Weights are taken relative to the maximum
-// LSE of each part (rect part: prefix + mid chunks; band part), found in a first pass over the LSE scalars.
+// 256 threads per (request, head).  Thread (c = tid/32, q = tid%32) accumulates the partials
+// x = first + c, first + c + 8, ... for the four output columns 4q..4q+3; the 8 partial sums are added in a fixed
+// order through LDS, so the result is bitwise reproducible.  Weights are taken relative to the maximum LSE of
+// each part (rect part: prefix + mid chunks; band part), found in a first pass over the LSE scalars.
 constexpr int kMergeThreads = 256;
 constexpr int kMergeLanes = 8;      // chunks summed in parallel
+
+struct MergeSmem {
+    float red[4];
+    float acc[2][kMergeLanes][kHeadDim];
+    float z[2][kMergeLanes];
+};
 
 __device__ __forceinline__ float block_max_256(float v, float* s_red) {
 #pragma unroll
@@ -50,8 +74,27 @@ __device__ __forceinline__ float block_max_256(float v, float* s_red) {
     return fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
 }
 
-__global__ __launch_bounds__(kMergeThreads) void merge_kernel(const MergeParams p) {
-    const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+// Ring append of one head by threads d < 128 (values of the rectified summary passed in registers).
+__device__ __forceinline__ void writeback_head(const WritebackParams& p, int b, int h, int d, float rect_o, float rect_l) {
+    const int n = clampi(p.kv_lens[b], 0, p.max_kv_len);
+    if (n < 1) return;
+    const int bh = b * p.Hq + h;
+    const int64_t slot = p.slot_ids[b];
+    const int j = (n - 1) % p.W;
+    const int64_t e = (slot * p.Hq + h) * p.W + j;
+    p.ring_q[e * kHeadDim + d] = p.q_pre[(int64_t)bh * kHeadDim + d];
+    p.ring_O[e * kHeadDim + d] = rect_o;
+    if (d == 0) {
+        p.ring_lse[e] = rect_l;
+        if (h == 0) p.ring_npos[slot * p.W + j] = n;
+    }
+}
+
+// Merge of one head by a 256-thread work-group; with `do_wb` it also appends to the ring.
+// Contains __syncthreads: every thread of the work-group must call it.
+__device__ __forceinline__ void merge_head(const MergeParams& p, const WritebackParams& wb, bool do_wb, int b, int h,
+                                           MergeSmem& sm) {
+    const int tid = threadIdx.x;
     const int c = tid >> 5, q = tid & 31;
     const int bh = b * p.Hq + h;
     const int n = clampi(p.kv_lens[b], 0, p.max_kv_len);
@@ -69,18 +112,14 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(const MergeParams 
         if (j >= 0) pre = ((int64_t)p.slot_ids[b] * p.Hq + h) * p.W + j;
     }
 
-    __shared__ float s_red[4];
-    __shared__ float s_acc[2][kMergeLanes][kHeadDim];
-    __shared__ float s_z[2][kMergeLanes];
-
     // pass 1: maxima of the LSE scalars
     float m_r = -INFINITY, m_b = -INFINITY;
     for (int x = x0 + tid; x < x1; x += kMergeThreads)
         if (max(s, x * C) < min(nb, (x + 1) * C)) m_r = fmaxf(m_r, p.part_lse[pbase + x]);
     if (tid == 0 && pre >= 0) m_r = fmaxf(m_r, p.ring_lse[pre]);
     for (int y = y0 + tid; y < y1; y += kMergeThreads) m_b = fmaxf(m_b, p.part_lse[pbase + y]);
-    const float M_r = block_max_256(m_r, s_red);
-    const float M_b = block_max_256(m_b, s_red);
+    const float M_r = block_max_256(m_r, sm.red);
+    const float M_b = block_max_256(m_b, sm.red);
 
     // pass 2: weighted sums; empty summaries (LSE = -inf) get weight 0
     f32x4 a_r = f32x4{0.f, 0.f, 0.f, 0.f}, a_b = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -108,22 +147,24 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(const MergeParams 
             z_b += wgt;
         }
     }
-    *reinterpret_cast<f32x4*>(&s_acc[0][c][4 * q]) = a_r;
-    *reinterpret_cast<f32x4*>(&s_acc[1][c][4 * q]) = a_b;
-    if (q == 0) { s_z[0][c] = z_r; s_z[1][c] = z_b; }
-    __syncthreads();
+    *reinterpret_cast<f32x4*>(&sm.acc[0][c][4 * q]) = a_r;
+    *reinterpret_cast<f32x4*>(&sm.acc[1][c][4 * q]) = a_b;
+    if (q == 0) { sm.z[0][c] = z_r; sm.z[1][c] = z_b; }
+    __syncthreads();                                     // also orders the prefix reads before the ring write below
     if (tid < kHeadDim) {
         const int d = tid;
         float S_r = 0.f, Z_r = 0.f, S_b = 0.f, Z_b = 0.f;
 #pragma unroll
         for (int k = 0; k < kMergeLanes; ++k) {
-            S_r += s_acc[0][k][d]; Z_r += s_z[0][k];
-            S_b += s_acc[1][k][d]; Z_b += s_z[1][k];
+            S_r += sm.acc[0][k][d]; Z_r += sm.z[0][k];
+            S_b += sm.acc[1][k][d]; Z_b += sm.z[1][k];
         }
         // rect = prefix (+) mid chunks: this step's total without the last-B band
+        const float rect_o = Z_r > 0.f ? S_r / Z_r : 0.f;
+        const float rect_l = Z_r > 0.f ? M_r + logf(Z_r) : -INFINITY;
         if (p.rect_O != nullptr) {
-            p.rect_O[(int64_t)bh * kHeadDim + d] = Z_r > 0.f ? S_r / Z_r : 0.f;
-            if (d == 0) p.rect_lse[bh] = Z_r > 0.f ? M_r + logf(Z_r) : -INFINITY;
+            p.rect_O[(int64_t)bh * kHeadDim + d] = rect_o;
+            if (d == 0) p.rect_lse[bh] = rect_l;
         }
         // out = rect (+) band
         const float M_o = fmaxf(M_r, M_b);
@@ -136,6 +177,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(const MergeParams 
         }
         p.out[(int64_t)bh * kHeadDim + d] = o;
         if (d == 0 && p.out_lse != nullptr) p.out_lse[bh] = lse;
+        if (do_wb) writeback_head(wb, b, h, d, rect_o, rect_l);
     }
 
     // KV tokens streamed by this step for the KV group (read once per group from its smallest start)
@@ -146,35 +188,24 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(const MergeParams 
         p.st_read[bg] += (unsigned long long)(n - gs);
         p.st_full[bg] += (unsigned long long)n;
     }
+    __syncthreads();                                     // shared memory is reused by the next head
 }
 
-struct WritebackParams {
-    const int32_t* kv_lens;
-    const int32_t* slot_ids;
-    const uint16_t* q_pre;       // [batch, Hq, 128] bf16
-    const float* rect_O;         // [batch*Hq, 128]
-    const float* rect_lse;       // [batch*Hq]
-    uint16_t* ring_q;            // [slots, Hq, W, 128]
-    float* ring_O;               // [slots, Hq, W, 128]
-    float* ring_lse;             // [slots, Hq, W]
-    int32_t* ring_npos;          // [slots, W]
-    int32_t Hq, W, max_kv_len;
-};
+__global__ __launch_bounds__(kMergeThreads) void merge_kernel(const MergeParams p) {
+    __shared__ MergeSmem sm;
+    const WritebackParams none{};
+    merge_head(p, none, false, blockIdx.y, blockIdx.x, sm);
+}
+
+__global__ __launch_bounds__(kMergeThreads) void merge_writeback_kernel(const MergeParams p, const WritebackParams wb) {
+    __shared__ MergeSmem sm;
+    merge_head(p, wb, true, blockIdx.y, blockIdx.x, sm);
+}
 
 __global__ __launch_bounds__(128) void writeback_kernel(const WritebackParams p) {
     const int h = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
     const int bh = b * p.Hq + h;
-    const int n = clampi(p.kv_lens[b], 0, p.max_kv_len);
-    if (n < 1) return;
-    const int64_t slot = p.slot_ids[b];
-    const int j = (n - 1) % p.W;
-    const int64_t e = (slot * p.Hq + h) * p.W + j;
-    p.ring_q[e * kHeadDim + d] = p.q_pre[(int64_t)bh * kHeadDim + d];
-    p.ring_O[e * kHeadDim + d] = p.rect_O[(int64_t)bh * kHeadDim + d];
-    if (d == 0) {
-        p.ring_lse[e] = p.rect_lse[bh];
-        if (h == 0) p.ring_npos[slot * p.W + j] = n;
-    }
+    writeback_head(p, b, h, d, p.rect_O[(int64_t)bh * kHeadDim + d], p.rect_lse[bh]);
 }
 
 }  // namespace mac

@@ -43,12 +43,13 @@ class GpuRun:
     """One library context + device buffers for a workload living on cuda:0."""
 
     def __init__(self, cfg: WorkloadConfig, wl: Workload, chunk_tokens: int = 0, strides=None, kv_pages=None,
-                 max_kv_len=None):
+                 max_kv_len=None, fuse_epilogue: bool = True):
         self.cfg, self.wl = cfg, wl
         dev = wl.device
         self.mac = mb.MacAttention(num_q_heads=cfg.num_q_heads, num_kv_heads=cfg.num_kv_heads, window=cfg.window,
                                    band=cfg.band, threshold=cfg.threshold, max_kv_len=max_kv_len or cfg.max_kv_len,
-                                   max_slots=cfg.batch, page_size=cfg.page_size, chunk_tokens=chunk_tokens)
+                                   max_slots=cfg.batch, page_size=cfg.page_size, chunk_tokens=chunk_tokens,
+                                   fuse_epilogue=fuse_epilogue)
         self.kv_pages = wl.kv_pages if kv_pages is None else kv_pages
         self.strides = wl.strides if strides is None else strides
         B, Hq, d = cfg.batch, cfg.num_q_heads, cfg.head_dim
@@ -76,13 +77,13 @@ class GpuRun:
 
 
 def run_parity(cfg: WorkloadConfig, chunk_tokens: int = 0, check_full: bool = True, check_ring_every: int = 4,
-               label: str = ""):
+               label: str = "", fuse_epilogue: bool = True):
     """All steps of `cfg` on both sides; returns summary dict.  Oracle inputs are host copies of the same bits."""
     say(f"[parity] {label or cfg.name}: batch={cfg.batch} Hq/Hkv={cfg.num_q_heads}/{cfg.num_kv_heads} "
         f"context={cfg.context} steps={cfg.steps} W={cfg.window} B={cfg.band} T={cfg.threshold:.4g} "
-        f"page={cfg.page_size} chunk={chunk_tokens} seed={cfg.seed}")
+        f"page={cfg.page_size} chunk={chunk_tokens} fused={fuse_epilogue} seed={cfg.seed}")
     wl = Workload(cfg, device="cuda:0")
-    run = GpuRun(cfg, wl, chunk_tokens)
+    run = GpuRun(cfg, wl, chunk_tokens, fuse_epilogue=fuse_epilogue)
     orc = make_oracle(cfg, wl)
     kvp = bf16_bits(wl.kv_pages)
     bt = wl.block_table.cpu().numpy()

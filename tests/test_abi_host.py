@@ -23,7 +23,8 @@ def lib():
 
 def _cfg(**kw):
     base = dict(device=0, max_slots=4, max_batch=4, num_q_heads=32, num_kv_heads=8, head_dim=128, page_size=16,
-                window=256, band=128, threshold=2.7, sm_scale=0.0, max_kv_len=131200, chunk_tokens=0)
+                window=256, band=128, threshold=2.7, sm_scale=0.0, max_kv_len=131200, chunk_tokens=1024,
+                fuse_epilogue=1)
     base.update(kw)
     return mb.mac_attn_config(**base)
 
@@ -38,7 +39,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_struct_layouts_match_header():
     """Field order/size of the ctypes mirrors: int32/float fields packed as in the C structs."""
-    assert C.sizeof(mb.mac_attn_config) == 13 * 4
+    assert C.sizeof(mb.mac_attn_config) == 14 * 4
     assert C.sizeof(mb.mac_attn_stats_t) == 8 * 8
     a = mb.mac_attn_step_args
     assert a.stride_page.offset % 8 == 0 and a.block_table_stride.offset == a.block_table.offset + 8
@@ -79,6 +80,7 @@ def test_device_bytes_accounts_rings_and_workspace(lib):
     (dict(chunk_tokens=100), mb.MAC_ATTN_ERR_INVALID_ARG),
     (dict(chunk_tokens=8192), mb.MAC_ATTN_ERR_INVALID_ARG),
     (dict(max_kv_len=0), mb.MAC_ATTN_ERR_INVALID_ARG),
+    (dict(fuse_epilogue=2), mb.MAC_ATTN_ERR_INVALID_ARG),
 ])
 def test_bad_configs_are_rejected_before_any_gpu_call(lib, kw, code):
     cfg = _cfg(**kw)

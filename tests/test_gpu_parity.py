@@ -23,14 +23,14 @@ def test_c1_tiny_config_exact():
     assert r["hits"] > 0
 
 
-@pytest.mark.parametrize("chunk", [0, 256])
-def test_llama_shape_reduced_mixed_hits(chunk):
+@pytest.mark.parametrize("chunk,fused", [(0, True), (256, True), (256, False)])
+def test_llama_shape_reduced_mixed_hits(chunk, fused):
     """C2 geometry (32/8 heads) at a reduced, ragged context; threshold near the lag-1 distance so that hits
     and misses mix inside KV groups (per-head start masks, group-level spans)."""
     from tests.gpu_harness import run_parity
     cfg = scaled(CONFIGS["C2"], name="C2r", batch=3, context=2500, steps=24, window=16, band=64,
                  threshold=2.8, ragged=37)
-    r = run_parity(cfg, chunk_tokens=chunk)
+    r = run_parity(cfg, chunk_tokens=chunk, fuse_epilogue=fused)
     assert 0 < r["hits"] < r["head_steps"]
 
 
@@ -42,20 +42,22 @@ def test_mqa_threshold_zero_equals_full_attention():
     assert r["hits"] == 0
 
 
-def test_mqa_matched_threshold():
+@pytest.mark.parametrize("fused", [True, False])
+def test_mqa_matched_threshold(fused):
     """C4 run B (MQA, G=32) at reduced context with the config's threshold: all hits after the first step."""
     from tests.gpu_harness import run_parity
     cfg = scaled(CONFIGS["C4_hit"], name="C4b", batch=2, context=1400, steps=20, window=8, ragged=3)
-    r = run_parity(cfg)
+    r = run_parity(cfg, fuse_epilogue=fused)
     assert r["hits"] == r["head_steps"] - cfg.batch * cfg.num_q_heads
 
 
-def test_continuous_generation_regime_shifts_and_ring_wrap():
+@pytest.mark.parametrize("fused", [True, False])
+def test_continuous_generation_regime_shifts_and_ring_wrap(fused):
     """C5 geometry (64/8 heads, G=8), regime shift every 8 steps, W=8 so the ring wraps 5 times."""
     from tests.gpu_harness import run_parity
     cfg = scaled(CONFIGS["C5"], name="C5r", batch=2, context=700, steps=40, window=8, band=64,
                  regime_shift_every=8)
-    r = run_parity(cfg, chunk_tokens=128, check_ring_every=1)
+    r = run_parity(cfg, chunk_tokens=128, check_ring_every=1, fuse_epilogue=fused)
     assert 0 < r["hits"] < r["head_steps"]
 
 
@@ -72,7 +74,8 @@ def test_edge_cases(kw):
     base = dict(name="edge", batch=2, num_q_heads=4, num_kv_heads=2, context=64, steps=8, window=4, band=8,
                 threshold=T_DEFAULT, rho=0.97, seed=5)
     base.update(kw)
-    run_parity(WorkloadConfig(**base), chunk_tokens=32, check_ring_every=1)
+    for fused in (True, False):
+        run_parity(WorkloadConfig(**base), chunk_tokens=32, check_ring_every=1, fuse_epilogue=fused)
 
 
 def test_strided_kv_layout_and_group_sizes():
