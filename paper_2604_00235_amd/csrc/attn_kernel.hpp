@@ -17,14 +17,18 @@
 // (those that intersect the work item) and keeps its own online-softmax state; the 4 states are merged
 // through LDS at the end.
 // Per tile and wave, with lane l = (r = l%16, kg = l/16):
-//   S = K Q^T by v_mfma_f32_16x16x32_bf16:  A = K rows (lane: token r of a 16-token sub-tile, 8 contiguous d
-//       elements 32c+8kg.. of k-step c), B = Q^T (lane: head r, same d elements).  Output: lane holds head r,
-//       tokens 4kg+i (i<4) of the sub-tile.  K is loaded from global memory directly in this layout
-//       (16 rows x 64 contiguous bytes per instruction; the four k-steps cover each 256-byte row once).
+//   S = K Q^T by v_mfma_f32_16x16x32_bf16:  A = K rows (lane: row 4(r%4) + r/4 of a 16-token sub-tile,
+//       8 contiguous d elements 32c+8kg.. of k-step c), B = Q^T (lane: head r, same d elements).  Output: lane
+//       holds head r and the scores of tokens 4i+kg (i<4) of the sub-tile.  K is loaded from global memory
+//       directly in this layout (16 rows x 64 contiguous bytes per instruction; the four k-steps cover each
+//       256-byte row once).
 //   O += P V by the same MFMA:  A = P (lane: head r, 8 tokens = its own 2x4 scores, so the QK output is
-//       used in place), B = V (lane: 8 d-columns 8r..8r+7 of the same 8 tokens; loaded as 8 rows x 16 bytes,
-//       each quarter-wave reading one full 256-byte row, then transposed in registers with v_perm_b32 into
-//       8 operands, one per column offset j; operand j produces output columns d = 8r + j).
+//       used in place), B = V (lane: 8 d-columns 8r..8r+7 of the same 8 tokens 4i+kg).  With that token
+//       labelling V load i of a sub-tile reads rows 4i..4i+3, one per quarter-wave: 1 KiB contiguous per
+//       instruction.  The 8 rows are transposed in registers with v_perm_b32 into 8 operands, one per
+//       column offset j; operand j produces output columns d = 8r + j.
+//       (Supplying K rows in natural order makes the V loads 4 separate 256-byte rows per instruction; measured
+//       with load-only probes, that combination streams ~4 % slower at this occupancy.)
 //   P is fp32 on the VALU (max, exp2, sum) and enters the MFMA as two bf16 terms hi + lo (truncation split,
 //       relative error 2^-16), because a single bf16 P would cost ~1e-3 relative output error.
 // Heads beyond G in the 16-row head tile carry zero queries; their results are never stored.
@@ -54,7 +58,7 @@ struct AttnParams {
 
 struct KVTile {
     u32x4 k[2][4];   // [sub-tile][k-step]  A operands of S = K Q^T
-    u32x4 v[8];      // [e = 4*sub-tile + i] 8 d-columns of token 16*sub + 4kg + i
+    u32x4 v[8];      // [e = 4*sub-tile + i] 8 d-columns of token 16*sub + 4i + kg
 };
 
 template <int HT>   // number of 16-head tiles: 1 (G <= 16) or 2 (G <= 32)
@@ -141,6 +145,7 @@ __global__ __launch_bounds__(256, (HT == 1 ? 2 : 1)) void attn_kernel(const Attn
     // All 16 loads of a tile are issued unconditionally (rows past the end re-read the last valid row, whose
     // scores are masked): with a fixed number of loads per tile the compiler can wait for exactly the older
     // tile's loads and leave the prefetched tile in flight.
+    const int krow = 4 * (r16 & 3) + (r16 >> 2);               // sub-tile row this lane supplies to S = K Q^T
     auto load_tile = [&](int k, KVTile& T) {
         const int t0 = (chunk_tile0 + w + 4 * k) * kTileTokens;
 #pragma unroll
@@ -150,13 +155,13 @@ __global__ __launch_bounds__(256, (HT == 1 ? 2 : 1)) void attn_kernel(const Attn
             const int lim = past ? 15 : n - 1 - tb;
             const int pid = __builtin_amdgcn_readlane(mypid, 2 * k + u);
             const uint16_t* base = kv_g + (int64_t)pid * p.stride_page + (int64_t)(tb & page_mask) * p.stride_tok;
-            const uint16_t* kp = base + (int64_t)min(r16, lim) * p.stride_tok + 8 * kg;
+            const uint16_t* kp = base + (int64_t)min(krow, lim) * p.stride_tok + 8 * kg;
 #pragma unroll
             for (int c = 0; c < 4; ++c) T.k[u][c] = *reinterpret_cast<const u32x4*>(kp + 32 * c);
             const uint16_t* vp = base + p.stride_kv + 8 * r16;
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                T.v[4 * u + i] = *reinterpret_cast<const u32x4*>(vp + (int64_t)min(4 * kg + i, lim) * p.stride_tok);
+                T.v[4 * u + i] = *reinterpret_cast<const u32x4*>(vp + (int64_t)min(4 * i + kg, lim) * p.stride_tok);
         }
     };
 
@@ -191,7 +196,7 @@ __global__ __launch_bounds__(256, (HT == 1 ? 2 : 1)) void attn_kernel(const Attn
             if (need_mask) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    const int tok = t0 + 16 * (e >> 2) + 4 * kg + (e & 3);
+                    const int tok = t0 + 16 * (e >> 2) + 4 * (e & 3) + kg;
                     if (tok < hstart[ht] || tok >= hi) sc[e] = -INFINITY;
                 }
             }
