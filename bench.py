@@ -26,6 +26,10 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 KV_BYTES_PER_TOKEN_HEAD = 512   # K row + V row, bf16, d = 128
+# HBM bytes per attention-kernel launch from two rocprofv3 --pmc runs of this command with its default arguments
+# (FETCH_SIZE x 2.0000 + WRITE_SIZE x 1.0000, scale factors from a 1 GiB copy; profiles/attn_kernel_C3_128k_pmc_traffic.txt).
+# Only valid for exactly that workload and step range, so it is reported for no other.
+PROFILED_TRAFFIC = {("C3_rho97", 40, 8): {"mac": 2.0266e9, "full": 2.1550e9}}
 
 
 def log(msg: str):
@@ -190,6 +194,7 @@ def main():
         del src, dst
 
     cfg = wl_mod.CONFIGS[a.config]
+    traffic = PROFILED_TRAFFIC.get((a.config, a.steps, a.warmup), {})
     line = {
         "metric": "decode_attention_us_per_step", "value": round(head["us_per_step"], 2), "unit": "us/step",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(head["us_per_step"] / 1e3, 5),
@@ -208,11 +213,12 @@ def main():
         "roofline": {
             "bound": "hbm", "kernel": "attn_kernel (band+tail / full split-K attention) inside mac_attn_decode_step",
             "achieved": round(head["attn_GBps"], 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-            "frac": round(head["attn_GBps"] / HBM_PEAK_GBPS, 4), "traffic": None,
+            "frac": round(head["attn_GBps"] / HBM_PEAK_GBPS, 4), "traffic": traffic.get("mac"),
             "bytes_per_launch": round(head["attn_bytes_per_launch"]), "us_per_launch": round(head["kernel_us"]["attention"], 2),
         },
         "full_decode_roofline": {
             "achieved": round(head["full_attn_GBps"], 1), "frac": round(head["full_attn_GBps"] / HBM_PEAK_GBPS, 4),
+            "traffic": traffic.get("full"),
             "bytes_per_launch": round(head["full_attn_bytes_per_launch"]),
             "us_per_launch": round(head["full_kernel_us"]["attention"], 2),
         },
