@@ -121,3 +121,64 @@ def test_c5_continuous_generation_full_batch():
     cfg = scaled(CONFIGS["C5"], regime_shift_every=16)
     hits, st = run_fullsize(cfg, steps=40, groups=[(0, 0), (31, 7)], full_heads=[(16, 33)])
     assert 0 < hits < st["head_steps"]
+
+
+def test_c5_full_length_16384_steps():
+    """BASELINE configs[4] as stated, all 16384 generated steps (context 8192 -> 24576, regime shift every 2048
+    steps, the ring of 256 entries wraps 64 times).  Every step runs on the GPU; the oracle follows two sampled KV
+    groups through every step (outputs and decisions), and checks the decisions of ALL 2048 heads on every 64th
+    step and on the three steps from each regime shift on (its matcher rings are kept up to date at every step)."""
+    from oracle.mac_oracle import Oracle
+    from tests.gpu_harness import GpuRun, check_rows, say
+    cfg = CONFIGS["C5"]
+    say(f"[fullsize] C5 full length: batch={cfg.batch} Hq/Hkv={cfg.num_q_heads}/{cfg.num_kv_heads} steps={cfg.steps}")
+    wl = Workload(cfg, device="cuda:0")
+    run = GpuRun(cfg, wl)
+    kvp = bf16_bits(wl.kv_pages)
+    bt = wl.block_table.cpu().numpy()
+    slots = wl.slot_ids.cpu().numpy()
+    G = cfg.group
+    morc = Oracle(num_q_heads=cfg.num_q_heads, num_kv_heads=cfg.num_kv_heads, head_dim=cfg.head_dim,
+                  page_size=cfg.page_size, window=cfg.window, band=cfg.band, threshold=cfg.threshold,
+                  strides=wl.strides, max_slots=cfg.batch)
+    groups = [(3, 1), (30, 6)]
+    gorc = {}
+    for (b, g) in groups:
+        kv_g = np.ascontiguousarray(kvp[:, :, g:g + 1])
+        gorc[(b, g)] = (_group_oracle(cfg, kv_g), kv_g, bt[b:b + 1].copy())
+    hits = checked_all = 0
+    worst = 0.0
+    miss_steps = set()
+    for s, (q_pre, q_rope, kv_lens) in enumerate(wl):
+        lens = kv_lens.cpu().numpy()
+        qp, qr = bf16_bits(q_pre), bf16_bits(q_rope)
+        run.mac.decode_step(run.args(q_pre, q_rope, kv_lens), run.stream)
+        torch.cuda.synchronize()
+        g_pos = run.pos.cpu().numpy()
+        if s % 64 == 0 or s % cfg.regime_shift_every < 3:
+            o_pos, _, _ = morc.match(slots, lens, qp)
+            assert np.array_equal(g_pos, o_pos), f"step {s}: decisions differ at {np.argwhere(g_pos != o_pos)[:4].tolist()}"
+            checked_all += 1
+        j = (int(lens[0]) - 1) % cfg.window             # all requests have the same length here
+        morc.ring_q[:, j] = qp
+        morc.ring_npos[:, j] = lens
+        n_hit = int((g_pos >= 0).sum())
+        hits += n_hit
+        if n_hit < g_pos.size // 2:
+            miss_steps.add(s)
+        for (b, g), (orc, kv_g, bt_b) in gorc.items():
+            hs = slice(g * G, (g + 1) * G)
+            ref = orc.mac_step(np.zeros(1, np.int32), lens[b:b + 1], qp[b:b + 1, hs], qr[b:b + 1, hs], kv_g, bt_b)
+            assert np.array_equal(ref["match_pos"][0], g_pos[b, hs]), f"step {s} group {(b, g)}"
+            a, r = check_rows(run.out[b, hs].cpu().numpy(), ref["out"][0], f"C5 step {s} b{b} g{g}")
+            worst = max(worst, r)
+        if s % 2048 == 0:
+            say(f"[fullsize] C5 step {s}: hits so far {hits}, worst rel-L2 {worst:.2e}")
+    st = run.mac.stats()
+    assert st["steps"] == cfg.steps and st["hits"] == hits
+    # the first step after each regime shift misses everywhere (jump ~ sqrt(2d)); everything else hits
+    assert miss_steps == set(range(0, cfg.steps, cfg.regime_shift_every)), sorted(miss_steps)[:12]
+    assert hits == (cfg.steps - len(miss_steps)) * cfg.batch * cfg.num_q_heads
+    run.mac.close()
+    say(f"[fullsize] C5 full length ok: hits {hits}/{st['head_steps']}, all-head decision checks on {checked_all} steps, "
+        f"worst rel-L2 {worst:.2e}, KV read {st['kv_tokens_read']}/{st['kv_tokens_full']}")
