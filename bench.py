@@ -36,7 +36,7 @@ def log(msg: str):
     print(msg, file=sys.stderr, flush=True)
 
 
-def run_config(name: str, steps: int, warmup: int, torch, mb, wl_mod, keep_kv=None):
+def run_config(name: str, steps: int, warmup: int, torch, mb, wl_mod, keep_kv=None, use_graph=False):
     """Timed MAC steps + timed full-decode steps + per-kernel timing pass for one config.
     Returns (result dict, workload) -- the workload's KV cache is reused by the next config of the sweep."""
     cfg = wl_mod.CONFIGS[name]
@@ -95,6 +95,30 @@ def run_config(name: str, steps: int, warmup: int, torch, mb, wl_mod, keep_kv=No
         mac.full_decode(a, stream)
     f_us, f_n = mb.mac_attn_kernel_us(mac.ctx)
     mb.mac_attn_set_timing(mac.ctx, False)
+
+    # --- the same MAC step replayed from one captured HIP graph (static input buffers refreshed by device copies,
+    # which are inside the timed region), to show what launch overhead is left in the eager figure
+    graph_us = None
+    if use_graph:
+        qp_s, qr_s, kl_s = (t.clone() for t in inputs[0])
+        g_args = mac.make_args(kv_lens=kl_s, q_rope=qr_s, kv_pages=wl.kv_pages, strides=wl.strides,
+                               block_table=wl.block_table, out=out, slot_ids=wl.slot_ids, q_pre=qp_s)
+        mac.reset()
+        for (qp, qr, kl) in inputs[:warmup]:
+            qp_s.copy_(qp); qr_s.copy_(qr); kl_s.copy_(kl)
+            mac.decode_step(g_args, stream)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=torch.cuda.Stream()):
+            mac.decode_step(g_args, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for (qp, qr, kl) in inputs[warmup:warmup + steps]:
+            qp_s.copy_(qp); qr_s.copy_(qr); kl_s.copy_(kl)
+            g.replay()
+        torch.cuda.synchronize()
+        graph_us = 1e6 * (time.perf_counter() - t0) / steps
+        del g
     mac.close()
 
     n_mid = cfg.context + warmup + steps // 2
@@ -116,6 +140,7 @@ def run_config(name: str, steps: int, warmup: int, torch, mb, wl_mod, keep_kv=No
         "attn_bytes_per_launch": KV_BYTES_PER_TOKEN_HEAD * st2["kv_tokens_read"] / k_n,
         "full_attn_bytes_per_launch": KV_BYTES_PER_TOKEN_HEAD * full_tokens / f_n,
         "kv_len_mid": n_mid,
+        "graph_us_per_step": graph_us,
     }
     res["attn_GBps"] = res["attn_bytes_per_launch"] / (res["kernel_us"]["attention"] * 1e-6) / 1e9
     res["full_attn_GBps"] = res["full_attn_bytes_per_launch"] / (res["full_kernel_us"]["attention"] * 1e-6) / 1e9
@@ -161,6 +186,9 @@ def main():
     ap.add_argument("--no-sweep", action="store_true", help="skip the other two (rho, threshold) pairs of C3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=12)
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the headline config replayed from one captured HIP graph (off by default: on this "
+                         "ROCm a replay costs more than the three eager launches it replaces)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (known traffic) so that a rocprofv3 --pmc run of this "
                          "command can scale FETCH_SIZE / WRITE_SIZE")
@@ -177,7 +205,7 @@ def main():
     from paper_2604_00235_amd import workload as wl_mod
     mb.load_library()     # fails loudly if the HIP library is not built
 
-    head, wl = run_config(a.config, a.steps, a.warmup, torch, mb, wl_mod)
+    head, wl = run_config(a.config, a.steps, a.warmup, torch, mb, wl_mod, use_graph=a.graph)
     sweep = {}
     if not a.no_sweep and a.config.startswith("C3_"):
         for other in ("C3_rho90", "C3_rho97", "C3_rho99"):
@@ -209,6 +237,7 @@ def main():
         "speedup_vs_full_decode": round(head["speedup_vs_full"], 3),
         "achieved_hbm_GBps": round(head["attn_GBps"], 1),
         "effective_hbm_GBps": round(head["effective_GBps"], 1),
+        "graph_replay_us_per_step": None if head["graph_us_per_step"] is None else round(head["graph_us_per_step"], 2),
         "kernel_us": {k: round(v, 2) for k, v in head["kernel_us"].items()},
         "roofline": {
             "bound": "hbm", "kernel": "attn_kernel (band+tail / full split-K attention) inside mac_attn_decode_step",

@@ -108,16 +108,17 @@ int mac_attn_decode_step(mac_attn_ctx* ctx, const mac_attn_step_args* args /*hos
  * the speed-up is reported against); reads and changes no ring state.  Sec. 2, Sec. 3.2.1. */
 int mac_attn_full_decode(mac_attn_ctx* ctx, const mac_attn_step_args* args /*host*/, void* hip_stream);
 
-/* Wait for the stream last used with ctx, then read the counters into *out; reset != 0 clears them. */
+/* Wait for all work on the context's device (steps may have been replayed from a captured graph on any stream),
+ * then read the counters into *out; reset != 0 clears them. */
 int mac_attn_stats(mac_attn_ctx* ctx, mac_attn_stats_t* out /*host*/, int reset);
 
 /* Empty the rings of the given ring sets (a new request takes over the slot); null/n <= 0 = all sets.
- * Synchronous with respect to the stream last used with ctx. */
+ * Waits for all work on the context's device first. */
 int mac_attn_reset(mac_attn_ctx* ctx, const int32_t* slot_ids /*host*/, int32_t n);
 
 /* Test/diagnostic accessor: copy ring entry j (0 <= j < W) of ring set `slot`, head h, to host buffers
  * (any may be null): q_pre bf16 bits [d], summary row fp32 [d], ln-LSE, and the entry's n_p (0 = empty).
- * Synchronises the stream last used with ctx. */
+ * Waits for all work on the context's device first. */
 int mac_attn_ring_peek(mac_attn_ctx* ctx, int32_t slot, int32_t j, int32_t h,
                        uint16_t* q_pre /*host*/, float* summary /*host*/, float* lse /*host*/, int32_t* n_p /*host*/);
 

@@ -82,7 +82,7 @@ int validate_config(const mac_attn_config* c, Layout* L) {
     L->part_lse_bytes = bh * L->n_slots * 4;
     L->match_bytes = bh * 3 * 4;
     L->rect_bytes = bh * (mac::kHeadDim + 1) * 4;
-    L->stats_bytes = bh * 3 * 8 + (int64_t)c->max_batch * c->num_kv_heads * 2 * 8;
+    L->stats_bytes = bh * 3 * 8 + (int64_t)c->max_batch * c->num_kv_heads * 2 * 8 + 2 * 8;
     return MAC_ATTN_OK;
 }
 
@@ -110,7 +110,6 @@ struct mac_attn_ctx {
     float* rect = nullptr;        // [bh*128] rows then [bh] lse
     // counters
     unsigned long long* stats = nullptr;
-    uint64_t steps = 0, head_steps = 0;
     hipStream_t last_stream = nullptr;
     // timing
     bool timing = false;
@@ -321,7 +320,7 @@ void mac_attn_destroy(mac_attn_ctx* ctx) {
     if (ctx == nullptr) return;
     int cur = -1;
     if (hipGetDevice(&cur) == hipSuccess && cur != ctx->cfg.device) (void)hipSetDevice(ctx->cfg.device);
-    if (ctx->last_stream != nullptr || ctx->steps > 0) (void)hipStreamSynchronize(ctx->last_stream);
+    (void)hipDeviceSynchronize();
     void* bufs[] = {ctx->ring_q, ctx->ring_O, ctx->ring_lse, ctx->ring_npos, ctx->part_O, ctx->part_lse,
                     ctx->m_np, ctx->rect, ctx->stats};
     for (void* b : bufs)
@@ -422,6 +421,7 @@ int mac_attn_decode_step(mac_attn_ctx* ctx, const mac_attn_step_args* args, void
         p.st_hits = ctx->stats;
         p.st_gap = ctx->stats + bh;
         p.st_skip = reinterpret_cast<double*>(ctx->stats + 2 * bh);
+        p.st_steps = ctx->stats + 3 * bh + 2 * (int64_t)c.max_batch * c.num_kv_heads;
         p.Hq = c.num_q_heads;
         p.W = c.window;
         p.B = c.band;
@@ -452,8 +452,6 @@ int mac_attn_decode_step(mac_attn_ctx* ctx, const mac_attn_step_args* args, void
         t.done(3);
     }
     t.finish();
-    ctx->steps += 1;
-    ctx->head_steps += (uint64_t)args->batch * c.num_q_heads;
     return t.rc;
 }
 
@@ -461,15 +459,15 @@ int mac_attn_stats(mac_attn_ctx* ctx, mac_attn_stats_t* out, int reset) {
     if (ctx == nullptr || out == nullptr) return MAC_ATTN_ERR_INVALID_ARG;
     int rc = ensure_device(ctx);
     if (rc != MAC_ATTN_OK) return rc;
-    HIP_TRY(hipStreamSynchronize(ctx->last_stream));
+    HIP_TRY(hipDeviceSynchronize());          // steps may have been replayed from a graph on any stream
     const mac_attn_config& c = ctx->cfg;
     const int64_t bh = (int64_t)c.max_batch * c.num_q_heads, bg = (int64_t)c.max_batch * c.num_kv_heads;
-    std::vector<unsigned long long> host((size_t)(3 * bh + 2 * bg));
+    std::vector<unsigned long long> host((size_t)(3 * bh + 2 * bg + 2));
     HIP_TRY(hipMemcpy(host.data(), ctx->stats, (size_t)ctx->L.stats_bytes, hipMemcpyDeviceToHost));
     mac_attn_stats_t s;
     std::memset(&s, 0, sizeof(s));
-    s.steps = ctx->steps;
-    s.head_steps = ctx->head_steps;
+    s.steps = host[(size_t)(3 * bh + 2 * bg)];
+    s.head_steps = host[(size_t)(3 * bh + 2 * bg + 1)];
     for (int64_t i = 0; i < bh; ++i) {          // fixed order: the double sum is reproducible
         s.hits += host[(size_t)i];
         s.sum_gap += host[(size_t)(bh + i)];
@@ -485,8 +483,6 @@ int mac_attn_stats(mac_attn_ctx* ctx, mac_attn_stats_t* out, int reset) {
     *out = s;
     if (reset) {
         HIP_TRY(hipMemset(ctx->stats, 0, (size_t)ctx->L.stats_bytes));
-        ctx->steps = 0;
-        ctx->head_steps = 0;
     }
     return MAC_ATTN_OK;
 }
@@ -495,7 +491,7 @@ int mac_attn_reset(mac_attn_ctx* ctx, const int32_t* slot_ids, int32_t n) {
     if (ctx == nullptr) return MAC_ATTN_ERR_INVALID_ARG;
     int rc = ensure_device(ctx);
     if (rc != MAC_ATTN_OK) return rc;
-    HIP_TRY(hipStreamSynchronize(ctx->last_stream));
+    HIP_TRY(hipDeviceSynchronize());
     const int W = ctx->cfg.window;
     if (slot_ids == nullptr || n <= 0) {
         HIP_TRY(hipMemset(ctx->ring_npos, 0, (size_t)ctx->L.ring_npos_bytes));
@@ -515,7 +511,7 @@ int mac_attn_ring_peek(mac_attn_ctx* ctx, int32_t slot, int32_t j, int32_t h, ui
     if (slot < 0 || slot >= c.max_slots || j < 0 || j >= c.window || h < 0 || h >= c.num_q_heads) return MAC_ATTN_ERR_INVALID_ARG;
     int rc = ensure_device(ctx);
     if (rc != MAC_ATTN_OK) return rc;
-    HIP_TRY(hipStreamSynchronize(ctx->last_stream));
+    HIP_TRY(hipDeviceSynchronize());
     const int64_t e = ((int64_t)slot * c.num_q_heads + h) * c.window + j;
     if (q_pre) HIP_TRY(hipMemcpy(q_pre, ctx->ring_q + e * mac::kHeadDim, mac::kHeadDim * 2, hipMemcpyDeviceToHost));
     if (summary) HIP_TRY(hipMemcpy(summary, ctx->ring_O + e * mac::kHeadDim, mac::kHeadDim * 4, hipMemcpyDeviceToHost));

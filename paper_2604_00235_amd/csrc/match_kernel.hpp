@@ -39,6 +39,7 @@ struct MatchParams {
     unsigned long long* st_hits; // per (b, h) accumulators, touched only by that (b, h)'s work-group
     unsigned long long* st_gap;
     double* st_skip;
+    unsigned long long* st_steps;   // [2]: decode steps, head-steps (device-side so that graph replays count too)
     int32_t Hq, W, B, max_kv_len;
     double T2;                   // (double)T * (double)T
 };
@@ -122,6 +123,10 @@ __global__ __launch_bounds__(kMatchThreads) void match_kernel(const MatchParams 
     if ((tid & 63) == 0) { s_d2[tid >> 6] = best_d2; s_np[tid >> 6] = best_np; s_j[tid >> 6] = best_j; }
     __syncthreads();
     if (tid == 0) {
+        if (h == 0 && b == 0) {
+            p.st_steps[0] += 1ull;
+            p.st_steps[1] += (unsigned long long)gridDim.x * gridDim.y;
+        }
         for (int w = 1; w < kWaves; ++w)
             if (better(s_d2[w], s_np[w], best_d2, best_np)) { best_d2 = s_d2[w]; best_np = s_np[w]; best_j = s_j[w]; }
         const bool hit = best_np >= 1 && best_d2 < p.T2;
