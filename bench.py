@@ -152,6 +152,76 @@ def run_config(name: str, steps: int, warmup: int, torch, mb, wl_mod, keep_kv=No
     return res, wl
 
 
+def paper_table(torch, mb, wl_mod, steps: int = 200):
+    """Our analogue of the paper's fine-grained latency table (Sec. 5.6: Match / Load-balance / Attention / Overall
+    at 32K / 60K / 120K context and KV budgets 1 / 5 / 10 / 20 %, window K = 1024, band r = 256): one request of
+    Llama-3.1-8B geometry, recurring queries with a reuse gap of ~400 tokens and some skew inside a KV group, and
+    a per-step probability of a whole-group miss chosen to land on the KV budget.  Context, not target: the paper's
+    figures are from an H100 with an unstated batch."""
+    rows = []
+    period, pstd, W, B = 400, 30.0, 1024, 256
+    warm = period + int(4 * pstd) + 16
+    for ctx in (32768, 61440, 122880):
+        kv = None
+        for budget in (1, 5, 10, 20):
+            # a jump makes its KV group miss at that step and, one period later, once per head of the group
+            # (its 4 heads have different periods): 5 full reads per jump
+            base = (period + B) / ctx
+            f = max(0.0, (budget / 100.0 - base) / (1.0 - base))
+            cfg = wl_mod.WorkloadConfig(name=f"T_{ctx}_{budget}", batch=1, num_q_heads=32, num_kv_heads=8, context=ctx,
+                                        steps=warm + 2 * steps, window=W, band=B, threshold=0.5 * 128 ** 0.5, rho=0.0,
+                                        seed=7, period=period, period_std=pstd, query_noise=0.1, jump_prob=f / 5)
+            if kv is None:
+                wl = wl_mod.Workload(cfg, device="cuda:0")
+                kv = wl
+            else:
+                wl = wl_mod.Workload(cfg, device="cuda:0", queries_only=True)
+                wl.kv_pages, wl.block_table = kv.kv_pages, kv.block_table
+            mac = mb.MacAttention(num_q_heads=32, num_kv_heads=8, window=W, band=B, threshold=cfg.threshold,
+                                  max_kv_len=cfg.max_kv_len, max_slots=1)
+            out = torch.zeros((1, 32, 128), dtype=torch.float32, device="cuda:0")
+            stream = torch.cuda.current_stream().cuda_stream
+            inputs = [wl.next_step() for _ in range(cfg.steps)]
+            args = [mac.make_args(kv_lens=kl, q_rope=qr, kv_pages=wl.kv_pages, strides=wl.strides,
+                                  block_table=wl.block_table, out=out, slot_ids=wl.slot_ids, q_pre=qp)
+                    for (qp, qr, kl) in inputs]
+            for a in args[:warm]:
+                mac.decode_step(a, stream)
+            torch.cuda.synchronize()
+            mac.stats(reset=True)
+            t0 = time.perf_counter()
+            for a in args[warm:warm + steps]:
+                mac.decode_step(a, stream)
+            torch.cuda.synchronize()
+            mac_us = 1e6 * (time.perf_counter() - t0) / steps
+            st = mac.stats(reset=True)
+            t0 = time.perf_counter()
+            for a in args[warm:warm + steps]:
+                mac.full_decode(a, stream)
+            torch.cuda.synchronize()
+            full_us = 1e6 * (time.perf_counter() - t0) / steps
+            mb.mac_attn_set_timing(mac.ctx, True)
+            for a in args[warm + steps:warm + 2 * steps]:
+                mac.decode_step(a, stream)
+            k_us, k_n = mb.mac_attn_kernel_us(mac.ctx)
+            mac.close()
+            row = {"context": ctx, "kv_budget_pct": budget,
+                   "kv_read_pct": round(100.0 * st["kv_tokens_read"] / max(1, st["kv_tokens_full"]), 2),
+                   "hit_rate": round(st["hits"] / max(1, st["head_steps"]), 4),
+                   "mean_gap": round(st["sum_gap"] / max(1, st["hits"]), 1),
+                   "full_us": round(full_us, 1), "match_us": round(k_us[0] / k_n, 1),
+                   "attention_us": round(k_us[1] / k_n, 1), "merge_writeback_us": round(k_us[2] / k_n, 1),
+                   "overall_us": round(mac_us, 1), "speedup": round(full_us / mac_us, 2)}
+            rows.append(row)
+            log(f"[table] ctx {ctx:6d} KV {budget:2d}% (read {row['kv_read_pct']:5.2f}%, hit {100 * row['hit_rate']:5.1f}%, "
+                f"gap {row['mean_gap']:5.0f}): full {row['full_us']:6.1f} | match {row['match_us']:5.1f} attn "
+                f"{row['attention_us']:6.1f} merge+wb {row['merge_writeback_us']:5.1f} | overall {row['overall_us']:6.1f} us "
+                f"({row['speedup']:.2f}x)")
+        del kv
+        torch.cuda.empty_cache()
+    return rows
+
+
 def cpu_baseline(name: str, torch, wl_mod, sample_steps: int):
     """The fp64 oracle as it stands, timed on the host cores on the first `sample_steps` decode steps of the
     same workload (rings start empty, so the sample is self-consistent)."""
@@ -186,6 +256,9 @@ def main():
     ap.add_argument("--no-sweep", action="store_true", help="skip the other two (rho, threshold) pairs of C3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=12)
+    ap.add_argument("--paper-table", action="store_true",
+                    help="also run the analogue of the paper's fine-grained latency table (batch 1, 32K/60K/120K x KV "
+                         "budgets 1/5/10/20 %, K 1024, r 256) and add it to the JSON line as 'paper_table'")
     ap.add_argument("--graph", action="store_true",
                     help="also time the headline config replayed from one captured HIP graph (off by default: on this "
                          "ROCm a replay costs more than the three eager launches it replaces)")
@@ -258,6 +331,8 @@ def main():
         "paper_context": "paper (H100 SXM5, FlashInfer 0.2.7 baseline, batch unstated): full attention 234.2 us and "
                          "MAC 63.6-104.5 us at 120K; another machine, context not target",
     }
+    if a.paper_table:
+        line["paper_table"] = paper_table(torch, mb, wl_mod)
     if not a.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(a.config, torch, wl_mod, a.cpu_steps)
     print(json.dumps(line), flush=True)

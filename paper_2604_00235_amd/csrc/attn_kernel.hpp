@@ -39,7 +39,7 @@ namespace mac {
 
 struct AttnParams {
     const int32_t* kv_lens;      // [batch]
-    const int32_t* start;        // [batch*Hq] per-head start s_h (match kernel), or nullptr = all 0 (full decode)
+    MatchView mv;                // per-head match results (part == nullptr: full decode, every head starts at 0)
     const uint16_t* q_rope;      // [batch, Hq, 128] bf16
     const uint16_t* kv_pages;    // paged cache, bf16
     int64_t stride_page, stride_kv, stride_head, stride_tok;   // elements
@@ -91,12 +91,24 @@ __global__ __launch_bounds__(256, (HT == 1 ? 2 : 1)) void attn_kernel(const Attn
 
     // smallest and largest start among the group's heads (wave-uniform scalar loop)
     int gs = 0, gmax = 0;
-    if (p.start != nullptr) {
+    int my_start[HT];                                        // start of the head this lane holds in each head tile
+#pragma unroll
+    for (int ht = 0; ht < HT; ++ht) my_start[ht] = 0;
+    if (p.mv.part != nullptr) {
         gs = nb;
-        for (int i = 0; i < G; ++i) {
-            const int s = clampi(p.start[hbase + i], 0, nb);
-            gs = s < gs ? s : gs;
-            gmax = s > gmax ? s : gmax;
+        const int hpp = 64 / p.mv.n_split;                   // heads decided per pass of the wave
+        for (int base = 0; base < G; base += hpp) {
+            const int cnt = min(hpp, G - base);
+            const MatchDecision md = match_decide_wave(p.mv, hbase + base, cnt, l);
+            const int s = clampi(md.start, 0, nb);
+            for (int i = 0; i < cnt; ++i) {                  // lane i * n_split holds head base + i
+                const int si = __builtin_amdgcn_readlane(s, i * p.mv.n_split);
+                gs = min(gs, si);
+                gmax = max(gmax, si);
+#pragma unroll
+                for (int ht = 0; ht < HT; ++ht)
+                    if (base + i == ht * 16 + r16) my_start[ht] = si;
+            }
         }
     }
     int lo, hi;
@@ -120,9 +132,7 @@ __global__ __launch_bounds__(256, (HT == 1 ? 2 : 1)) void attn_kernel(const Attn
     for (int ht = 0; ht < HT; ++ht) {
         const int hh = ht * 16 + r16;
         const bool valid = hh < G;
-        int s = lo;
-        if (valid && p.start != nullptr) s = max(lo, clampi(p.start[hbase + hh], 0, nb));
-        hstart[ht] = s;
+        hstart[ht] = valid ? max(lo, my_start[ht]) : lo;
         const uint16_t* qp = p.q_rope + (int64_t)(hbase + (valid ? hh : 0)) * kHeadDim + 8 * kg;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {

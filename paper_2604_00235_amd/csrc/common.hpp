@@ -29,4 +29,61 @@ __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_ex
 
 __device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
+// Result of scanning one slice of a head's query-ring window: the nearest entry of the slice.
+struct MatchPartial {
+    double d2;      // squared distance, +inf if the slice has no candidate
+    int32_t np;     // length n_p at which the entry was created, -1 if none
+    int32_t j;      // ring entry index, -1 if none
+};
+
+// lexicographic order of candidates: smaller distance first, then the more recent entry
+__device__ __forceinline__ bool better(double d2, int np, double od2, int onp) {
+    return d2 < od2 || (d2 == od2 && np > onp);
+}
+
+// Where the per-slice results of the match kernel live and how to turn them into the decision.
+struct MatchView {
+    const MatchPartial* part;   // [batch*Hq, n_split]; nullptr = no matching (full decode)
+    int32_t n_split;
+    int32_t band;               // B
+    double T2;                  // (double)T * (double)T
+};
+
+struct MatchDecision {
+    double d2;      // nearest squared distance over the whole window (+inf if it is empty)
+    int32_t np;     // matched n_p, or -1 on a miss
+    int32_t j;      // matched ring entry, or -1
+    int32_t start;  // first key this head has to recompute: max(0, n_p - B) on a hit, 0 on a miss
+};
+
+// Final reduction over the slices and threshold test (paper Eq. (accept); Sec. 4.2 K1 "final reducer").
+// Every consumer (attention kernel, merge kernel) evaluates it itself from the same slice results, so the
+// decision needs no extra kernel and no inter-work-group synchronisation.
+//
+// One wave decides up to 64 / n_split consecutive heads at once: lane l holds slice l % n_split of head
+// bh0 + l / n_split (n_split is a power of two <= 64), one coalesced 16-byte load per lane, then a butterfly
+// inside each n_split-lane segment.  On return every lane of a segment holds its head's decision; lanes of
+// segments >= cnt hold a miss.  Must be called by all 64 lanes of the wave.
+__device__ __forceinline__ MatchDecision match_decide_wave(const MatchView& mv, int bh0, int cnt, int lane) {
+    MatchDecision r{INFINITY, -1, -1, 0};
+    if (mv.part == nullptr) return r;
+    const int S = mv.n_split;
+    const int seg = lane / S;
+    MatchPartial c{INFINITY, -1, -1};
+    if (seg < cnt) c = mv.part[(int64_t)bh0 * S + lane];
+    for (int off = S >> 1; off > 0; off >>= 1) {
+        const double od2 = __shfl_xor(c.d2, off);
+        const int onp = __shfl_xor(c.np, off);
+        const int oj = __shfl_xor(c.j, off);
+        if (better(od2, onp, c.d2, c.np)) { c.d2 = od2; c.np = onp; c.j = oj; }
+    }
+    r.d2 = c.d2;
+    if (c.np >= 1 && c.d2 < mv.T2) {
+        r.np = c.np;
+        r.j = c.j;
+        r.start = c.np - mv.band > 0 ? c.np - mv.band : 0;
+    }
+    return r;
+}
+
 }  // namespace mac

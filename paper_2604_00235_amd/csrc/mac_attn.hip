@@ -38,7 +38,7 @@ int default_chunk(int64_t groups, int64_t max_kv_len) {
 }
 
 struct Layout {            // derived sizes, pure host arithmetic
-    int G, chunk, n_mid_slots, n_band_slots, n_slots, page_shift;
+    int G, chunk, n_mid_slots, n_band_slots, n_slots, page_shift, max_split;
     int64_t ring_q_bytes, ring_O_bytes, ring_lse_bytes, ring_npos_bytes;
     int64_t part_O_bytes, part_lse_bytes, match_bytes, rect_bytes, stats_bytes;
     int64_t total() const {
@@ -80,7 +80,8 @@ int validate_config(const mac_attn_config* c, Layout* L) {
     L->ring_npos_bytes = (int64_t)c->max_slots * c->window * 4;
     L->part_O_bytes = bh * L->n_slots * mac::kHeadDim * 4;
     L->part_lse_bytes = bh * L->n_slots * 4;
-    L->match_bytes = bh * 3 * 4;
+    L->max_split = 64;                                      // window slices per head (power of two)
+    L->match_bytes = bh * L->max_split * (int64_t)sizeof(mac::MatchPartial);
     L->rect_bytes = bh * (mac::kHeadDim + 1) * 4;
     L->stats_bytes = bh * 3 * 8 + (int64_t)c->max_batch * c->num_kv_heads * 2 * 8 + 2 * 8;
     return MAC_ATTN_OK;
@@ -106,7 +107,8 @@ struct mac_attn_ctx {
     // per-step scratch
     float* part_O = nullptr;
     float* part_lse = nullptr;
-    int32_t* m_np = nullptr;      // [bh] x3: n_p, entry, start
+    mac::MatchPartial* m_part = nullptr;   // [bh, n_split] nearest entry per window slice (match kernel)
+    int32_t n_split = 1;                   // slices used by the current / last decode_step
     float* rect = nullptr;        // [bh*128] rows then [bh] lse
     // counters
     unsigned long long* stats = nullptr;
@@ -188,12 +190,21 @@ struct Timer {          // brackets the kernels of one call with events when tim
     }
 };
 
+mac::MatchView match_view(const mac_attn_ctx* ctx, bool mac_mode) {
+    mac::MatchView mv;
+    mv.part = mac_mode ? ctx->m_part : nullptr;
+    mv.n_split = ctx->n_split;
+    mv.band = ctx->cfg.band;
+    mv.T2 = ctx->T2;
+    return mv;
+}
+
 int launch_attention(mac_attn_ctx* ctx, const mac_attn_step_args* a, bool mac_mode, hipStream_t stream) {
     const mac_attn_config& c = ctx->cfg;
     const Layout& L = ctx->L;
     mac::AttnParams p;
     p.kv_lens = a->kv_lens;
-    p.start = mac_mode ? ctx->m_np + 2 * (int64_t)c.max_batch * c.num_q_heads : nullptr;
+    p.mv = match_view(ctx, mac_mode);
     p.q_rope = static_cast<const uint16_t*>(a->q_rope);
     p.kv_pages = static_cast<const uint16_t*>(a->kv_pages);
     p.stride_page = a->stride_page;
@@ -230,8 +241,12 @@ mac::MergeParams merge_params(mac_attn_ctx* ctx, const mac_attn_step_args* a, bo
     mac::MergeParams p;
     p.kv_lens = a->kv_lens;
     p.slot_ids = mac_mode ? a->slot_ids : nullptr;
-    p.m_j = mac_mode ? ctx->m_np + bh : nullptr;
-    p.m_start = mac_mode ? ctx->m_np + 2 * bh : nullptr;
+    p.mv = match_view(ctx, mac_mode);
+    p.out_match_pos = mac_mode ? a->match_pos : nullptr;
+    p.out_match_d2 = mac_mode ? a->match_d2 : nullptr;
+    p.st_hits = mac_mode ? ctx->stats : nullptr;
+    p.st_gap = mac_mode ? ctx->stats + bh : nullptr;
+    p.st_skip = mac_mode ? reinterpret_cast<double*>(ctx->stats + 2 * bh) : nullptr;
     p.ring_O = ctx->ring_O;
     p.ring_lse = ctx->ring_lse;
     p.part_O = ctx->part_O;
@@ -322,7 +337,7 @@ void mac_attn_destroy(mac_attn_ctx* ctx) {
     if (hipGetDevice(&cur) == hipSuccess && cur != ctx->cfg.device) (void)hipSetDevice(ctx->cfg.device);
     (void)hipDeviceSynchronize();
     void* bufs[] = {ctx->ring_q, ctx->ring_O, ctx->ring_lse, ctx->ring_npos, ctx->part_O, ctx->part_lse,
-                    ctx->m_np, ctx->rect, ctx->stats};
+                    ctx->m_part, ctx->rect, ctx->stats};
     for (void* b : bufs)
         if (b != nullptr) (void)hipFree(b);
     for (TimedCall& t : ctx->timed)
@@ -353,7 +368,7 @@ int mac_attn_init(const mac_attn_config* cfg, mac_attn_ctx** out_ctx) {
         {reinterpret_cast<void**>(&ctx->ring_npos), L.ring_npos_bytes, true},
         {reinterpret_cast<void**>(&ctx->part_O), L.part_O_bytes, false},
         {reinterpret_cast<void**>(&ctx->part_lse), L.part_lse_bytes, false},
-        {reinterpret_cast<void**>(&ctx->m_np), L.match_bytes, true},
+        {reinterpret_cast<void**>(&ctx->m_part), L.match_bytes, true},
         {reinterpret_cast<void**>(&ctx->rect), L.rect_bytes, true},
         {reinterpret_cast<void**>(&ctx->stats), L.stats_bytes, true},
     };
@@ -413,21 +428,21 @@ int mac_attn_decode_step(mac_attn_ctx* ctx, const mac_attn_step_args* args, void
         p.q_pre = static_cast<const uint16_t*>(args->q_pre);
         p.ring_q = ctx->ring_q;
         p.ring_npos = ctx->ring_npos;
-        p.m_np = ctx->m_np;
-        p.m_j = ctx->m_np + bh;
-        p.m_start = ctx->m_np + 2 * bh;
-        p.out_match_pos = args->match_pos;
-        p.out_match_d2 = args->match_d2;
-        p.st_hits = ctx->stats;
-        p.st_gap = ctx->stats + bh;
-        p.st_skip = reinterpret_cast<double*>(ctx->stats + 2 * bh);
+        // window slices: a power of two, enough work-groups to fill the chip at small batch, and at least one
+        // 64-row pass each
+        const int64_t heads = (int64_t)args->batch * c.num_q_heads;
+        int split = 1;
+        while (split * 2 <= 64 && split * heads < 512 && (c.window + split * 2 - 1) / (split * 2) >= 64) split *= 2;
+        const int rows = (((c.window + split - 1) / split + 63) / 64) * 64;
+        ctx->n_split = split;
+        p.part = ctx->m_part;
         p.st_steps = ctx->stats + 3 * bh + 2 * (int64_t)c.max_batch * c.num_kv_heads;
         p.Hq = c.num_q_heads;
         p.W = c.window;
-        p.B = c.band;
         p.max_kv_len = c.max_kv_len;
-        p.T2 = ctx->T2;
-        dim3 grid(c.num_q_heads, args->batch), block(mac::kMatchThreads);
+        p.n_split = split;
+        p.rows_per_split = rows;
+        dim3 grid(c.num_q_heads, args->batch, split), block(mac::kMatchThreads);
         hipLaunchKernelGGL(mac::match_kernel, grid, block, 0, stream, p);
         HIP_TRY(hipGetLastError());
         t.done(0);

@@ -5,15 +5,20 @@
 // For request b (ring set slot_ids[b]) and query head h, over the ring entries created at lengths
 // n_p in [max(1, n - W), n - 1]:  d2_j = sum_i (q_i - ring_j,i)^2,  j* = argmin (ties -> larger n_p),
 // hit iff d2_j* < T^2.  On a hit the head's fresh range starts at s_h = max(0, n_p - B), else at 0.
+// This kernel produces the nearest entry of each window slice; match_decide_wave() finishes the argmin and applies
+// the threshold.
 //
 // Arithmetic.  The decision has to agree with an fp64 evaluation of the exact bf16 inputs, so each
 // difference is formed in fp64 (exact) and squared/accumulated with fp64 FMAs; the result is within a few
 // ulp(fp64) of the true real value, so decisions differ from any other fp64 evaluation only for candidates
 // that tie to ~1e-15 relative.  v_fma_f64 is full rate on this chip and the kernel stays bandwidth-bound.
 //
-// Mapping.  One work-group (256 threads = 4 waves, 64 ring rows per pass) per (head, request); measured at
-// 134 MB of ring (batch 32 x 64 heads x 256 entries) 256-thread groups stream ~1.9x faster than 1024-thread
-// ones, and within 1 us of them on small batches.  The head's window is contiguous in the ring
+// Mapping.  One work-group (256 threads = 4 waves, 64 ring rows per pass) per (head, request, window slice).
+// The host cuts the window into slices so that a small batch still yields ~512 work-groups (a single group
+// scanning a 1024-entry window needs 16 dependent passes, ~17 us; 16 slices take one pass each); the slices'
+// results are reduced and thresholded by the consumers (match_decide_wave).  Measured at 134 MB of ring (batch 32 x
+// 64 heads x 256 entries) 256-thread groups stream ~1.9x faster than 1024-thread ones.
+// The head's window is contiguous in the ring
 // ([slot][head][entry][d]).  A quad of 4 lanes owns one 256-byte row per iteration, lane `sub` reading the
 // 16-byte chunks sub, sub+4, sub+8, sub+12, so each load instruction of a wave fetches 16 rows x 64
 // contiguous bytes.  Rows are loaded without waiting for their n_p tag (the ring memory always exists; an
@@ -31,31 +36,21 @@ struct MatchParams {
     const uint16_t* q_pre;       // [batch, Hq, 128] bf16
     const uint16_t* ring_q;      // [slots, Hq, W, 128] bf16
     const int32_t* ring_npos;    // [slots, W]; 0 = empty entry
-    int32_t* m_np;               // [batch*Hq] matched n_p or -1
-    int32_t* m_j;                // [batch*Hq] matched ring entry or -1
-    int32_t* m_start;            // [batch*Hq] s_h
-    int32_t* out_match_pos;      // optional caller outputs
-    double* out_match_d2;
-    unsigned long long* st_hits; // per (b, h) accumulators, touched only by that (b, h)'s work-group
-    unsigned long long* st_gap;
-    double* st_skip;
+    MatchPartial* part;          // [batch*Hq, n_split] nearest entry of each window slice
     unsigned long long* st_steps;   // [2]: decode steps, head-steps (device-side so that graph replays count too)
-    int32_t Hq, W, B, max_kv_len;
-    double T2;                   // (double)T * (double)T
+    int32_t Hq, W, max_kv_len;
+    int32_t n_split;             // window slices per head = gridDim.z
+    int32_t rows_per_split;      // multiple of 64
 };
 
 __device__ __forceinline__ double bf16_lo_to_f64(uint32_t pair) { return (double)bits_to_float(pair << 16); }
 __device__ __forceinline__ double bf16_hi_to_f64(uint32_t pair) { return (double)bits_to_float(pair & 0xffff0000u); }
 
-__device__ __forceinline__ bool better(double d2, int np, double od2, int onp) {
-    return d2 < od2 || (d2 == od2 && np > onp);
-}
-
 constexpr int kMatchThreads = 256;
 constexpr int kMatchRowsPerPass = kMatchThreads / 4;
 
 __global__ __launch_bounds__(kMatchThreads) void match_kernel(const MatchParams p) {
-    const int h = blockIdx.x, b = blockIdx.y;
+    const int h = blockIdx.x, b = blockIdx.y, sp = blockIdx.z;
     const int tid = threadIdx.x, quad = tid >> 2, sub = tid & 3;
     const int bh = b * p.Hq + h;
     const int n = clampi(p.kv_lens[b], 0, p.max_kv_len);
@@ -82,7 +77,8 @@ __global__ __launch_bounds__(kMatchThreads) void match_kernel(const MatchParams 
 
     double best_d2 = INFINITY;
     int best_np = -1, best_j = -1;
-    for (int j0 = 0; j0 < W; j0 += kMatchRowsPerPass) {
+    const int j_begin = sp * p.rows_per_split, j_end = min(W, j_begin + p.rows_per_split);
+    for (int j0 = j_begin; j0 < j_end; j0 += kMatchRowsPerPass) {
         const int j = j0 + quad;
         const int jc = j < W ? j : W - 1;                      // keep the speculative loads inside the ring
         const int np = npos[jc];
@@ -90,7 +86,7 @@ __global__ __launch_bounds__(kMatchThreads) void match_kernel(const MatchParams 
         u32x4 v[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) v[i] = *reinterpret_cast<const u32x4*>(rp + 32 * i);
-        const bool valid = j < W && np >= np_lo && np <= np_hi;
+        const bool valid = j < j_end && np >= np_lo && np <= np_hi;
         double s0 = 0.0, s1 = 0.0;
         {
 #pragma unroll
@@ -123,24 +119,13 @@ __global__ __launch_bounds__(kMatchThreads) void match_kernel(const MatchParams 
     if ((tid & 63) == 0) { s_d2[tid >> 6] = best_d2; s_np[tid >> 6] = best_np; s_j[tid >> 6] = best_j; }
     __syncthreads();
     if (tid == 0) {
-        if (h == 0 && b == 0) {
-            p.st_steps[0] += 1ull;
-            p.st_steps[1] += (unsigned long long)gridDim.x * gridDim.y;
+        if (h == 0 && b == 0 && sp == 0) {
+            atomicAdd(&p.st_steps[0], 1ull);
+            atomicAdd(&p.st_steps[1], (unsigned long long)gridDim.x * gridDim.y);
         }
         for (int w = 1; w < kWaves; ++w)
             if (better(s_d2[w], s_np[w], best_d2, best_np)) { best_d2 = s_d2[w]; best_np = s_np[w]; best_j = s_j[w]; }
-        const bool hit = best_np >= 1 && best_d2 < p.T2;
-        const int s = hit ? max(best_np - p.B, 0) : 0;
-        p.m_np[bh] = hit ? best_np : -1;
-        p.m_j[bh] = hit ? best_j : -1;
-        p.m_start[bh] = s;
-        if (p.out_match_pos) p.out_match_pos[bh] = hit ? best_np : -1;
-        if (p.out_match_d2) p.out_match_d2[bh] = best_d2;
-        if (hit) {
-            p.st_hits[bh] += 1ull;
-            p.st_gap[bh] += (unsigned long long)(n - best_np);
-            p.st_skip[bh] += (double)s / (double)n;
-        }
+        p.part[(int64_t)bh * p.n_split + sp] = MatchPartial{best_d2, best_np, best_j};
     }
 }
 

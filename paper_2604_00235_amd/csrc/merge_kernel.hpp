@@ -37,8 +37,12 @@ struct WritebackParams {
 struct MergeParams {
     const int32_t* kv_lens;
     const int32_t* slot_ids;     // null for full decode
-    const int32_t* m_j;          // [batch*Hq] matched ring entry or -1; null for full decode
-    const int32_t* m_start;      // [batch*Hq] s_h; null for full decode (all 0)
+    MatchView mv;                // per-head match results; part == nullptr for full decode
+    int32_t* out_match_pos;      // optional caller outputs [batch*Hq] (MAC mode)
+    double* out_match_d2;
+    unsigned long long* st_hits; // per (b, h) accumulators, touched only by that (b, h)'s work-group; null for full decode
+    unsigned long long* st_gap;
+    double* st_skip;
     const float* ring_O;         // [slots, Hq, W, 128]
     const float* ring_lse;       // [slots, Hq, W]
     const float* part_O;         // [batch*Hq, n_slots, 128]
@@ -53,26 +57,31 @@ struct MergeParams {
 };
 
 // 256 threads per (request, head).  Thread (c = tid/32, q = tid%32) accumulates the partials
-// x = first + c, first + c + 8, ... for the four output columns 4q..4q+3; the 8 partial sums are added in a fixed
-// order through LDS, so the result is bitwise reproducible.  Weights are taken relative to the maximum LSE of
-// each part (rect part: prefix + mid chunks; band part), found in a first pass over the LSE scalars.
+// x = first + c, first + c + 8, ... for the four output columns 4q..4q+3 in a single pass, with weights relative
+// to the largest LSE that lane has seen; the 8 lane summaries are combined in a fixed order through LDS, so the
+// result is bitwise reproducible.  Two summaries are kept: the rect part (prefix + mid chunks) and the band part.
 constexpr int kMergeThreads = 256;
 constexpr int kMergeLanes = 8;      // chunks summed in parallel
 
 struct MergeSmem {
-    float red[4];
-    float acc[2][kMergeLanes][kHeadDim];
-    float z[2][kMergeLanes];
+    float acc[2][kMergeLanes][kHeadDim];   // [rect part | band part][chunk lane][column]
+    float m[2][kMergeLanes];               // running maximum of the LSEs each lane has seen
+    float z[2][kMergeLanes];               // sum of weights relative to that maximum
 };
 
-__device__ __forceinline__ float block_max_256(float v, float* s_red) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
-    __syncthreads();                              // s_red may still be read from a previous call
-    if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = v;
-    __syncthreads();
-    return fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
-}
+// One chunk lane's running summary of four output columns: weights relative to the largest LSE seen so far.
+struct LaneMerge {
+    float M = -INFINITY, Z = 0.f;
+    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+    __device__ __forceinline__ void add(const f32x4 o, float L) {
+        if (L == -INFINITY) return;                // empty summary: identity
+        const float Mn = fmaxf(M, L);
+        const float a = expf(M - Mn), w = expf(L - Mn);      // exp(-inf) = 0 on the first add
+        acc = acc * a + o * w;
+        Z = Z * a + w;
+        M = Mn;
+    }
+};
 
 // Ring append of one head by threads d < 128 (values of the rectified summary passed in registers).
 __device__ __forceinline__ void writeback_head(const WritebackParams& p, int b, int h, int d, float rect_o, float rect_l) {
@@ -100,64 +109,46 @@ __device__ __forceinline__ void merge_head(const MergeParams& p, const Writeback
     const int n = clampi(p.kv_lens[b], 0, p.max_kv_len);
     const int nb = n - p.band > 0 ? n - p.band : 0;
     const int C = p.chunk;
-    const int s = p.m_start ? clampi(p.m_start[bh], 0, nb) : 0;
+    MatchDecision md = match_decide_wave(p.mv, bh, 1, tid & 63);           // every wave decides this head itself;
+    md.d2 = __shfl(md.d2, 0);                                              // lane 0 holds it, the rest take it over
+    md.np = __shfl(md.np, 0);
+    md.j = __shfl(md.j, 0);
+    md.start = __shfl(md.start, 0);
+    const int s = clampi(md.start, 0, nb);
     const int64_t pbase = (int64_t)bh * p.n_slots;
 
     // chunks of this head: mid slots [x0, x1) (those with a non-empty part of [s, nb)), band slots [y0, y1)
     const int x0 = s / C, x1 = (nb + C - 1) / C;
     const int y0 = p.n_mid_slots, y1 = nb < n ? p.n_mid_slots + ((n + C - 1) / C - nb / C) : p.n_mid_slots;
     int64_t pre = -1;                                    // ring entry of the reused prefix, if any
-    if (p.m_j != nullptr) {
-        const int j = p.m_j[bh];
-        if (j >= 0) pre = ((int64_t)p.slot_ids[b] * p.Hq + h) * p.W + j;
-    }
+    if (md.j >= 0) pre = ((int64_t)p.slot_ids[b] * p.Hq + h) * p.W + md.j;
 
-    // pass 1: maxima of the LSE scalars
-    float m_r = -INFINITY, m_b = -INFINITY;
-    for (int x = x0 + tid; x < x1; x += kMergeThreads)
-        if (max(s, x * C) < min(nb, (x + 1) * C)) m_r = fmaxf(m_r, p.part_lse[pbase + x]);
-    if (tid == 0 && pre >= 0) m_r = fmaxf(m_r, p.ring_lse[pre]);
-    for (int y = y0 + tid; y < y1; y += kMergeThreads) m_b = fmaxf(m_b, p.part_lse[pbase + y]);
-    const float M_r = block_max_256(m_r, sm.red);
-    const float M_b = block_max_256(m_b, sm.red);
-
-    // pass 2: weighted sums; empty summaries (LSE = -inf) get weight 0
-    f32x4 a_r = f32x4{0.f, 0.f, 0.f, 0.f}, a_b = f32x4{0.f, 0.f, 0.f, 0.f};
-    float z_r = 0.f, z_b = 0.f;
-    if (M_r != -INFINITY) {
-        if (c == 0 && pre >= 0) {
-            const float wgt = expf(p.ring_lse[pre] - M_r);
-            const f32x4 o = *reinterpret_cast<const f32x4*>(p.ring_O + pre * kHeadDim + 4 * q);
-            a_r += o * wgt;
-            z_r += wgt;
-        }
-        for (int x = x0 + c; x < x1; x += kMergeLanes) {
-            if (max(s, x * C) >= min(nb, (x + 1) * C)) continue;      // nothing of this head in the chunk
-            const float wgt = expf(p.part_lse[pbase + x] - M_r);
-            const f32x4 o = *reinterpret_cast<const f32x4*>(p.part_O + (pbase + x) * kHeadDim + 4 * q);
-            a_r += o * wgt;
-            z_r += wgt;
-        }
+    // single pass over this lane's chunks (all loads are independent of one another)
+    LaneMerge r, bnd;
+    if (c == 0 && pre >= 0)
+        r.add(*reinterpret_cast<const f32x4*>(p.ring_O + pre * kHeadDim + 4 * q), p.ring_lse[pre]);
+    for (int x = x0 + c; x < x1; x += kMergeLanes) {
+        if (max(s, x * C) >= min(nb, (x + 1) * C)) continue;          // nothing of this head in the chunk
+        r.add(*reinterpret_cast<const f32x4*>(p.part_O + (pbase + x) * kHeadDim + 4 * q), p.part_lse[pbase + x]);
     }
-    if (M_b != -INFINITY) {
-        for (int y = y0 + c; y < y1; y += kMergeLanes) {
-            const float wgt = expf(p.part_lse[pbase + y] - M_b);
-            const f32x4 o = *reinterpret_cast<const f32x4*>(p.part_O + (pbase + y) * kHeadDim + 4 * q);
-            a_b += o * wgt;
-            z_b += wgt;
-        }
-    }
-    *reinterpret_cast<f32x4*>(&sm.acc[0][c][4 * q]) = a_r;
-    *reinterpret_cast<f32x4*>(&sm.acc[1][c][4 * q]) = a_b;
-    if (q == 0) { sm.z[0][c] = z_r; sm.z[1][c] = z_b; }
+    for (int y = y0 + c; y < y1; y += kMergeLanes)
+        bnd.add(*reinterpret_cast<const f32x4*>(p.part_O + (pbase + y) * kHeadDim + 4 * q), p.part_lse[pbase + y]);
+    *reinterpret_cast<f32x4*>(&sm.acc[0][c][4 * q]) = r.acc;
+    *reinterpret_cast<f32x4*>(&sm.acc[1][c][4 * q]) = bnd.acc;
+    if (q == 0) { sm.m[0][c] = r.M; sm.z[0][c] = r.Z; sm.m[1][c] = bnd.M; sm.z[1][c] = bnd.Z; }
     __syncthreads();                                     // also orders the prefix reads before the ring write below
     if (tid < kHeadDim) {
         const int d = tid;
+        float M_r = -INFINITY, M_b = -INFINITY;
+#pragma unroll
+        for (int k = 0; k < kMergeLanes; ++k) { M_r = fmaxf(M_r, sm.m[0][k]); M_b = fmaxf(M_b, sm.m[1][k]); }
         float S_r = 0.f, Z_r = 0.f, S_b = 0.f, Z_b = 0.f;
 #pragma unroll
         for (int k = 0; k < kMergeLanes; ++k) {
-            S_r += sm.acc[0][k][d]; Z_r += sm.z[0][k];
-            S_b += sm.acc[1][k][d]; Z_b += sm.z[1][k];
+            const float fr = sm.z[0][k] > 0.f ? expf(sm.m[0][k] - M_r) : 0.f;     // an empty lane has m = -inf
+            const float fb = sm.z[1][k] > 0.f ? expf(sm.m[1][k] - M_b) : 0.f;
+            S_r += sm.acc[0][k][d] * fr; Z_r += sm.z[0][k] * fr;
+            S_b += sm.acc[1][k][d] * fb; Z_b += sm.z[1][k] * fb;
         }
         // rect = prefix (+) mid chunks: this step's total without the last-B band
         const float rect_o = Z_r > 0.f ? S_r / Z_r : 0.f;
@@ -180,14 +171,35 @@ __device__ __forceinline__ void merge_head(const MergeParams& p, const Writeback
         if (do_wb) writeback_head(wb, b, h, d, rect_o, rect_l);
     }
 
-    // KV tokens streamed by this step for the KV group (read once per group from its smallest start)
-    if (p.st_read != nullptr && tid == 0 && (h % p.G) == 0) {
-        int gs = nb;
-        for (int i = 0; i < p.G; ++i) gs = min(gs, clampi(p.m_start[bh + i], 0, nb));
-        const int bg = bh / p.G;
-        p.st_read[bg] += (unsigned long long)(n - gs);
-        p.st_full[bg] += (unsigned long long)n;
+    // The decision, for the caller and the counters (acceptance, reuse gap, skipped-prefix fraction).
+    if (p.mv.part != nullptr && tid < 64) {
+        if (tid == 0) {
+            if (p.out_match_pos) p.out_match_pos[bh] = md.np;
+            if (p.out_match_d2) p.out_match_d2[bh] = md.d2;
+            if (md.np >= 0) {          // one writer per address and step: the atomics only make the adds fire-and-forget
+                atomicAdd(&p.st_hits[bh], 1ull);
+                atomicAdd(&p.st_gap[bh], (unsigned long long)(n - md.np));
+                atomicAdd(&p.st_skip[bh], (double)md.start / (double)n);
+            }
+        }
+        // KV tokens streamed by this step for the KV group (read once per group from its smallest start)
+        if ((h % p.G) == 0) {
+            int gs = nb;
+            const int hpp = 64 / p.mv.n_split;
+            for (int base = 0; base < p.G; base += hpp) {
+                const int cnt = min(hpp, p.G - base);
+                const MatchDecision g = match_decide_wave(p.mv, bh + base, cnt, tid);
+                const int gstart = clampi(g.start, 0, nb);
+                for (int i = 0; i < cnt; ++i) gs = min(gs, __builtin_amdgcn_readlane(gstart, i * p.mv.n_split));
+            }
+            if (tid == 0) {
+                const int bg = bh / p.G;
+                atomicAdd(&p.st_read[bg], (unsigned long long)(n - gs));
+                atomicAdd(&p.st_full[bg], (unsigned long long)n);
+            }
+        }
     }
+
     __syncthreads();                                     // shared memory is reused by the next head
 }
 

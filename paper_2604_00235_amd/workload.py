@@ -47,6 +47,15 @@ class WorkloadConfig:
     regime_shift_every: int = 0     # >0: add a fresh random mean every this many steps
     use_rope: bool = True
     ragged: int = 0                 # >0: request b is `ragged * b` tokens shorter than request 0
+    # second query model ("recurring queries"): the pre-RoPE query of head h repeats a random base sequence with
+    # period P_h = period + N(0, period_std) (fixed per head) plus per-step noise, so its nearest neighbour in the
+    # window lies one period back (reuse gaps of hundreds of tokens with some skew inside a KV group, as the
+    # paper's match-position table reports); with probability jump_prob per step a whole KV group gets fresh
+    # random queries instead (a miss for the group).  period = 0 selects the AR(1) model above.
+    period: int = 0
+    period_std: float = 0.0
+    query_noise: float = 0.1
+    jump_prob: float = 0.0
 
     @property
     def group(self) -> int:
@@ -170,6 +179,12 @@ class Workload:
         self._x = torch.randn((cfg.batch, cfg.num_q_heads, d), generator=gq, device=dev, dtype=torch.float32)
         self._mu = torch.zeros_like(self._x)
         self._step = 0
+        if cfg.period > 0:
+            pmax = int(cfg.period + 4 * cfg.period_std) + 1
+            offs = torch.round(cfg.period_std * torch.randn((cfg.batch, cfg.num_q_heads), generator=gq, device=dev))
+            self._period = torch.clamp(cfg.period + offs, 2, pmax).to(torch.int64)           # [batch, Hq]
+            self._base = torch.randn((cfg.batch, cfg.num_q_heads, pmax, d), generator=gq, device=dev,
+                                     dtype=torch.float32)
 
     # ------------------------------------------------------------------ queries
     def next_step(self) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
@@ -180,12 +195,22 @@ class Workload:
         s = self._step
         if s >= cfg.steps:
             raise StopIteration
-        if s > 0:
+        if cfg.period > 0:
             noise = torch.randn(self._x.shape, generator=self._gen, device=self.device, dtype=torch.float32)
-            self._x = cfg.rho * self._x + math.sqrt(1.0 - cfg.rho * cfg.rho) * noise
-        if cfg.regime_shift_every > 0 and s % cfg.regime_shift_every == 0:
-            self._mu = torch.randn(self._x.shape, generator=self._gen, device=self.device, dtype=torch.float32)
-        x = self._x + self._mu if cfg.regime_shift_every > 0 else self._x
+            phase = (s % self._period).view(cfg.batch, cfg.num_q_heads, 1, 1).expand(-1, -1, 1, cfg.head_dim)
+            x = torch.gather(self._base, 2, phase).squeeze(2) + cfg.query_noise * noise
+            if cfg.jump_prob > 0:
+                u = torch.rand((cfg.batch, cfg.num_kv_heads), generator=self._gen, device=self.device)
+                fresh = torch.randn(self._x.shape, generator=self._gen, device=self.device, dtype=torch.float32)
+                jump = (u < cfg.jump_prob).repeat_interleave(cfg.group, dim=1).unsqueeze(-1)
+                x = torch.where(jump, fresh, x)
+        else:
+            if s > 0:
+                noise = torch.randn(self._x.shape, generator=self._gen, device=self.device, dtype=torch.float32)
+                self._x = cfg.rho * self._x + math.sqrt(1.0 - cfg.rho * cfg.rho) * noise
+            if cfg.regime_shift_every > 0 and s % cfg.regime_shift_every == 0:
+                self._mu = torch.randn(self._x.shape, generator=self._gen, device=self.device, dtype=torch.float32)
+            x = self._x + self._mu if cfg.regime_shift_every > 0 else self._x
         n = cfg.context + s + 1
         kv_lens = torch.full((cfg.batch,), n, device=self.device, dtype=torch.int32)
         if cfg.ragged > 0:

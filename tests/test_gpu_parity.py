@@ -136,3 +136,17 @@ def test_error_paths_on_device():
     with pytest.raises(mb.MacAttnError):
         mb.mac_attn_full_decode(mac.ctx, args)           # batch > max_batch
     mac.close()
+
+
+@pytest.mark.parametrize("hq,hkv,window,batch", [(32, 8, 1024, 1), (16, 2, 1024, 1), (32, 1, 256, 2), (8, 2, 200, 3)])
+def test_recurring_queries_large_window_split_match(hq, hkv, window, batch):
+    """Second query model (reuse gaps of tens to hundreds of tokens with skew inside a KV group, whole-group misses):
+    exercises large windows, where the matcher cuts the window into slices (16 slices at W=1024 and batch 1) and
+    the consumers finish the argmin, including groups that need more than one wave pass (G x slices > 64) and a
+    window that is not a multiple of the slice size."""
+    from tests.gpu_harness import run_parity
+    cfg = WorkloadConfig(name=f"recur{hq}_{hkv}_{window}", batch=batch, num_q_heads=hq, num_kv_heads=hkv, context=1500,
+                         steps=150, window=window, band=48, threshold=T_DEFAULT, rho=0.0, seed=21, period=40,
+                         period_std=4.0, query_noise=0.1, jump_prob=0.05, ragged=11 if batch > 1 else 0)
+    r = run_parity(cfg, chunk_tokens=256, check_full=False, check_ring_every=16)
+    assert 0.3 * r["head_steps"] < r["hits"] < r["head_steps"]
