@@ -88,8 +88,12 @@ __global__ __launch_bounds__(256, (HT == 1 ? 2 : 1)) void attn_kernel(const Attn
     const int n = clampi(p.kv_lens[b], 0, p.max_kv_len);
     const int nb = n - p.band > 0 ? n - p.band : 0;          // the band is [nb, n)
     const int hbase = b * p.Hq + g * G;
+    if (!is_mid) {                                           // a band chunk's position needs kv_len only
+        chunk_tile0 = (nb / C + (x - p.n_mid_slots)) * tiles_per_chunk;
+        fetch_pid();
+    }
 
-    // smallest and largest start among the group's heads (wave-uniform scalar loop)
+    // smallest and largest start among the group's heads
     int gs = 0, gmax = 0;
     int my_start[HT];                                        // start of the head this lane holds in each head tile
 #pragma unroll
@@ -117,12 +121,10 @@ __global__ __launch_bounds__(256, (HT == 1 ? 2 : 1)) void attn_kernel(const Attn
         hi = min(nb, (x + 1) * C);
     } else {
         const int c = nb / C + (x - p.n_mid_slots);
-        chunk_tile0 = c * tiles_per_chunk;
         lo = max(nb, c * C);
         hi = min(n, (c + 1) * C);
     }
     if (lo >= hi) return;
-    if (!is_mid) fetch_pid();
     const int maxstart = max(gmax, lo);                       // tiles at or above it need no start mask
 
     // per-lane head data for each head tile: first token this head attends to, and its query (B operand)

@@ -68,7 +68,7 @@ __device__ __forceinline__ MatchDecision match_decide_wave(const MatchView& mv, 
     MatchDecision r{INFINITY, -1, -1, 0};
     if (mv.part == nullptr) return r;
     const int S = mv.n_split;
-    const int seg = lane / S;
+    const int seg = lane >> (31 - __builtin_clz(S));         // S is a power of two
     MatchPartial c{INFINITY, -1, -1};
     if (seg < cnt) c = mv.part[(int64_t)bh0 * S + lane];
     for (int off = S >> 1; off > 0; off >>= 1) {
