@@ -256,6 +256,9 @@ def main():
     ap.add_argument("--no-sweep", action="store_true", help="skip the other two (rho, threshold) pairs of C3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=12)
+    ap.add_argument("--report", action="store_true",
+                    help="also run every BASELINE config (C1, C2, C3 x3, C4 miss/hit, C5 past its first regime) and add "
+                         "a per-config summary to the JSON line as 'configs_report'")
     ap.add_argument("--paper-table", action="store_true",
                     help="also run the analogue of the paper's fine-grained latency table (batch 1, 32K/60K/120K x KV "
                          "budgets 1/5/10/20 %, K 1024, r 256) and add it to the JSON line as 'paper_table'")
@@ -331,6 +334,21 @@ def main():
         "paper_context": "paper (H100 SXM5, FlashInfer 0.2.7 baseline, batch unstated): full attention 234.2 us and "
                          "MAC 63.6-104.5 us at 120K; another machine, context not target",
     }
+    if a.report:
+        plan = [("C1", 10, 4), ("C2", 60, 8), ("C3_rho90", 40, 8), ("C3_rho97", 40, 8), ("C3_rho99", 40, 8),
+                ("C4_miss", 30, 4), ("C4_hit", 30, 8), ("C5", 100, 300)]
+        rep = []
+        for name, st, wu in plan:
+            r, w_ = run_config(name, st, wu, torch, mb, wl_mod)
+            del w_
+            torch.cuda.empty_cache()
+            rep.append({"config": name, "us_per_step": round(r["us_per_step"], 1),
+                        "full_decode_us_per_step": round(r["full_decode_us_per_step"], 1),
+                        "speedup_vs_full_decode": round(r["speedup_vs_full"], 2), "hit_rate": round(r["hit_rate"], 4),
+                        "kv_read_reduction_pct": round(r["kv_read_reduction_pct"], 2),
+                        "attn_kernel_GBps": round(r["attn_GBps"], 0), "full_attn_kernel_GBps": round(r["full_attn_GBps"], 0),
+                        "kernel_us": {k: round(v, 1) for k, v in r["kernel_us"].items()}})
+        line["configs_report"] = rep
     if a.paper_table:
         line["paper_table"] = paper_table(torch, mb, wl_mod)
     if not a.no_cpu_baseline:
