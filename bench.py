@@ -29,7 +29,7 @@ KV_BYTES_PER_TOKEN_HEAD = 512   # K row + V row, bf16, d = 128
 # HBM bytes per attention-kernel launch from two rocprofv3 --pmc runs of this command with its default arguments
 # (FETCH_SIZE x 2.0000 + WRITE_SIZE x 1.0000, scale factors from a 1 GiB copy; profiles/attn_kernel_C3_128k_pmc_traffic.txt).
 # Only valid for exactly that workload and step range, so it is reported for no other.
-PROFILED_TRAFFIC = {("C3_rho97", 40, 8): {"mac": 2.0266e9, "full": 2.1550e9}}
+PROFILED_TRAFFIC = {("C3_rho97", 40, 8): {"mac": 2.02665e9, "full": 2.15498e9}}
 
 
 def log(msg: str):
@@ -255,7 +255,7 @@ def main():
     ap.add_argument("--config", default="C3_rho97", help="headline config (a C3 pair by default)")
     ap.add_argument("--no-sweep", action="store_true", help="skip the other two (rho, threshold) pairs of C3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-steps", type=int, default=12)
+    ap.add_argument("--cpu-steps", type=int, default=100)
     ap.add_argument("--report", action="store_true",
                     help="also run every BASELINE config (C1, C2, C3 x3, C4 miss/hit, C5 past its first regime) and add "
                          "a per-config summary to the JSON line as 'configs_report'")

@@ -73,10 +73,11 @@ struct MergeSmem {
 struct LaneMerge {
     float M = -INFINITY, Z = 0.f;
     f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+    // branch-free, so that the loads of later chunks are not held back: an empty summary (L = -inf) gets weight 0
     __device__ __forceinline__ void add(const f32x4 o, float L) {
-        if (L == -INFINITY) return;                // empty summary: identity
         const float Mn = fmaxf(M, L);
-        const float a = expf(M - Mn), w = expf(L - Mn);      // exp(-inf) = 0 on the first add
+        const float a = M == -INFINITY ? 0.f : __expf(M - Mn);
+        const float w = L == -INFINITY ? 0.f : __expf(L - Mn);
         acc = acc * a + o * w;
         Z = Z * a + w;
         M = Mn;
@@ -125,14 +126,35 @@ __device__ __forceinline__ void merge_head(const MergeParams& p, const Writeback
 
     // single pass over this lane's chunks (all loads are independent of one another)
     LaneMerge r, bnd;
-    if (c == 0 && pre >= 0)
-        r.add(*reinterpret_cast<const f32x4*>(p.ring_O + pre * kHeadDim + 4 * q), p.ring_lse[pre]);
-    for (int x = x0 + c; x < x1; x += kMergeLanes) {
-        if (max(s, x * C) >= min(nb, (x + 1) * C)) continue;          // nothing of this head in the chunk
-        r.add(*reinterpret_cast<const f32x4*>(p.part_O + (pbase + x) * kHeadDim + 4 * q), p.part_lse[pbase + x]);
+    const f32x4 zero4 = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (c == 0 && pre >= 0) {
+        const float L = p.ring_lse[pre];
+        const f32x4 o = *reinterpret_cast<const f32x4*>(p.ring_O + pre * kHeadDim + 4 * q);
+        r.add(L == -INFINITY ? zero4 : o, L);
     }
-    for (int y = y0 + c; y < y1; y += kMergeLanes)
-        bnd.add(*reinterpret_cast<const f32x4*>(p.part_O + (pbase + y) * kHeadDim + 4 * q), p.part_lse[pbase + y]);
+    // four chunks per trip, loads first (clamped to a slot of this head, then masked)
+    constexpr int kU = 4;
+    for (int x = x0 + c; x < x1; x += kU * kMergeLanes) {
+        f32x4 o[kU];
+        float L[kU];
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            const int xu = x + u * kMergeLanes;
+            const int xc = min(xu, x1 - 1);
+            o[u] = *reinterpret_cast<const f32x4*>(p.part_O + (pbase + xc) * kHeadDim + 4 * q);
+            L[u] = p.part_lse[pbase + xc];
+            // nothing of this head in the chunk (or past the last chunk): identity
+            if (xu >= x1 || max(s, xu * C) >= min(nb, (xu + 1) * C)) { L[u] = -INFINITY; }
+            if (L[u] == -INFINITY) o[u] = zero4;
+        }
+#pragma unroll
+        for (int u = 0; u < kU; ++u) r.add(o[u], L[u]);
+    }
+    for (int y = y0 + c; y < y1; y += kMergeLanes) {
+        const float L = p.part_lse[pbase + y];
+        const f32x4 o = *reinterpret_cast<const f32x4*>(p.part_O + (pbase + y) * kHeadDim + 4 * q);
+        bnd.add(L == -INFINITY ? zero4 : o, L);
+    }
     *reinterpret_cast<f32x4*>(&sm.acc[0][c][4 * q]) = r.acc;
     *reinterpret_cast<f32x4*>(&sm.acc[1][c][4 * q]) = bnd.acc;
     if (q == 0) { sm.m[0][c] = r.M; sm.z[0][c] = r.Z; sm.m[1][c] = bnd.M; sm.z[1][c] = bnd.Z; }
@@ -145,8 +167,8 @@ __device__ __forceinline__ void merge_head(const MergeParams& p, const Writeback
         float S_r = 0.f, Z_r = 0.f, S_b = 0.f, Z_b = 0.f;
 #pragma unroll
         for (int k = 0; k < kMergeLanes; ++k) {
-            const float fr = sm.z[0][k] > 0.f ? expf(sm.m[0][k] - M_r) : 0.f;     // an empty lane has m = -inf
-            const float fb = sm.z[1][k] > 0.f ? expf(sm.m[1][k] - M_b) : 0.f;
+            const float fr = sm.z[0][k] > 0.f ? __expf(sm.m[0][k] - M_r) : 0.f;     // an empty lane has m = -inf
+            const float fb = sm.z[1][k] > 0.f ? __expf(sm.m[1][k] - M_b) : 0.f;
             S_r += sm.acc[0][k][d] * fr; Z_r += sm.z[0][k] * fr;
             S_b += sm.acc[1][k][d] * fb; Z_b += sm.z[1][k] * fb;
         }
