@@ -7,7 +7,10 @@ Differences from the C oracle, on purpose, so that the two do not share a mistak
     (Fig. 1(c): "online subtraction"), not by adding prefix and middle part;
   * keeps the whole history of inserted entries, and selects the window by n_p in [n-W, n-1],
     instead of a ring indexed modulo W (Sec. 4.1);
-  * squared distances can be evaluated in exact rational arithmetic.
+  * squared distances can be evaluated in exact rational arithmetic;
+  * the two matching variants are written from their statement, not from the C code: the distance cap tests the
+    gap n - n_p of the nearest candidate after the threshold; group matching concatenates the group's queries
+    into one vector of G*d elements and compares its squared distance with G*T^2.
 """
 from __future__ import annotations
 
@@ -47,7 +50,8 @@ class DefinitionMAC:
     """One request, all heads; K, V given densely for the whole run."""
 
     def __init__(self, K: np.ndarray, V: np.ndarray, num_q_heads: int, window: int, band: int,
-                 threshold: float, scale: float, exact_match: bool = True):
+                 threshold: float, scale: float, exact_match: bool = True, max_gap: int = 0,
+                 group_match: bool = False):
         self.K, self.V = K, V                    # [tokens, Hkv, d] float64
         self.Hq = num_q_heads
         self.Hkv = K.shape[1]
@@ -56,6 +60,7 @@ class DefinitionMAC:
         self.T = float(np.float32(threshold))
         self.scale = float(np.float32(scale))
         self.exact = exact_match
+        self.max_gap, self.group_match = max_gap, group_match
         self.history: List[dict] = []            # every inserted entry, never evicted
 
     def step(self, n: int, q_pre: np.ndarray, q_rope: np.ndarray):
@@ -68,16 +73,22 @@ class DefinitionMAC:
         T2 = Fraction(self.T) * Fraction(self.T) if self.exact else self.T * self.T
         for h in range(Hq):
             g = h // self.G
+            # the vectors compared: this head's query, or the whole group's queries laid end to end
+            hs = slice(g * self.G, (g + 1) * self.G) if self.group_match else slice(h, h + 1)
+            nh = self.G if self.group_match else 1
             best = None
             best_d2 = None
             for e in cands:
+                a, c = q_pre[hs].reshape(-1), e["q"][hs].reshape(-1)
                 if self.exact:
-                    d2 = exact_sq_dist(q_pre[h], e["q"][h])
+                    d2 = exact_sq_dist(a, c)
                 else:
-                    d2 = float(np.sum((q_pre[h] - e["q"][h]) ** 2))
+                    d2 = float(np.sum((a - c) ** 2))
                 if best is None or d2 < best_d2 or (d2 == best_d2 and e["n_p"] > best["n_p"]):
                     best, best_d2 = e, d2
-            hit = best is not None and best_d2 < T2
+            hit = best is not None and best_d2 < nh * T2
+            if hit and self.max_gap > 0:
+                hit = n - best["n_p"] <= self.max_gap
             if hit:
                 n_p = best["n_p"]
                 s = max(0, n_p - self.B)

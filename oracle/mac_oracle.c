@@ -26,6 +26,14 @@
  *     the last-B band removed:  rect = prefix (+) fresh[s, n-B)  (add-only form
  *     of "total minus band"), so summaries chain across consecutive hits;
  *   - every step inserts, hit or miss; rings start empty.
+ * Two variants beyond the per-head test (both off by default):
+ *   - distance cap (appendix on prefill, "Recommendations" (i); Sec. C "Common issues" (2)): the nearest
+ *     candidate is accepted only if it also lies at most max_gap positions back, n - n_p <= max_gap;
+ *   - one reuse point per KV group instead of per query head (the paper matches per query head, Sec. 4;
+ *     this variant removes the skew inside a group of Sec. 5.8): the distance of a candidate is that of
+ *     the group's concatenated pre-RoPE queries, D^2_j = sum over the group's heads of d^2_{h,j}; argmin
+ *     and tie-break as above; hit iff D^2 < G T^2 (root-mean-square per-head distance below T); every
+ *     head of the group takes the same reuse point.
  *
  * Summaries are carried in the numerically stable form (O, LSE): O = S/Z,
  * LSE = M + ln(sum e^{l - M}); the empty set is (0, -inf).
@@ -53,6 +61,8 @@ typedef struct {
     int64_t stride_page, stride_kv, stride_head, stride_tok;   /* elements */
     int32_t block_table_stride;
     int32_t num_threads;   /* 0 = OpenMP default */
+    int32_t max_gap;       /* distance cap: accept only n - n_p <= max_gap; 0 = no cap */
+    int32_t group_match;   /* 0 = one reuse point per query head, 1 = per KV group */
 } oracle_params;
 
 typedef struct {
@@ -143,12 +153,24 @@ void oracle_full_decode(const oracle_params *P, const int32_t *kv_lens, const ui
     }
 }
 
+/* Squared L2 distance of two bf16 rows, Eq. (accept), accumulated in index order. */
+static double sq_dist(const uint16_t *a, const uint16_t *b, int d) {
+    double d2 = 0.0;
+    for (int i = 0; i < d; ++i) {
+        double diff = bf16_to_double(a[i]) - bf16_to_double(b[i]);
+        d2 += diff * diff;
+    }
+    return d2;
+}
+
 /* Match, Sec. 3.5 step 1 / Eq. (accept): nearest ring entry among those created at lengths
- * n_p in [n - W, n - 1]; squared L2 distance of the pre-RoPE queries; ties -> larger n_p;
- * hit iff d^2 < T^2.  Returns ring index j (or -1), writes n_p (or -1) and the nearest d^2
- * (+inf when there is no candidate). */
-static int match_one(const oracle_params *P, const uint16_t *q_pre, const uint16_t *ring_q /*[W,Hq,d] of this slot*/,
-                     const int32_t *ring_npos /*[W]*/, int h, int64_t n, int32_t *n_p_out, double *d2_out) {
+ * n_p in [n - W, n - 1]; squared L2 distance of the pre-RoPE queries of heads [h0, h0 + nh) taken together
+ * (nh = 1: the paper's per-head test; nh = G: one reuse point per KV group); ties -> larger n_p;
+ * hit iff d^2 < nh T^2 and, with a distance cap, n - n_p <= max_gap.  Returns ring index j (or -1), writes
+ * n_p (or -1) and the nearest d^2 (+inf when there is no candidate). */
+static int match_one(const oracle_params *P, const uint16_t *q_pre /*[Hq,d] of this request*/,
+                     const uint16_t *ring_q /*[W,Hq,d] of this slot*/,
+                     const int32_t *ring_npos /*[W]*/, int h0, int nh, int64_t n, int32_t *n_p_out, double *d2_out) {
     int W = P->window, Hq = P->num_q_heads, d = P->head_dim;
     int best = -1;
     int32_t best_np = -1;
@@ -156,18 +178,17 @@ static int match_one(const oracle_params *P, const uint16_t *q_pre, const uint16
     for (int j = 0; j < W; ++j) {
         int32_t np = ring_npos[j];
         if (np < n - W || np > n - 1 || np < 1) continue;      /* empty entries carry n_p = 0 */
-        const uint16_t *r = ring_q + ((int64_t)j * Hq + h) * d;
         double d2 = 0.0;
-        for (int i = 0; i < d; ++i) {
-            double diff = bf16_to_double(q_pre[i]) - bf16_to_double(r[i]);
-            d2 += diff * diff;
-        }
+        for (int h = h0; h < h0 + nh; ++h)
+            d2 += sq_dist(q_pre + (int64_t)h * d, ring_q + ((int64_t)j * Hq + h) * d, d);
         if (best < 0 || d2 < best_d2 || (d2 == best_d2 && np > best_np)) {
             best = j; best_d2 = d2; best_np = np;
         }
     }
     *d2_out = best_d2;
-    if (best >= 0 && best_d2 < P->threshold * P->threshold) { *n_p_out = best_np; return best; }
+    int ok = best >= 0 && best_d2 < P->threshold * P->threshold * (double)nh;
+    if (ok && P->max_gap > 0 && n - best_np > P->max_gap) ok = 0;
+    if (ok) { *n_p_out = best_np; return best; }
     *n_p_out = -1;
     return -1;
 }
@@ -176,12 +197,17 @@ void oracle_match(const oracle_params *P, const int32_t *slot_ids, const int32_t
                   const uint16_t *ring_q, const int32_t *ring_npos,
                   int32_t *match_pos /*[batch,Hq]*/, int32_t *match_idx /*[batch,Hq]*/, double *match_d2 /*[batch,Hq]*/) {
     int Hq = P->num_q_heads, d = P->head_dim, W = P->window;
+    int G = Hq / P->num_kv_heads;
+    int nh = P->group_match ? G : 1;
     for (int b = 0; b < P->batch; ++b)
-        for (int h = 0; h < Hq; ++h) {
+        for (int h0 = 0; h0 < Hq; h0 += nh) {
             int64_t slot = slot_ids[b];
-            int bh = b * Hq + h;
-            match_idx[bh] = match_one(P, q_pre + (int64_t)bh * d, ring_q + slot * W * Hq * d,
-                                      ring_npos + slot * W, h, kv_lens[b], &match_pos[bh], &match_d2[bh]);
+            int bh = b * Hq + h0;
+            match_idx[bh] = match_one(P, q_pre + (int64_t)b * Hq * d, ring_q + slot * W * Hq * d,
+                                      ring_npos + slot * W, h0, nh, kv_lens[b], &match_pos[bh], &match_d2[bh]);
+            for (int k = 1; k < nh; ++k) {      /* the group's heads share the decision */
+                match_idx[bh + k] = match_idx[bh]; match_pos[bh + k] = match_pos[bh]; match_d2[bh + k] = match_d2[bh];
+            }
         }
 }
 

@@ -32,6 +32,7 @@ class _Params(C.Structure):
         ("threshold", C.c_double), ("sm_scale", C.c_double),
         ("stride_page", C.c_int64), ("stride_kv", C.c_int64), ("stride_head", C.c_int64), ("stride_tok", C.c_int64),
         ("block_table_stride", C.c_int32), ("num_threads", C.c_int32),
+        ("max_gap", C.c_int32), ("group_match", C.c_int32),
     ]
 
 
@@ -85,7 +86,8 @@ class Oracle:
 
     def __init__(self, *, num_q_heads: int, num_kv_heads: int, head_dim: int, page_size: int,
                  window: int, band: int, threshold: float, sm_scale: Optional[float] = None,
-                 strides: Tuple[int, int, int, int], max_slots: int, num_threads: int = 0):
+                 strides: Tuple[int, int, int, int], max_slots: int, num_threads: int = 0,
+                 max_gap: int = 0, group_match: bool = False):
         assert num_q_heads % num_kv_heads == 0 and head_dim <= 1024 and window >= 1 and band >= 0
         self.Hq, self.Hkv, self.d, self.ps = num_q_heads, num_kv_heads, head_dim, page_size
         self.W, self.B = window, band
@@ -95,6 +97,7 @@ class Oracle:
         self.strides = tuple(int(s) for s in strides)
         self.max_slots = max_slots
         self.num_threads = num_threads
+        self.max_gap, self.group_match = int(max_gap), int(bool(group_match))
         self.reset()
         self.stats = Stats()
 
@@ -111,7 +114,7 @@ class Oracle:
     def _params(self, batch: int, block_table: np.ndarray) -> _Params:
         sp, skv, sh, st = self.strides
         return _Params(batch, self.Hq, self.Hkv, self.d, self.ps, self.W, self.B, self.T, self.sm_scale,
-                       sp, skv, sh, st, block_table.shape[1], self.num_threads)
+                       sp, skv, sh, st, block_table.shape[1], self.num_threads, self.max_gap, self.group_match)
 
     # ------------------------------------------------------------------ definitions
     def summary(self, q_rope, kv_pages, block_table, b: int, h: int, lo: int, hi: int):

@@ -339,6 +339,105 @@ def test_against_literal_definition_with_full_history(band, window, threshold):
     assert n_hit > 0 and n_miss > 0, (n_hit, n_miss)
 
 
+@pytest.mark.parametrize("kw", [dict(max_gap=1), dict(max_gap=2), dict(group_match=True),
+                                dict(group_match=True, max_gap=3)])
+def test_variants_against_literal_definition(kw):
+    """Distance cap (appendix on prefill, recommendation (i)) and one reuse point per KV group, against the literal
+    version with exact rational distances on the concatenated group query: decisions identical, outputs to
+    rounding; hits and misses both occur."""
+    cfg = small_cfg(band=3, window=5, threshold=3.2, steps=24, rho=0.93, num_q_heads=4, num_kv_heads=2)
+    wl = Workload(cfg)
+    orc = make_oracle(cfg, wl, **kw)
+    kvp, bt, slots = host_inputs(wl)
+    Kd = [dense_kv(wl, b, cfg.max_kv_len) for b in range(cfg.batch)]
+    lit = [DefinitionMAC(Kd[b][0], Kd[b][1], cfg.num_q_heads, cfg.window, cfg.band, cfg.threshold, orc.sm_scale, **kw)
+           for b in range(cfg.batch)]
+    n_hit = n_miss = 0
+    for q_pre, q_rope, kv_lens in wl:
+        r = orc.mac_step(slots, kv_lens.numpy(), bf16_bits(q_pre), bf16_bits(q_rope), kvp, bt)
+        for b in range(cfg.batch):
+            out, pos = lit[b].step(int(kv_lens[b]), q_pre[b].double().numpy(), q_rope[b].double().numpy())
+            np.testing.assert_array_equal(r["match_pos"][b], pos)
+            np.testing.assert_allclose(r["out"][b], out, rtol=1e-10, atol=1e-13)
+            n_hit += int((pos >= 0).sum())
+            n_miss += int((pos < 0).sum())
+    assert n_hit > 0 and n_miss > 0, (n_hit, n_miss)
+
+
+def test_distance_cap_only_filters_the_uncapped_decision():
+    """The ring of queries does not depend on the decisions (every step inserts its query), so a capped run decides
+    exactly like the uncapped run with the hits farther than max_gap turned into misses; a cap of at least W
+    changes nothing; max_gap = 0 means no cap."""
+    cfg = WorkloadConfig(name="cap", batch=2, num_q_heads=4, num_kv_heads=2, context=60, steps=60, window=16, band=4,
+                         threshold=1.6, rho=0.0, head_dim=16, page_size=4, seed=2, period=5, period_std=1.5,
+                         query_noise=0.1, jump_prob=0.05)
+    runs = {}
+    for cap in (0, 3, 16, 1000):
+        wl = Workload(cfg)
+        orc = make_oracle(cfg, wl, max_gap=cap)
+        kvp, bt, slots = host_inputs(wl)
+        seq = []
+        for q_pre, q_rope, kv_lens in wl:
+            r = orc.mac_step(slots, kv_lens.numpy(), bf16_bits(q_pre), bf16_bits(q_rope), kvp, bt)
+            seq.append((kv_lens.numpy().copy(), r["match_pos"].copy(), r["out"].copy()))
+        runs[cap] = seq
+    far = 0
+    for (n, p0, o0), (_, p3, _), (_, p16, o16), (_, pbig, obig) in zip(runs[0], runs[3], runs[16], runs[1000]):
+        gap = n[:, None] - p0
+        keep = (p0 >= 0) & (gap <= 3)
+        far += int(((p0 >= 0) & (gap > 3)).sum())
+        np.testing.assert_array_equal(p3, np.where(keep, p0, -1))
+        np.testing.assert_array_equal(p16, p0)
+        np.testing.assert_array_equal(pbig, p0)
+        np.testing.assert_array_equal(o16, o0)
+        np.testing.assert_array_equal(obig, o0)
+    assert far > 20          # the cap did remove hits
+
+
+def test_group_matching_reduces_to_per_head_matching_of_concatenated_queries():
+    """One reuse point per KV group == the per-head test applied to the group's queries laid end to end: a pure
+    reshape of the query and of the ring ([.., Hq, d] -> [.., Hkv, G*d]) with threshold sqrt(G)*T (G = 4, so that
+    (2T)^2 = 4 T^2 exactly).  With G = 1 the two modes are the same function."""
+    rng = np.random.default_rng(8)
+    Hq, Hkv, d, W = 8, 2, 8, 6
+    G = Hq // Hkv
+    n_hit = n_miss = 0
+    for trial in range(20):
+        T = float(np.float32(rng.uniform(2.0, 4.0)))
+        grp = Oracle(num_q_heads=Hq, num_kv_heads=Hkv, head_dim=d, page_size=4, window=W, band=2, threshold=T,
+                     strides=(1, 1, 1, 1), max_slots=1, group_match=True)
+        cat = Oracle(num_q_heads=Hkv, num_kv_heads=Hkv, head_dim=G * d, page_size=4, window=W, band=2, threshold=2 * T,
+                     strides=(1, 1, 1, 1), max_slots=1)
+        n = 50 + trial
+        _fill_ring(grp, rng, n, int(rng.integers(1, 7)))
+        if trial % 3 == 0:      # a near-duplicate of a ring entry, so that hits occur
+            j = int(np.argmax(grp.ring_npos[0]))
+            q = torch.from_numpy(bf16_bits_to_f64(grp.ring_q[0, j])[None] + rng.normal(size=(1, Hq, d)) * 0.3)
+        else:
+            q = torch.from_numpy(rng.normal(size=(1, Hq, d)))
+        qb = bf16_bits(q.float().to(torch.bfloat16))
+        cat.ring_q[:] = grp.ring_q.reshape(1, W, Hkv, G * d)
+        cat.ring_npos[:] = grp.ring_npos
+        pos_g, idx_g, d2_g = grp.match(np.array([0]), np.array([n]), qb)
+        pos_c, idx_c, d2_c = cat.match(np.array([0]), np.array([n]), qb.reshape(1, Hkv, G * d))
+        np.testing.assert_array_equal(pos_g.reshape(Hkv, G), np.repeat(pos_c.reshape(Hkv, 1), G, axis=1))
+        np.testing.assert_array_equal(idx_g.reshape(Hkv, G), np.repeat(idx_c.reshape(Hkv, 1), G, axis=1))
+        np.testing.assert_allclose(d2_g.reshape(Hkv, G), np.repeat(d2_c.reshape(Hkv, 1), G, axis=1), rtol=1e-14)
+        n_hit += int((pos_g >= 0).sum())
+        n_miss += int((pos_g < 0).sum())
+    assert n_hit >= 8 and n_miss >= 8, (n_hit, n_miss)
+    # G = 1
+    a = Oracle(num_q_heads=3, num_kv_heads=3, head_dim=d, page_size=4, window=W, band=2, threshold=3.0,
+               strides=(1, 1, 1, 1), max_slots=1, group_match=True)
+    b = Oracle(num_q_heads=3, num_kv_heads=3, head_dim=d, page_size=4, window=W, band=2, threshold=3.0,
+               strides=(1, 1, 1, 1), max_slots=1)
+    _fill_ring(a, rng, 40, 5)
+    b.ring_q[:], b.ring_npos[:] = a.ring_q, a.ring_npos
+    qb = bf16_bits(torch.from_numpy(rng.normal(size=(1, 3, d)).astype(np.float32)).to(torch.bfloat16))
+    for x, y in zip(a.match(np.array([0]), np.array([40]), qb), b.match(np.array([0]), np.array([40]), qb)):
+        np.testing.assert_array_equal(x, y)
+
+
 def test_writeback_holds_rectified_summary_of_this_step():
     """Fig. 1(c) / Sec. 4.2 K3: the entry inserted at length n is prefix (+) fresh[s, n-B) -- checked by
     recomputing it from the pre-step ring and the exported summary/merge; and it sits in slot (n-1) mod W."""
