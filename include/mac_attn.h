@@ -60,6 +60,14 @@ typedef struct mac_attn_config {
                               max_batch * Hkv * max_kv_len so that a full-length step has ~2000 work items */
     int32_t fuse_epilogue; /* 1: the merge kernel also appends to the ring (decode_step = 3 launches);
                               0: write-back runs as a kernel of its own (4 launches)                      */
+    int32_t max_gap;       /* distance cap of the appendix on prefill ("Recommendations" (i)): the nearest
+                              candidate is accepted only if also n - n_p <= max_gap; 0 = no cap           */
+    int32_t group_match;   /* 0: one reuse point per query head (the paper's matching, Sec. 4);
+                              1: one per KV group: candidates are ranked by the squared distance of the
+                              group's concatenated pre-RoPE queries, D^2 = sum over the group's heads of
+                              d^2, hit iff D^2 < G * T^2; match_pos / match_d2 of every head of the group
+                              carry the group's n_p / D^2.  Removes the skew inside a group (Sec. 5.8)     */
+    int32_t out_dtype;     /* type of `out`: 0 = fp32, 1 = bf16 (rounded to nearest even)                 */
 } mac_attn_config;
 
 /* Arguments of one decode step for a batch of requests. */
@@ -77,7 +85,7 @@ typedef struct mac_attn_step_args {
                                                                           the d elements of a row are contiguous */
     const int32_t* block_table;        /* device [batch, block_table_stride]: physical page of logical page */
     int32_t        block_table_stride; /* >= ceil(max_kv_len / page_size)                                 */
-    float*         out;                /* device fp32 [batch, Hq, d]: attention output                    */
+    void*          out;                /* device fp32 (or bf16, see out_dtype) [batch, Hq, d]: output     */
     float*         out_lse;            /* optional device fp32 [batch, Hq]: natural-log LSE of the output */
     int32_t*       match_pos;          /* optional device [batch, Hq]: matched n_p, or -1 on a miss
                                           (written by mac_attn_decode_step only)                          */

@@ -33,6 +33,7 @@ class mac_attn_config(C.Structure):
         ("page_size", C.c_int32), ("window", C.c_int32), ("band", C.c_int32),
         ("threshold", C.c_float), ("sm_scale", C.c_float),
         ("max_kv_len", C.c_int32), ("chunk_tokens", C.c_int32), ("fuse_epilogue", C.c_int32),
+        ("max_gap", C.c_int32), ("group_match", C.c_int32), ("out_dtype", C.c_int32),
     ]
 
 
@@ -190,16 +191,17 @@ class MacAttention:
     def __init__(self, *, num_q_heads: int, num_kv_heads: int, window: int, band: int, threshold: float,
                  max_kv_len: int, max_slots: int, max_batch: Optional[int] = None, head_dim: int = 128,
                  page_size: int = 16, sm_scale: float = 0.0, chunk_tokens: int = 0, fuse_epilogue: bool = True,
-                 device: int = 0):
+                 max_gap: int = 0, group_match: bool = False, out_bf16: bool = False, device: int = 0):
         self.cfg = mac_attn_config(device, max_slots, max_batch or max_slots, num_q_heads, num_kv_heads, head_dim,
                                    page_size, window, band, threshold, sm_scale, max_kv_len, chunk_tokens,
-                                   int(fuse_epilogue))
+                                   int(fuse_epilogue), int(max_gap), int(group_match), int(out_bf16))
         self.ctx = mac_attn_init(self.cfg)
 
     def make_args(self, *, kv_lens, q_rope, kv_pages, strides, block_table, out, slot_ids=None, q_pre=None,
                   out_lse=None, match_pos=None, match_d2=None) -> mac_attn_step_args:
         import torch
-        assert kv_lens.dtype == torch.int32 and block_table.dtype == torch.int32 and out.dtype == torch.float32
+        assert kv_lens.dtype == torch.int32 and block_table.dtype == torch.int32
+        assert out.dtype == (torch.bfloat16 if self.cfg.out_dtype else torch.float32)
         assert q_rope.dtype == torch.bfloat16 and kv_pages.dtype == torch.bfloat16
         assert q_rope.is_contiguous() and out.is_contiguous() and block_table.stride(1) == 1
         ptr = lambda t: None if t is None else t.data_ptr()

@@ -103,7 +103,7 @@ __global__ __launch_bounds__(256, (HT == 1 ? 2 : 1)) void attn_kernel(const Attn
         const int hpp = 64 / p.mv.n_split;                   // heads decided per pass of the wave
         for (int base = 0; base < G; base += hpp) {
             const int cnt = min(hpp, G - base);
-            const MatchDecision md = match_decide_wave(p.mv, hbase + base, cnt, l);
+            const MatchDecision md = match_decide_wave(p.mv, hbase + base, cnt, l, n);
             const int s = clampi(md.start, 0, nb);
             for (int i = 0; i < cnt; ++i) {                  // lane i * n_split holds head base + i
                 const int si = __builtin_amdgcn_readlane(s, i * p.mv.n_split);

@@ -25,6 +25,13 @@ __device__ __forceinline__ uint32_t perm(uint32_t hi_src, uint32_t lo_src, uint3
 __device__ __forceinline__ uint32_t pack_lo16(uint32_t first, uint32_t second) { return perm(second, first, 0x05040100u); }
 __device__ __forceinline__ uint32_t pack_hi16(uint32_t first, uint32_t second) { return perm(second, first, 0x07060302u); }
 
+// fp32 -> bf16 bits, round to nearest even; NaN stays NaN
+__device__ __forceinline__ uint16_t float_to_bf16_rne(float f) {
+    const uint32_t u = float_to_bits(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+    return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+}
+
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }   // v_exp_f32; exp2(-inf) = 0
 
 __device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
@@ -46,7 +53,8 @@ struct MatchView {
     const MatchPartial* part;   // [batch*Hq, n_split]; nullptr = no matching (full decode)
     int32_t n_split;
     int32_t band;               // B
-    double T2;                  // (double)T * (double)T
+    int32_t max_gap;            // distance cap on n - n_p; 0 = none
+    double T2;                  // (double)T * (double)T, times G when one reuse point is chosen per KV group
 };
 
 struct MatchDecision {
@@ -63,8 +71,9 @@ struct MatchDecision {
 // One wave decides up to 64 / n_split consecutive heads at once: lane l holds slice l % n_split of head
 // bh0 + l / n_split (n_split is a power of two <= 64), one coalesced 16-byte load per lane, then a butterfly
 // inside each n_split-lane segment.  On return every lane of a segment holds its head's decision; lanes of
-// segments >= cnt hold a miss.  Must be called by all 64 lanes of the wave.
-__device__ __forceinline__ MatchDecision match_decide_wave(const MatchView& mv, int bh0, int cnt, int lane) {
+// segments >= cnt hold a miss.  Must be called by all 64 lanes of the wave.  `n` is the request's kv_len (all heads
+// of one call belong to one request); it only enters through the optional distance cap n - n_p <= max_gap.
+__device__ __forceinline__ MatchDecision match_decide_wave(const MatchView& mv, int bh0, int cnt, int lane, int n) {
     MatchDecision r{INFINITY, -1, -1, 0};
     if (mv.part == nullptr) return r;
     const int S = mv.n_split;
@@ -78,7 +87,7 @@ __device__ __forceinline__ MatchDecision match_decide_wave(const MatchView& mv, 
         if (better(od2, onp, c.d2, c.np)) { c.d2 = od2; c.np = onp; c.j = oj; }
     }
     r.d2 = c.d2;
-    if (c.np >= 1 && c.d2 < mv.T2) {
+    if (c.np >= 1 && c.d2 < mv.T2 && (mv.max_gap <= 0 || n - c.np <= mv.max_gap)) {
         r.np = c.np;
         r.j = c.j;
         r.start = c.np - mv.band > 0 ? c.np - mv.band : 0;

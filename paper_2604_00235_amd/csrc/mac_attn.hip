@@ -57,6 +57,8 @@ int validate_config(const mac_attn_config* c, Layout* L) {
     if (c->window < 1 || c->band < 0 || c->max_kv_len < 1 || c->page_size < 1) return MAC_ATTN_ERR_INVALID_ARG;
     if (!(c->threshold >= 0.f) || !std::isfinite(c->sm_scale)) return MAC_ATTN_ERR_INVALID_ARG;   // rejects NaN; +inf T is legal
     if (c->chunk_tokens < 0 || (c->fuse_epilogue != 0 && c->fuse_epilogue != 1)) return MAC_ATTN_ERR_INVALID_ARG;
+    if (c->max_gap < 0 || (c->group_match != 0 && c->group_match != 1) || (c->out_dtype != 0 && c->out_dtype != 1))
+        return MAC_ATTN_ERR_INVALID_ARG;
     if (c->head_dim != mac::kHeadDim) return MAC_ATTN_ERR_UNSUPPORTED;
     const int G = c->num_q_heads / c->num_kv_heads;
     if (G > 32) return MAC_ATTN_ERR_UNSUPPORTED;
@@ -199,6 +201,7 @@ mac::MatchView match_view(const mac_attn_ctx* ctx, bool mac_mode) {
     mv.n_split = ctx->n_split;
     mv.band = ctx->cfg.band;
     mv.T2 = ctx->T2;
+    mv.max_gap = ctx->cfg.max_gap;
     return mv;
 }
 
@@ -255,6 +258,7 @@ mac::MergeParams merge_params(mac_attn_ctx* ctx, const mac_attn_step_args* a, bo
     p.part_O = ctx->part_O;
     p.part_lse = ctx->part_lse;
     p.out = a->out;
+    p.out_bf16 = ctx->cfg.out_dtype;
     p.out_lse = a->out_lse;
     p.rect_O = stage_rect ? ctx->rect : nullptr;
     p.rect_lse = stage_rect ? ctx->rect + bh * mac::kHeadDim : nullptr;
@@ -364,6 +368,7 @@ int mac_attn_init(const mac_attn_config* cfg, mac_attn_ctx** out_ctx) {
     ctx->L = L;
     ctx->sm_scale = cfg->sm_scale > 0.f ? cfg->sm_scale : 1.0f / std::sqrt((float)cfg->head_dim);
     ctx->T2 = (double)cfg->threshold * (double)cfg->threshold;
+    if (cfg->group_match) ctx->T2 = ctx->T2 * (double)L.G;      // concatenated group query: D^2 < G T^2
     struct { void** p; int64_t bytes; bool zero; } allocs[] = {
         {reinterpret_cast<void**>(&ctx->ring_q), L.ring_q_bytes, true},
         {reinterpret_cast<void**>(&ctx->ring_O), L.ring_O_bytes, true},
@@ -431,22 +436,37 @@ int mac_attn_decode_step(mac_attn_ctx* ctx, const mac_attn_step_args* args, void
         p.q_pre = static_cast<const uint16_t*>(args->q_pre);
         p.ring_q = ctx->ring_q;
         p.ring_npos = ctx->ring_npos;
-        // window slices: a power of two, enough work-groups to fill the chip at small batch, and at least one
-        // 64-row pass each
-        const int64_t heads = (int64_t)args->batch * c.num_q_heads;
-        int split = 1;
-        while (split * 2 <= 64 && split * heads < 512 && (c.window + split * 2 - 1) / (split * 2) >= 64) split *= 2;
-        const int rows = (((c.window + split - 1) / split + 63) / 64) * 64;
-        ctx->n_split = split;
         p.part = ctx->m_part;
         p.st_steps = ctx->stats + 3 * bh + 2 * (int64_t)c.max_batch * c.num_kv_heads;
         p.Hq = c.num_q_heads;
         p.W = c.window;
         p.max_kv_len = c.max_kv_len;
+        p.G = ctx->L.G;
+        // window slices: a power of two, enough work-groups to fill the chip at small batch
+        int split = 1;
+        if (!c.group_match) {
+            // per head: every slice keeps at least one 64-row pass
+            const int64_t heads = (int64_t)args->batch * c.num_q_heads;
+            while (split * 2 <= 64 && split * heads < 512 && (c.window + split * 2 - 1) / (split * 2) >= 64) split *= 2;
+            p.rows_per_split = (((c.window + split - 1) / split + 63) / 64) * 64;
+        } else {
+            // per KV group: a slice holds at most kMatchGroupItems (row, head) pairs and at least 16 rows
+            const int64_t groups = (int64_t)args->batch * c.num_kv_heads;
+            auto rows_of = [&](int sp) { return (((c.window + sp - 1) / sp + 15) / 16) * 16; };
+            while (split * 2 <= 64 && (rows_of(split) * p.G > mac::kMatchGroupItems ||
+                                       (split * groups < 512 && (c.window + split * 2 - 1) / (split * 2) >= 16)))
+                split *= 2;
+            p.rows_per_split = rows_of(split);
+        }
+        ctx->n_split = split;
         p.n_split = split;
-        p.rows_per_split = rows;
-        dim3 grid(c.num_q_heads, args->batch, split), block(mac::kMatchThreads);
-        hipLaunchKernelGGL(mac::match_kernel, grid, block, 0, stream, p);
+        if (!c.group_match) {
+            dim3 grid(c.num_q_heads, args->batch, split), block(mac::kMatchThreads);
+            hipLaunchKernelGGL(mac::match_kernel, grid, block, 0, stream, p);
+        } else {
+            dim3 grid(c.num_kv_heads, args->batch, split), block(mac::kMatchThreads);
+            hipLaunchKernelGGL(mac::match_group_kernel, grid, block, 0, stream, p);
+        }
         HIP_TRY(hipGetLastError());
         t.done(0);
     }

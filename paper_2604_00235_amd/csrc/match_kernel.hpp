@@ -40,11 +40,41 @@ struct MatchParams {
     unsigned long long* st_steps;   // [2]: decode steps, head-steps (device-side so that graph replays count too)
     int32_t Hq, W, max_kv_len;
     int32_t n_split;             // window slices per head = gridDim.z
-    int32_t rows_per_split;      // multiple of 64
+    int32_t rows_per_split;      // multiple of 64 (match_kernel) / of 16 with rows_per_split * G <= 4096 (group kernel)
+    int32_t G;                   // heads per KV group (group kernel only)
 };
 
 __device__ __forceinline__ double bf16_lo_to_f64(uint32_t pair) { return (double)bits_to_float(pair << 16); }
 __device__ __forceinline__ double bf16_hi_to_f64(uint32_t pair) { return (double)bits_to_float(pair & 0xffff0000u); }
+
+// Partial squared distance of one lane: its 32 query elements (already fp64) against the 4 x 16 bytes it loaded.
+__device__ __forceinline__ double lane_sq_dist(const double (&q)[32], const u32x4 (&v)[4]) {
+    double s0 = 0.0, s1 = 0.0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const double d0 = q[8 * i + 2 * e] - bf16_lo_to_f64(v[i][e]);
+            const double d1 = q[8 * i + 2 * e + 1] - bf16_hi_to_f64(v[i][e]);
+            s0 = fma(d0, d0, s0);
+            s1 = fma(d1, d1, s1);
+        }
+    }
+    return s0 + s1;
+}
+
+// this lane's 32 elements of a 128-element bf16 row (16-byte chunks sub, sub + 4, sub + 8, sub + 12), widened
+__device__ __forceinline__ void load_query_f64(const uint16_t* row_plus_8sub, double (&q)[32]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const u32x4 v = *reinterpret_cast<const u32x4*>(row_plus_8sub + 32 * i);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            q[8 * i + 2 * e] = bf16_lo_to_f64(v[e]);
+            q[8 * i + 2 * e + 1] = bf16_hi_to_f64(v[e]);
+        }
+    }
+}
 
 constexpr int kMatchThreads = 256;
 constexpr int kMatchRowsPerPass = kMatchThreads / 4;
@@ -59,18 +89,7 @@ __global__ __launch_bounds__(kMatchThreads) void match_kernel(const MatchParams 
 
     // this lane's 32 query elements (chunks sub + 4i), widened once
     double q[32];
-    {
-        const uint16_t* qp = p.q_pre + (int64_t)bh * kHeadDim + 8 * sub;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const u32x4 v = *reinterpret_cast<const u32x4*>(qp + 32 * i);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                q[8 * i + 2 * e] = bf16_lo_to_f64(v[e]);
-                q[8 * i + 2 * e + 1] = bf16_hi_to_f64(v[e]);
-            }
-        }
-    }
+    load_query_f64(p.q_pre + (int64_t)bh * kHeadDim + 8 * sub, q);
     const uint16_t* ring = p.ring_q + ((slot * p.Hq + h) * W) * (int64_t)kHeadDim + 8 * sub;
     const int32_t* npos = p.ring_npos + slot * W;
     const int np_lo = max(1, n - W), np_hi = n - 1;
@@ -87,20 +106,7 @@ __global__ __launch_bounds__(kMatchThreads) void match_kernel(const MatchParams 
 #pragma unroll
         for (int i = 0; i < 4; ++i) v[i] = *reinterpret_cast<const u32x4*>(rp + 32 * i);
         const bool valid = j < j_end && np >= np_lo && np <= np_hi;
-        double s0 = 0.0, s1 = 0.0;
-        {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const double d0 = q[8 * i + 2 * e] - bf16_lo_to_f64(v[i][e]);
-                    const double d1 = q[8 * i + 2 * e + 1] - bf16_hi_to_f64(v[i][e]);
-                    s0 = fma(d0, d0, s0);
-                    s1 = fma(d1, d1, s1);
-                }
-            }
-        }
-        double d2 = s0 + s1;
+        double d2 = lane_sq_dist(q, v);
         d2 += __shfl_xor(d2, 1);
         d2 += __shfl_xor(d2, 2);
         if (valid && better(d2, np, best_d2, best_np)) { best_d2 = d2; best_np = np; best_j = j; }
@@ -126,6 +132,76 @@ __global__ __launch_bounds__(kMatchThreads) void match_kernel(const MatchParams 
         for (int w = 1; w < kWaves; ++w)
             if (better(s_d2[w], s_np[w], best_d2, best_np)) { best_d2 = s_d2[w]; best_np = s_np[w]; best_j = s_j[w]; }
         p.part[(int64_t)bh * p.n_split + sp] = MatchPartial{best_d2, best_np, best_j};
+    }
+}
+
+// One reuse point per KV group: candidates are ranked by D2_j = sum over the group's heads of d2_{h,j} (the squared
+// distance of the group's concatenated queries), summed in head order.  One work-group per (KV group, request,
+// window slice).  The (row, head) pairs of the slice are dealt to the 64 quads, so all ring loads are independent;
+// the per-pair distances meet in shared memory, then thread r sums row r over the heads and the argmin proceeds as
+// in match_kernel.  The slice result is written for every head of the group, so the consumers need no change.
+constexpr int kMatchGroupItems = 4096;   // (row, head) pairs per work-group: 32 KB of shared memory
+
+__global__ __launch_bounds__(kMatchThreads) void match_group_kernel(const MatchParams p) {
+    const int g = blockIdx.x, b = blockIdx.y, sp = blockIdx.z;
+    const int tid = threadIdx.x, quad = tid >> 2, sub = tid & 3;
+    const int G = p.G, W = p.W;
+    const int n = clampi(p.kv_lens[b], 0, p.max_kv_len);
+    const int64_t slot = p.slot_ids[b];
+    const int32_t* npos = p.ring_npos + slot * W;
+    const int np_lo = max(1, n - W), np_hi = n - 1;
+    const int j_begin = sp * p.rows_per_split;
+    const int rows = max(0, min(W, j_begin + p.rows_per_split) - j_begin);
+    const int items = rows * G;                                  // <= kMatchGroupItems (host)
+    __shared__ double s_pair[kMatchGroupItems];
+
+    for (int i0 = 0; i0 < items; i0 += kMatchRowsPerPass) {
+        const int i = i0 + quad;
+        const int ic = i < items ? i : items - 1;                // keeps the loads of idle quads inside the slice
+        const int r = ic / G, h = g * G + (ic - r * G);
+        double q[32];
+        load_query_f64(p.q_pre + ((int64_t)b * p.Hq + h) * kHeadDim + 8 * sub, q);
+        const uint16_t* rp = p.ring_q + ((slot * p.Hq + h) * W + j_begin + r) * (int64_t)kHeadDim + 8 * sub;
+        u32x4 v[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v[k] = *reinterpret_cast<const u32x4*>(rp + 32 * k);
+        double d2 = lane_sq_dist(q, v);
+        d2 += __shfl_xor(d2, 1);
+        d2 += __shfl_xor(d2, 2);
+        if (i < items && sub == 0) s_pair[i] = d2;
+    }
+    __syncthreads();
+
+    double best_d2 = INFINITY;
+    int best_np = -1, best_j = -1;
+    for (int r = tid; r < rows; r += kMatchThreads) {
+        const int j = j_begin + r;
+        const int np = npos[j];
+        double D = 0.0;
+        for (int hh = 0; hh < G; ++hh) D += s_pair[r * G + hh];
+        if (np >= np_lo && np <= np_hi && better(D, np, best_d2, best_np)) { best_d2 = D; best_np = np; best_j = j; }
+    }
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const double od2 = __shfl_xor(best_d2, off);
+        const int onp = __shfl_xor(best_np, off);
+        const int oj = __shfl_xor(best_j, off);
+        if (better(od2, onp, best_d2, best_np)) { best_d2 = od2; best_np = onp; best_j = oj; }
+    }
+    constexpr int kWaves = kMatchThreads / 64;
+    __shared__ double s_d2[kWaves];
+    __shared__ int s_np[kWaves], s_j[kWaves];
+    if ((tid & 63) == 0) { s_d2[tid >> 6] = best_d2; s_np[tid >> 6] = best_np; s_j[tid >> 6] = best_j; }
+    __syncthreads();
+    if (tid == 0 && g == 0 && b == 0 && sp == 0) {
+        atomicAdd(&p.st_steps[0], 1ull);
+        atomicAdd(&p.st_steps[1], (unsigned long long)gridDim.x * gridDim.y * G);
+    }
+    if (tid < G) {
+        best_d2 = s_d2[0]; best_np = s_np[0]; best_j = s_j[0];
+        for (int w = 1; w < kWaves; ++w)
+            if (better(s_d2[w], s_np[w], best_d2, best_np)) { best_d2 = s_d2[w]; best_np = s_np[w]; best_j = s_j[w]; }
+        p.part[((int64_t)b * p.Hq + g * G + tid) * p.n_split + sp] = MatchPartial{best_d2, best_np, best_j};
     }
 }
 

@@ -47,7 +47,8 @@ struct MergeParams {
     const float* ring_lse;       // [slots, Hq, W]
     const float* part_O;         // [batch*Hq, n_slots, 128]
     const float* part_lse;       // [batch*Hq, n_slots]
-    float* out;                  // [batch, Hq, 128]
+    void* out;                   // [batch, Hq, 128] fp32, or bf16 when out_bf16
+    int32_t out_bf16;
     float* out_lse;              // optional [batch, Hq]
     float* rect_O;               // staging for a separate write-back kernel [batch*Hq, 128]; may be null
     float* rect_lse;             // [batch*Hq]
@@ -110,7 +111,7 @@ __device__ __forceinline__ void merge_head(const MergeParams& p, const Writeback
     const int n = clampi(p.kv_lens[b], 0, p.max_kv_len);
     const int nb = n - p.band > 0 ? n - p.band : 0;
     const int C = p.chunk;
-    MatchDecision md = match_decide_wave(p.mv, bh, 1, tid & 63);           // every wave decides this head itself;
+    MatchDecision md = match_decide_wave(p.mv, bh, 1, tid & 63, n);           // every wave decides this head itself;
     md.d2 = __shfl(md.d2, 0);                                              // lane 0 holds it, the rest take it over
     md.np = __shfl(md.np, 0);
     md.j = __shfl(md.j, 0);
@@ -188,7 +189,11 @@ __device__ __forceinline__ void merge_head(const MergeParams& p, const Writeback
             o = (fr * S_r + fb * S_b) / Z;
             lse = M_o + logf(Z);
         }
-        p.out[(int64_t)bh * kHeadDim + d] = o;
+        if (p.out_bf16) {
+            static_cast<uint16_t*>(p.out)[(int64_t)bh * kHeadDim + d] = float_to_bf16_rne(o);
+        } else {
+            static_cast<float*>(p.out)[(int64_t)bh * kHeadDim + d] = o;
+        }
         if (d == 0 && p.out_lse != nullptr) p.out_lse[bh] = lse;
         if (do_wb) writeback_head(wb, b, h, d, rect_o, rect_l);
     }
@@ -210,7 +215,7 @@ __device__ __forceinline__ void merge_head(const MergeParams& p, const Writeback
             const int hpp = 64 / p.mv.n_split;
             for (int base = 0; base < p.G; base += hpp) {
                 const int cnt = min(hpp, p.G - base);
-                const MatchDecision g = match_decide_wave(p.mv, bh + base, cnt, tid);
+                const MatchDecision g = match_decide_wave(p.mv, bh + base, cnt, tid, n);
                 const int gstart = clampi(g.start, 0, nb);
                 for (int i = 0; i < cnt; ++i) gs = min(gs, __builtin_amdgcn_readlane(gstart, i * p.mv.n_split));
             }

@@ -43,17 +43,19 @@ class GpuRun:
     """One library context + device buffers for a workload living on cuda:0."""
 
     def __init__(self, cfg: WorkloadConfig, wl: Workload, chunk_tokens: int = 0, strides=None, kv_pages=None,
-                 max_kv_len=None, fuse_epilogue: bool = True):
+                 max_kv_len=None, fuse_epilogue: bool = True, max_gap: int = 0, group_match: bool = False,
+                 out_bf16: bool = False):
         self.cfg, self.wl = cfg, wl
         dev = wl.device
         self.mac = mb.MacAttention(num_q_heads=cfg.num_q_heads, num_kv_heads=cfg.num_kv_heads, window=cfg.window,
                                    band=cfg.band, threshold=cfg.threshold, max_kv_len=max_kv_len or cfg.max_kv_len,
                                    max_slots=cfg.batch, page_size=cfg.page_size, chunk_tokens=chunk_tokens,
-                                   fuse_epilogue=fuse_epilogue)
+                                   fuse_epilogue=fuse_epilogue, max_gap=max_gap, group_match=group_match,
+                                   out_bf16=out_bf16)
         self.kv_pages = wl.kv_pages if kv_pages is None else kv_pages
         self.strides = wl.strides if strides is None else strides
         B, Hq, d = cfg.batch, cfg.num_q_heads, cfg.head_dim
-        self.out = torch.zeros((B, Hq, d), dtype=torch.float32, device=dev)
+        self.out = torch.zeros((B, Hq, d), dtype=torch.bfloat16 if out_bf16 else torch.float32, device=dev)
         self.lse = torch.zeros((B, Hq), dtype=torch.float32, device=dev)
         self.pos = torch.zeros((B, Hq), dtype=torch.int32, device=dev)
         self.d2 = torch.zeros((B, Hq), dtype=torch.float64, device=dev)
@@ -67,24 +69,25 @@ class GpuRun:
     def mac_step(self, q_pre, q_rope, kv_lens):
         self.mac.decode_step(self.args(q_pre, q_rope, kv_lens), self.stream)
         torch.cuda.synchronize()
-        return (self.out.cpu().numpy().copy(), self.lse.cpu().numpy().copy(), self.pos.cpu().numpy().copy(),
+        return (self.out.float().cpu().numpy().copy(), self.lse.cpu().numpy().copy(), self.pos.cpu().numpy().copy(),
                 self.d2.cpu().numpy().copy())
 
     def full(self, q_rope, kv_lens):
         self.mac.full_decode(self.args(None, q_rope, kv_lens), self.stream)
         torch.cuda.synchronize()
-        return self.out.cpu().numpy().copy(), self.lse.cpu().numpy().copy()
+        return self.out.float().cpu().numpy().copy(), self.lse.cpu().numpy().copy()
 
 
 def run_parity(cfg: WorkloadConfig, chunk_tokens: int = 0, check_full: bool = True, check_ring_every: int = 4,
-               label: str = "", fuse_epilogue: bool = True):
+               label: str = "", fuse_epilogue: bool = True, max_gap: int = 0, group_match: bool = False):
     """All steps of `cfg` on both sides; returns summary dict.  Oracle inputs are host copies of the same bits."""
     say(f"[parity] {label or cfg.name}: batch={cfg.batch} Hq/Hkv={cfg.num_q_heads}/{cfg.num_kv_heads} "
         f"context={cfg.context} steps={cfg.steps} W={cfg.window} B={cfg.band} T={cfg.threshold:.4g} "
-        f"page={cfg.page_size} chunk={chunk_tokens} fused={fuse_epilogue} seed={cfg.seed}")
+        f"page={cfg.page_size} chunk={chunk_tokens} fused={fuse_epilogue} max_gap={max_gap} group_match={group_match} "
+        f"seed={cfg.seed}")
     wl = Workload(cfg, device="cuda:0")
-    run = GpuRun(cfg, wl, chunk_tokens, fuse_epilogue=fuse_epilogue)
-    orc = make_oracle(cfg, wl)
+    run = GpuRun(cfg, wl, chunk_tokens, fuse_epilogue=fuse_epilogue, max_gap=max_gap, group_match=group_match)
+    orc = make_oracle(cfg, wl, max_gap=max_gap, group_match=group_match)
     kvp = bf16_bits(wl.kv_pages)
     bt = wl.block_table.cpu().numpy()
     slots = wl.slot_ids.cpu().numpy()

@@ -39,7 +39,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_struct_layouts_match_header():
     """Field order/size of the ctypes mirrors: int32/float fields packed as in the C structs."""
-    assert C.sizeof(mb.mac_attn_config) == 14 * 4
+    assert C.sizeof(mb.mac_attn_config) == 17 * 4
     assert C.sizeof(mb.mac_attn_stats_t) == 8 * 8
     a = mb.mac_attn_step_args
     assert a.stride_page.offset % 8 == 0 and a.block_table_stride.offset == a.block_table.offset + 8

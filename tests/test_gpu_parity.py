@@ -150,3 +150,70 @@ def test_recurring_queries_large_window_split_match(hq, hkv, window, batch):
                          period_std=4.0, query_noise=0.1, jump_prob=0.05, ragged=11 if batch > 1 else 0)
     r = run_parity(cfg, chunk_tokens=256, check_full=False, check_ring_every=16)
     assert 0.3 * r["head_steps"] < r["hits"] < r["head_steps"]
+
+
+# ----------------------------------------------------------------------------- variants of the match rule
+def _recurring(name, hq, hkv, window, batch=2, steps=150, **kw):
+    base = dict(name=name, batch=batch, num_q_heads=hq, num_kv_heads=hkv, context=1500, steps=steps, window=window,
+                band=48, threshold=T_DEFAULT, rho=0.0, seed=23, period=40, period_std=4.0, query_noise=0.1,
+                jump_prob=0.05, ragged=11 if batch > 1 else 0)
+    base.update(kw)
+    return WorkloadConfig(**base)
+
+
+@pytest.mark.parametrize("max_gap", [30, 40, 1000])
+def test_distance_cap(max_gap):
+    """Accept the nearest candidate only if it is at most max_gap positions back (reuse gaps are ~40 +- 4 here, so
+    a cap of 30 removes nearly every hit, 40 about half, 1000 none)."""
+    from tests.gpu_harness import run_parity
+    cfg = _recurring("cap", 8, 2, 200)
+    r = run_parity(cfg, chunk_tokens=256, check_full=False, max_gap=max_gap)
+    if max_gap == 30:
+        assert r["hits"] < 0.1 * r["head_steps"]
+    elif max_gap == 40:
+        assert 0.1 * r["head_steps"] < r["hits"] < 0.7 * r["head_steps"]
+    else:
+        assert r["hits"] > 0.5 * r["head_steps"]
+
+
+@pytest.mark.parametrize("hq,hkv,window,batch", [(32, 8, 256, 2), (32, 1, 128, 2), (8, 8, 64, 2), (6, 2, 100, 3),
+                                                 (10, 2, 1024, 1), (32, 1, 4096, 1)])
+def test_group_granular_matching(hq, hkv, window, batch):
+    """One reuse point per KV group (ranked by the distance of the group's concatenated queries, threshold G T^2):
+    G = 4, 32, 1, 3, 5; windows that are cut into slices, one that is not a multiple of the slice size, and the
+    largest window with the largest group."""
+    from tests.gpu_harness import run_parity
+    steps = 150 if window <= 1024 else 60
+    # one period for all heads, so that a group has a common nearest entry (with per-head periods it never hits)
+    cfg = _recurring(f"group{hq}_{hkv}_{window}", hq, hkv, window, batch=batch, steps=steps, period_std=0.0)
+    r = run_parity(cfg, chunk_tokens=256, check_full=False, check_ring_every=16, group_match=True)
+    assert 0.2 * r["head_steps"] < r["hits"] < r["head_steps"]
+
+
+def test_group_granular_matching_with_cap_ar1_queries():
+    """AR(1) queries at C2 geometry, threshold near the lag-1 distance of a whole group, capped at one step back."""
+    from tests.gpu_harness import run_parity
+    cfg = scaled(CONFIGS["C2"], name="C2g", batch=3, context=2500, steps=24, window=16, band=64, threshold=2.8, ragged=37)
+    r = run_parity(cfg, chunk_tokens=256, group_match=True, max_gap=1)
+    assert 0 < r["hits"] < r["head_steps"]
+
+
+def test_bf16_output_is_the_rounded_fp32_output():
+    """out_dtype = bf16: the same step on two contexts, one per output type; the bf16 result must be the fp32
+    result rounded to nearest even (torch's conversion is the reference rounding), for decode_step and full_decode."""
+    from tests.gpu_harness import GpuRun
+    cfg = scaled(CONFIGS["C2"], name="bf16out", batch=2, context=700, steps=6, window=8, band=32, threshold=2.8)
+    wl = Workload(cfg, device="cuda:0")
+    r32 = GpuRun(cfg, wl, chunk_tokens=128)
+    r16 = GpuRun(cfg, wl, chunk_tokens=128, out_bf16=True)
+    for q_pre, q_rope, kv_lens in wl:
+        for mode in ("full", "mac"):
+            for run in (r32, r16):
+                a = run.args(q_pre if mode == "mac" else None, q_rope, kv_lens)
+                (run.mac.decode_step if mode == "mac" else run.mac.full_decode)(a, run.stream)
+            torch.cuda.synchronize()
+            assert r16.out.dtype == torch.bfloat16
+            assert torch.equal(r16.out, r32.out.to(torch.bfloat16)), mode
+        assert torch.equal(r16.pos, r32.pos)
+    r32.mac.close()
+    r16.mac.close()
