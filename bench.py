@@ -222,6 +222,108 @@ def paper_table(torch, mb, wl_mod, steps: int = 200):
     return rows
 
 
+def match_table(torch, mb, wl_mod, timed: int = 40):
+    """Our analogue of the paper's kernel micro-benchmark (Sec. 5.7, kernel-breakdown figure, panel a): the Match
+    kernel over a window of L queries against the full-attention kernel over L keys, for GQA 8-2, 32-8 and 40-10 and
+    L = 512, 1024, 2048.  The paper does not state the batch; batch 1 (latency-bound on this chip) and batch 32 are
+    reported.  Threshold 0, so every step misses and attention streams all L keys; the window is full (L steps run
+    first from an empty context)."""
+    rows = []
+    for batch in (1, 32):
+        for hq, hkv in ((8, 2), (32, 8), (40, 10)):
+            for L in (512, 1024, 2048):
+                cfg = wl_mod.WorkloadConfig(name=f"M_{hq}_{hkv}_{L}", batch=batch, num_q_heads=hq, num_kv_heads=hkv,
+                                            context=0, steps=L + timed, window=L, band=64, threshold=0.0, rho=0.97, seed=11)
+                wl = wl_mod.Workload(cfg, device="cuda:0")
+                mac = mb.MacAttention(num_q_heads=hq, num_kv_heads=hkv, window=L, band=64, threshold=0.0,
+                                      max_kv_len=cfg.max_kv_len, max_slots=batch)
+                out = torch.zeros((batch, hq, 128), dtype=torch.float32, device="cuda:0")
+                stream = torch.cuda.current_stream().cuda_stream
+                inputs = [wl.next_step() for _ in range(cfg.steps)]
+                args = [mac.make_args(kv_lens=kl, q_rope=qr, kv_pages=wl.kv_pages, strides=wl.strides,
+                                      block_table=wl.block_table, out=out, slot_ids=wl.slot_ids, q_pre=qp)
+                        for (qp, qr, kl) in inputs]
+                for a in args[:L]:
+                    mac.decode_step(a, stream)
+                torch.cuda.synchronize()
+                mb.mac_attn_set_timing(mac.ctx, True)
+                for a in args[L:]:
+                    mac.decode_step(a, stream)
+                k_us, k_n = mb.mac_attn_kernel_us(mac.ctx)
+                mac.close()
+                ring_mb = batch * hq * L * 256 / 1e6
+                kv_mb = batch * hkv * (L + timed // 2) * 512 / 1e6
+                row = {"batch": batch, "gqa": f"{hq}-{hkv}", "tokens": L, "match_us": round(k_us[0] / k_n, 2),
+                       "attention_us": round(k_us[1] / k_n, 2), "match_over_attention": round(k_us[0] / k_us[1], 2),
+                       "ring_MB": round(ring_mb, 2), "kv_MB": round(kv_mb, 2)}
+                rows.append(row)
+                log(f"[match-table] batch {batch:2d} GQA {row['gqa']:>5s} L {L:4d}: match {row['match_us']:6.2f} us "
+                    f"({ring_mb:6.1f} MB)  attention {row['attention_us']:6.2f} us ({kv_mb:6.1f} MB)  ratio "
+                    f"{row['match_over_attention']:.2f}")
+                del wl
+    torch.cuda.empty_cache()
+    return rows
+
+
+def err_table(torch, mb, wl_mod, align: float = 1.5, context: int = 32768, timed: int = 48):
+    """Synthetic analogue of the paper's rectification-error heat-map (Sec. 5.4): the relative error of the MAC output
+    against full attention of the same step, Err = |o_MAC - o_full| / |o_full|, averaged over the heads that hit, as a
+    function of the reuse gap Delta and the band width r.  One request of Llama-3.1-8B geometry; queries recur with
+    period Delta exactly and the window holds Delta + 1 entries, so the entry Delta back is the only near-duplicate
+    in the window; keys and queries share a per-KV-head direction
+    of weight `align`, which under RoPE makes recent keys carry most of the attention mass.  Both outputs come from
+    the library (decode_step and full_decode).  Only the trend is comparable with the paper's figure (trained
+    model, real text): error falls quickly as r grows and rises with Delta."""
+    rows = []
+    kv = None
+    for gap in (2, 8, 64, 512):
+        W = gap + 1
+        for r in (0, 8, 32, 128, 256):
+            steps = 2 * gap + timed
+            cfg = wl_mod.WorkloadConfig(name=f"E_{gap}_{r}", batch=1, num_q_heads=32, num_kv_heads=8, context=context,
+                                        steps=steps, window=W, band=r, threshold=0.5 * 128 ** 0.5, rho=0.0, seed=13,
+                                        period=gap, period_std=0.0, query_noise=0.05, align=align)
+            if kv is None:
+                kv = wl_mod.Workload(wl_mod.scaled(cfg, steps=2 * 512 + timed), device="cuda:0")   # K/V for the longest run
+            wl = wl_mod.Workload(cfg, device="cuda:0", queries_only=True)
+            wl.kv_pages, wl.block_table = kv.kv_pages, kv.block_table
+            mac = mb.MacAttention(num_q_heads=32, num_kv_heads=8, window=W, band=r, threshold=cfg.threshold,
+                                  max_kv_len=kv.cfg.max_kv_len, max_slots=1)
+            o_mac = torch.zeros((1, 32, 128), dtype=torch.float32, device="cuda:0")
+            o_full = torch.zeros_like(o_mac)
+            pos = torch.zeros((1, 32), dtype=torch.int32, device="cuda:0")
+            stream = torch.cuda.current_stream().cuda_stream
+            err_sum = torch.zeros((), dtype=torch.float64, device="cuda:0")
+            err_max = torch.zeros((), dtype=torch.float64, device="cuda:0")
+            n_hit = torch.zeros((), dtype=torch.int64, device="cuda:0")
+            for s, (qp, qr, kl) in enumerate(wl):
+                a = mac.make_args(kv_lens=kl, q_rope=qr, kv_pages=wl.kv_pages, strides=kv.strides,
+                                  block_table=wl.block_table, out=o_mac, slot_ids=wl.slot_ids, q_pre=qp, match_pos=pos)
+                mac.decode_step(a, stream)
+                if s == 2 * gap - 1:
+                    mac.stats(reset=True)
+                if s >= 2 * gap:
+                    a.out = o_full.data_ptr()
+                    mac.full_decode(a, stream)
+                    e = (o_mac - o_full).double().norm(dim=-1) / o_full.double().norm(dim=-1)
+                    hit = pos >= 0
+                    err_sum += (e * hit).sum()
+                    err_max = torch.maximum(err_max, (e * hit).max())
+                    n_hit += hit.sum()
+            torch.cuda.synchronize()
+            st = mac.stats()
+            mac.close()
+            nh = int(n_hit.item())
+            row = {"gap": gap, "band": r, "mean_err": float(err_sum.item()) / max(1, nh), "max_err": float(err_max.item()),
+                   "hit_heads": nh, "mean_gap": round(st["sum_gap"] / max(1, st["hits"]), 1)}
+            rows.append(row)
+            log(f"[err-table] gap {gap:4d} band {r:4d}: mean Err {row['mean_err']:.3e}  max {row['max_err']:.3e}  "
+                f"(hits {nh}, measured gap {row['mean_gap']})")
+    del kv
+    torch.cuda.empty_cache()
+    return rows
+
+
 def cpu_baseline(name: str, torch, wl_mod, sample_steps: int):
     """The fp64 oracle as it stands, timed on the host cores on the first `sample_steps` decode steps of the
     same workload (rings start empty, so the sample is self-consistent)."""
@@ -262,6 +364,12 @@ def main():
     ap.add_argument("--paper-table", action="store_true",
                     help="also run the analogue of the paper's fine-grained latency table (batch 1, 32K/60K/120K x KV "
                          "budgets 1/5/10/20 %, K 1024, r 256) and add it to the JSON line as 'paper_table'")
+    ap.add_argument("--match-table", action="store_true",
+                    help="also run the Match-vs-Attention kernel micro-benchmark (GQA 8-2 / 32-8 / 40-10 x 512 / 1024 / "
+                         "2048 tokens) and add it to the JSON line as 'match_table'")
+    ap.add_argument("--err-table", action="store_true",
+                    help="also run the synthetic analogue of the rectification-error heat-map (error of MAC against full "
+                         "attention over reuse gap x band width) and add it as 'err_table'")
     ap.add_argument("--graph", action="store_true",
                     help="also time the headline config replayed from one captured HIP graph (off by default: on this "
                          "ROCm a replay costs more than the three eager launches it replaces)")
@@ -351,6 +459,10 @@ def main():
         line["configs_report"] = rep
     if a.paper_table:
         line["paper_table"] = paper_table(torch, mb, wl_mod)
+    if a.match_table:
+        line["match_table"] = match_table(torch, mb, wl_mod)
+    if a.err_table:
+        line["err_table"] = err_table(torch, mb, wl_mod)
     if not a.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(a.config, torch, wl_mod, a.cpu_steps)
     print(json.dumps(line), flush=True)

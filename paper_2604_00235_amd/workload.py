@@ -56,6 +56,12 @@ class WorkloadConfig:
     period_std: float = 0.0
     query_noise: float = 0.1
     jump_prob: float = 0.0
+    # Recency structure for the error-vs-gap report: a random direction u per (request, KV head) is added, with
+    # this weight, to every pre-RoPE key of that head and to every pre-RoPE query of its group.  After RoPE the
+    # common part contributes align^2 * sum_j |u_j|^2 cos(omega_j (m - t)) / sqrt(d) to the logit of key t under
+    # the query at m: largest for the newest keys and decaying with distance, as in a trained model's heads.
+    # 0 = off (drawn from a generator of its own, so the other streams do not move).
+    align: float = 0.0
 
     @property
     def group(self) -> int:
@@ -147,6 +153,12 @@ class Workload:
         gq = torch.Generator(device=dev)         # query process (own stream, so queries_only reproduces it)
         gq.manual_seed(cfg.seed + 7919)
         self._gen = gq
+        self._u = None
+        if cfg.align != 0.0:
+            ga = torch.Generator(device=dev)
+            ga.manual_seed(cfg.seed + 104729)
+            self._u = torch.randn((cfg.batch, cfg.num_kv_heads, cfg.head_dim), generator=ga, device=dev,
+                                  dtype=torch.float32)
         d, ps, hkv = cfg.head_dim, cfg.page_size, cfg.num_kv_heads
         ppr = cfg.pages_per_request
         num_pages = cfg.batch * ppr
@@ -166,6 +178,8 @@ class Workload:
                 ntok = (p1 - p0) * ps
                 kt = torch.randn((ntok, hkv, d), generator=g, device=dev, dtype=torch.float32)
                 v = torch.randn((ntok, hkv, d), generator=g, device=dev, dtype=torch.float32)
+                if self._u is not None:
+                    kt = kt + cfg.align * self._u[b].unsqueeze(0)
                 if cfg.use_rope:
                     pos = torch.arange(p0 * ps, p1 * ps, device=dev).view(ntok, 1)
                     kt = _rope(kt, pos, cfg.rope_theta)
@@ -211,6 +225,8 @@ class Workload:
             if cfg.regime_shift_every > 0 and s % cfg.regime_shift_every == 0:
                 self._mu = torch.randn(self._x.shape, generator=self._gen, device=self.device, dtype=torch.float32)
             x = self._x + self._mu if cfg.regime_shift_every > 0 else self._x
+        if self._u is not None:
+            x = x + cfg.align * self._u.repeat_interleave(cfg.group, dim=1)
         n = cfg.context + s + 1
         kv_lens = torch.full((cfg.batch,), n, device=self.device, dtype=torch.int32)
         if cfg.ragged > 0:
