@@ -169,11 +169,11 @@ __global__ __launch_bounds__(256, (HT == 1 ? 2 : 1)) void attn_kernel(const Attn
             const uint16_t* base = kv_g + (int64_t)pid * p.stride_page + (int64_t)(tb & page_mask) * p.stride_tok;
             const uint16_t* kp = base + (int64_t)min(krow, lim) * p.stride_tok + 8 * kg;
 #pragma unroll
-            for (int c = 0; c < 4; ++c) T.k[u][c] = *reinterpret_cast<const u32x4*>(kp + 32 * c);
+            for (int c = 0; c < 4; ++c) T.k[u][c] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kp + 32 * c));
             const uint16_t* vp = base + p.stride_kv + 8 * r16;
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                T.v[4 * u + i] = *reinterpret_cast<const u32x4*>(vp + (int64_t)min(4 * i + kg, lim) * p.stride_tok);
+                T.v[4 * u + i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vp + (int64_t)min(4 * i + kg, lim) * p.stride_tok));
         }
     };
 
