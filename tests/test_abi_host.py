@@ -82,6 +82,9 @@ def test_device_bytes_accounts_rings_and_workspace(lib):
     (dict(chunk_tokens=8192), mb.MAC_ATTN_ERR_INVALID_ARG),
     (dict(max_kv_len=0), mb.MAC_ATTN_ERR_INVALID_ARG),
     (dict(fuse_epilogue=2), mb.MAC_ATTN_ERR_INVALID_ARG),
+    (dict(max_gap=-1), mb.MAC_ATTN_ERR_INVALID_ARG),
+    (dict(group_match=2), mb.MAC_ATTN_ERR_INVALID_ARG),
+    (dict(out_dtype=3), mb.MAC_ATTN_ERR_INVALID_ARG),
 ])
 def test_bad_configs_are_rejected_before_any_gpu_call(lib, kw, code):
     cfg = _cfg(**kw)
@@ -111,3 +114,36 @@ def test_workload_thresholds_match_calibration_file():
     cal = json.load(open(os.path.join(ROOT, "tests", "golden", "c3_thresholds.json")))
     for name, rec in cal.items():
         assert abs(CONFIGS[name].threshold - rec["threshold"]) < 0.006, (name, CONFIGS[name].threshold, rec)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU only: bench.py --gpus 2 exits with a message instead of running."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr and not r.stdout.strip()
+
+
+def test_workload_streams_are_reproducible_and_independent():
+    """Inputs are a pure function of the config: two builds agree bit for bit; the query stream does not depend on
+    whether K/V were generated; the recency option draws from a stream of its own (align = 0 leaves K/V and the
+    queries unchanged); the recurring-query model repeats its base sequence with the stated period."""
+    import torch
+    from paper_2604_00235_amd.workload import Workload, WorkloadConfig, bf16_bits
+    cfg = WorkloadConfig(name="w", batch=2, num_q_heads=4, num_kv_heads=2, context=40, steps=12, window=4, band=3,
+                         threshold=3.0, rho=0.9, seed=3)
+    a, b, q = Workload(cfg), Workload(cfg), Workload(cfg, queries_only=True)
+    assert torch.equal(a.kv_pages, b.kv_pages) and torch.equal(a.block_table, b.block_table) and q.kv_pages is None
+    assert sorted(a.block_table.flatten().tolist()) == list(range(cfg.batch * cfg.pages_per_request))
+    for (p1, r1, l1), (p2, r2, l2), (p3, r3, l3) in zip(a, b, q):
+        assert torch.equal(p1, p2) and torch.equal(r1, r2) and torch.equal(l1, l2)
+        assert torch.equal(p1, p3) and torch.equal(r1, r3)
+        assert p1.dtype == torch.bfloat16 and l1.dtype == torch.int32
+    al = Workload(WorkloadConfig(**{**cfg.__dict__, "align": 0.5}))
+    assert not torch.equal(al.kv_pages[:, 0], a.kv_pages[:, 0])           # keys moved
+    assert torch.equal(al.kv_pages[:, 1], a.kv_pages[:, 1])               # values did not
+    rec = WorkloadConfig(name="r", batch=1, num_q_heads=2, num_kv_heads=1, context=10, steps=15, window=8, band=2,
+                         threshold=3.0, rho=0.0, seed=4, period=5, period_std=0.0, query_noise=0.0)
+    qs = [bf16_bits(p).copy() for p, _, _ in Workload(rec)]
+    for s in range(5, 15):
+        assert (qs[s] == qs[s - 5]).all() and not (qs[s] == qs[s - 1]).all()
