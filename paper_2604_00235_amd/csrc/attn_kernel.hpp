@@ -64,7 +64,8 @@ struct KVTile {
 template <int HT>   // number of 16-head tiles: 1 (G <= 16) or 2 (G <= 32)
 __global__ __launch_bounds__(256, (HT == 1 ? 2 : 1)) void attn_kernel(const AttnParams p) {
     const int b = blockIdx.z, g = blockIdx.y, x = blockIdx.x;
-    const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
+    const int tid = threadIdx.x, l = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave index as a scalar: tile positions and page bases stay in SGPRs
     const int r16 = l & 15, kg = l >> 4;
     const int G = p.G;
     const int C = p.chunk;
@@ -157,23 +158,34 @@ __global__ __launch_bounds__(256, (HT == 1 ? 2 : 1)) void attn_kernel(const Attn
     // All 16 loads of a tile are issued unconditionally (rows past the end re-read the last valid row, whose
     // scores are masked): with a fixed number of loads per tile the compiler can wait for exactly the older
     // tile's loads and leave the prefetched tile in flight.
+    // The page base of a sub-tile is wave-uniform (scalar registers); each lane adds a 32-bit byte offset that does
+    // not depend on the tile: its row times the token stride (clamped to the last valid row with one v_min) plus its
+    // 16-byte column.  So a load costs one or two vector instructions of address arithmetic.
     const int krow = 4 * (r16 & 3) + (r16 >> 2);               // sub-tile row this lane supplies to S = K Q^T
+    const uint32_t tok_bytes = (uint32_t)p.stride_tok * 2u;    // host checks stride_tok < 2^26
+    const uint32_t k_row_b = (uint32_t)krow * tok_bytes, k_col_b = 16u * (uint32_t)kg;
+    uint32_t v_row_b[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v_row_b[i] = (uint32_t)(4 * i + kg) * tok_bytes;
+    const uint32_t v_col_b = 16u * (uint32_t)r16;
     auto load_tile = [&](int k, KVTile& T) {
         const int t0 = (chunk_tile0 + w + 4 * k) * kTileTokens;
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             const bool past = t0 + 16 * u >= n;
             const int tb = past ? 0 : t0 + 16 * u;
-            const int lim = past ? 15 : n - 1 - tb;
+            const uint32_t lim_b = (uint32_t)(past ? 15 : min(15, n - 1 - tb)) * tok_bytes;   // last valid row, in bytes
             const int pid = __builtin_amdgcn_readlane(mypid, 2 * k + u);
-            const uint16_t* base = kv_g + (int64_t)pid * p.stride_page + (int64_t)(tb & page_mask) * p.stride_tok;
-            const uint16_t* kp = base + (int64_t)min(krow, lim) * p.stride_tok + 8 * kg;
+            const char* base = reinterpret_cast<const char*>(kv_g + (int64_t)pid * p.stride_page +
+                                                             (int64_t)(tb & page_mask) * p.stride_tok);
+            const char* kp = base + (min(k_row_b, lim_b) + k_col_b);
 #pragma unroll
-            for (int c = 0; c < 4; ++c) T.k[u][c] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kp + 32 * c));
-            const uint16_t* vp = base + p.stride_kv + 8 * r16;
+            for (int c = 0; c < 4; ++c) T.k[u][c] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kp + 64 * c));
+            const char* vbase = base + 2 * p.stride_kv;
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                T.v[4 * u + i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vp + (int64_t)min(4 * i + kg, lim) * p.stride_tok));
+                T.v[4 * u + i] = __builtin_nontemporal_load(
+                    reinterpret_cast<const u32x4*>(vbase + (min(v_row_b[i], lim_b) + v_col_b)));
         }
     };
 

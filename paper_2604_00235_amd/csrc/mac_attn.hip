@@ -147,7 +147,8 @@ int validate_args(const mac_attn_ctx* ctx, const mac_attn_step_args* a, bool nee
     const int64_t st[4] = {a->stride_page, a->stride_kv, a->stride_head, a->stride_tok};
     for (int64_t s : st)
         if (s <= 0 || (s % 8) != 0) return MAC_ATTN_ERR_INVALID_ARG;
-    if (a->stride_tok < mac::kHeadDim) return MAC_ATTN_ERR_INVALID_ARG;
+    // the kernels form row offsets inside a 16-token sub-tile in 32 bits
+    if (a->stride_tok < mac::kHeadDim || a->stride_tok >= (1 << 26)) return MAC_ATTN_ERR_INVALID_ARG;
     // 16-byte vector loads: base pointers must be 16-byte aligned
     if ((reinterpret_cast<uintptr_t>(a->kv_pages) & 15u) || (reinterpret_cast<uintptr_t>(a->q_rope) & 15u)) return MAC_ATTN_ERR_INVALID_ARG;
     if (need_pre && (reinterpret_cast<uintptr_t>(a->q_pre) & 15u)) return MAC_ATTN_ERR_INVALID_ARG;
