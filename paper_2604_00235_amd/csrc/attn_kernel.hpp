@@ -62,6 +62,8 @@ struct AttnParams {
     int32_t n_mid_slots, n_slots;
     int32_t max_kv_len;
     float scale_log2;            // sm_scale * log2(e)
+    unsigned long long* st_read; // [batch*Hkv] KV tokens streamed per group (counter); null for full decode
+    unsigned long long* st_full; // [batch*Hkv] KV tokens a full decode would stream
 };
 
 struct KVTile {
@@ -123,6 +125,13 @@ __global__ __launch_bounds__(256, (HT == 1 ? 2 : 1)) void attn_kernel(const Attn
                     if (base + i == ht * 16 + r16) my_start[ht] = si;
             }
         }
+    }
+    // KV tokens streamed by this step for the group (read once per group from its smallest start, Sec. 5.8):
+    // counted by the group's first work-group, which always exists.  One writer per address and step, so the
+    // atomics only make the adds fire-and-forget.
+    if (x == 0 && tid == 0 && p.st_read != nullptr) {
+        atomicAdd(&p.st_read[b * gridDim.y + g], (unsigned long long)(n - gs));
+        atomicAdd(&p.st_full[b * gridDim.y + g], (unsigned long long)n);
     }
     int lo, hi;
     if (is_mid) {

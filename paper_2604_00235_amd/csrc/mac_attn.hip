@@ -233,6 +233,9 @@ int launch_attention(mac_attn_ctx* ctx, const mac_attn_step_args* a, bool mac_mo
     p.n_slots = L.n_slots;
     p.max_kv_len = c.max_kv_len;
     p.scale_log2 = ctx->sm_scale * mac::kLog2e;
+    const int64_t bh = (int64_t)c.max_batch * c.num_q_heads;
+    p.st_read = mac_mode ? ctx->stats + 3 * bh : nullptr;
+    p.st_full = mac_mode ? ctx->stats + 3 * bh + (int64_t)c.max_batch * c.num_kv_heads : nullptr;
     const int gx = mac_mode ? L.n_slots : L.n_mid_slots;
     dim3 grid(gx, c.num_kv_heads, a->batch), block(256);
     if (L.G <= 16)
@@ -265,8 +268,6 @@ mac::MergeParams merge_params(mac_attn_ctx* ctx, const mac_attn_step_args* a, bo
     p.out_lse = a->out_lse;
     p.rect_O = stage_rect ? ctx->rect : nullptr;
     p.rect_lse = stage_rect ? ctx->rect + bh * mac::kHeadDim : nullptr;
-    p.st_read = mac_mode ? ctx->stats + 3 * bh : nullptr;
-    p.st_full = mac_mode ? ctx->stats + 3 * bh + (int64_t)c.max_batch * c.num_kv_heads : nullptr;
     p.Hq = c.num_q_heads;
     p.G = L.G;
     p.W = c.window;

@@ -52,8 +52,6 @@ struct MergeParams {
     float* out_lse;              // optional [batch, Hq]
     float* rect_O;               // staging for a separate write-back kernel [batch*Hq, 128]; may be null
     float* rect_lse;             // [batch*Hq]
-    unsigned long long* st_read; // per (b, kv head) accumulators; null for full decode
-    unsigned long long* st_full;
     int32_t Hq, G, W, band, chunk, n_mid_slots, n_slots, max_kv_len;
 };
 
@@ -207,22 +205,6 @@ __device__ __forceinline__ void merge_head(const MergeParams& p, const Writeback
                 atomicAdd(&p.st_hits[bh], 1ull);
                 atomicAdd(&p.st_gap[bh], (unsigned long long)(n - md.np));
                 atomicAdd(&p.st_skip[bh], (double)md.start / (double)n);
-            }
-        }
-        // KV tokens streamed by this step for the KV group (read once per group from its smallest start)
-        if ((h % p.G) == 0) {
-            int gs = nb;
-            const int hpp = 64 / p.mv.n_split;
-            for (int base = 0; base < p.G; base += hpp) {
-                const int cnt = min(hpp, p.G - base);
-                const MatchDecision g = match_decide_wave(p.mv, bh + base, cnt, tid, n);
-                const int gstart = clampi(g.start, 0, nb);
-                for (int i = 0; i < cnt; ++i) gs = min(gs, __builtin_amdgcn_readlane(gstart, i * p.mv.n_split));
-            }
-            if (tid == 0) {
-                const int bg = bh / p.G;
-                atomicAdd(&p.st_read[bg], (unsigned long long)(n - gs));
-                atomicAdd(&p.st_full[bg], (unsigned long long)n);
             }
         }
     }
