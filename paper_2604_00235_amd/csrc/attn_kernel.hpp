@@ -62,6 +62,7 @@ struct AttnParams {
     int32_t n_mid_slots, n_slots;
     int32_t max_kv_len;
     float scale_log2;            // sm_scale * log2(e)
+    const int32_t* head_start;   // [batch*Hq + 32] start of each head's fresh range if the match kernel stored it, else null
     unsigned long long* st_read; // [batch*Hkv] KV tokens streamed per group (counter); null for full decode
     unsigned long long* st_full; // [batch*Hkv] KV tokens a full decode would stream
 };
@@ -102,6 +103,31 @@ __global__ __launch_bounds__(256, (HT == 1 ? 2 : 1)) void attn_kernel(const Attn
     if (!is_mid) {                                           // a band chunk's position needs kv_len only
         chunk_tile0 = (nb / C + (x - p.n_mid_slots)) * tiles_per_chunk;
         fetch_pid();
+    }
+
+    // With the heads' starts stored by the match kernel, a work-group without work finds that out from G scalar
+    // loads issued together with kv_len, without the cross-lane reduction of the match results below.
+    if (p.head_start != nullptr && x != 0) {
+        // (the array is padded by 32 entries, so that blocks of 16 loads can be issued without a bound check)
+        int gs0 = nb;
+        for (int i0 = 0; i0 < G; i0 += 16) {
+            int t[16];
+#pragma unroll
+            for (int j = 0; j < 16; ++j) t[j] = p.head_start[hbase + i0 + j];
+#pragma unroll
+            for (int j = 0; j < 16; ++j)
+                if (i0 + j < G) gs0 = min(gs0, t[j]);
+        }
+        int lo0, hi0;
+        if (is_mid) {
+            lo0 = max(gs0, x * C);
+            hi0 = min(nb, (x + 1) * C);
+        } else {
+            const int c0 = nb / C + (x - p.n_mid_slots);
+            lo0 = max(nb, c0 * C);
+            hi0 = min(n, (c0 + 1) * C);
+        }
+        if (lo0 >= hi0) return;
     }
 
     // smallest and largest start among the group's heads

@@ -64,6 +64,11 @@ struct MatchDecision {
     int32_t start;  // first key this head has to recompute: max(0, n_p - B) on a hit, 0 on a miss
 };
 
+// Acceptance of the nearest candidate (d2, np) of a whole window at length n: threshold, then the optional distance cap.
+__device__ __forceinline__ bool match_accept(const MatchView& mv, double d2, int np, int n) {
+    return np >= 1 && d2 < mv.T2 && (mv.max_gap <= 0 || n - np <= mv.max_gap);
+}
+
 // Final reduction over the slices and threshold test (paper Eq. (accept); Sec. 4.2 K1 "final reducer").
 // Every consumer (attention kernel, merge kernel) evaluates it itself from the same slice results, so the
 // decision needs no extra kernel and no inter-work-group synchronisation.
@@ -87,7 +92,7 @@ __device__ __forceinline__ MatchDecision match_decide_wave(const MatchView& mv, 
         if (better(od2, onp, c.d2, c.np)) { c.d2 = od2; c.np = onp; c.j = oj; }
     }
     r.d2 = c.d2;
-    if (c.np >= 1 && c.d2 < mv.T2 && (mv.max_gap <= 0 || n - c.np <= mv.max_gap)) {
+    if (match_accept(mv, c.d2, c.np, n)) {
         r.np = c.np;
         r.j = c.j;
         r.start = c.np - mv.band > 0 ? c.np - mv.band : 0;

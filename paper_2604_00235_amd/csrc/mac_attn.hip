@@ -45,10 +45,10 @@ int default_chunk(int64_t groups, int64_t max_kv_len, int heads_per_group) {
 struct Layout {            // derived sizes, pure host arithmetic
     int G, chunk, n_mid_slots, n_band_slots, n_slots, page_shift, max_split;
     int64_t ring_q_bytes, ring_O_bytes, ring_lse_bytes, ring_npos_bytes;
-    int64_t part_O_bytes, part_lse_bytes, match_bytes, rect_bytes, stats_bytes;
+    int64_t part_O_bytes, part_lse_bytes, match_bytes, rect_bytes, stats_bytes, head_start_bytes;
     int64_t total() const {
         return ring_q_bytes + ring_O_bytes + ring_lse_bytes + ring_npos_bytes + part_O_bytes + part_lse_bytes +
-               match_bytes + rect_bytes + stats_bytes;
+               match_bytes + rect_bytes + stats_bytes + head_start_bytes;
     }
 };
 
@@ -91,6 +91,7 @@ int validate_config(const mac_attn_config* c, Layout* L) {
     L->match_bytes = bh * L->max_split * (int64_t)sizeof(mac::MatchPartial);
     L->rect_bytes = bh * (mac::kHeadDim + 1) * 4;
     L->stats_bytes = bh * 3 * 8 + (int64_t)c->max_batch * c->num_kv_heads * 2 * 8 + 2 * 8;
+    L->head_start_bytes = (bh + 32) * 4;                    // padded: read in blocks of 16 without a bound check
     return MAC_ATTN_OK;
 }
 
@@ -116,6 +117,7 @@ struct mac_attn_ctx {
     float* part_lse = nullptr;
     mac::MatchPartial* m_part = nullptr;   // [bh, n_split] nearest entry per window slice (match kernel)
     int32_t n_split = 1;                   // slices used by the current / last decode_step
+    int32_t* head_start = nullptr;         // [max_batch*Hq] fresh-range start per head, written by the match kernel when n_split == 1
     float* rect = nullptr;        // [bh*128] rows then [bh] lse
     // counters
     unsigned long long* stats = nullptr;
@@ -234,6 +236,7 @@ int launch_attention(mac_attn_ctx* ctx, const mac_attn_step_args* a, bool mac_mo
     p.max_kv_len = c.max_kv_len;
     p.scale_log2 = ctx->sm_scale * mac::kLog2e;
     const int64_t bh = (int64_t)c.max_batch * c.num_q_heads;
+    p.head_start = (mac_mode && ctx->n_split == 1) ? ctx->head_start : nullptr;
     p.st_read = mac_mode ? ctx->stats + 3 * bh : nullptr;
     p.st_full = mac_mode ? ctx->stats + 3 * bh + (int64_t)c.max_batch * c.num_kv_heads : nullptr;
     const int gx = mac_mode ? L.n_slots : L.n_mid_slots;
@@ -348,7 +351,7 @@ void mac_attn_destroy(mac_attn_ctx* ctx) {
     if (hipGetDevice(&cur) == hipSuccess && cur != ctx->cfg.device) (void)hipSetDevice(ctx->cfg.device);
     (void)hipDeviceSynchronize();
     void* bufs[] = {ctx->ring_q, ctx->ring_O, ctx->ring_lse, ctx->ring_npos, ctx->part_O, ctx->part_lse,
-                    ctx->m_part, ctx->rect, ctx->stats};
+                    ctx->m_part, ctx->rect, ctx->stats, ctx->head_start};
     for (void* b : bufs)
         if (b != nullptr) (void)hipFree(b);
     for (TimedCall& t : ctx->timed)
@@ -383,6 +386,7 @@ int mac_attn_init(const mac_attn_config* cfg, mac_attn_ctx** out_ctx) {
         {reinterpret_cast<void**>(&ctx->m_part), L.match_bytes, true},
         {reinterpret_cast<void**>(&ctx->rect), L.rect_bytes, true},
         {reinterpret_cast<void**>(&ctx->stats), L.stats_bytes, true},
+        {reinterpret_cast<void**>(&ctx->head_start), L.head_start_bytes, true},
     };
     for (auto& a : allocs) {
         hipError_t e = hipMalloc(a.p, (size_t)a.bytes);
@@ -464,6 +468,8 @@ int mac_attn_decode_step(mac_attn_ctx* ctx, const mac_attn_step_args* args, void
         }
         ctx->n_split = split;
         p.n_split = split;
+        p.head_start = split == 1 ? ctx->head_start : nullptr;
+        p.mv = match_view(ctx, true);
         if (!c.group_match) {
             dim3 grid(c.num_q_heads, args->batch, split), block(mac::kMatchThreads);
             hipLaunchKernelGGL(mac::match_kernel, grid, block, 0, stream, p);

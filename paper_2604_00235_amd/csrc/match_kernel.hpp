@@ -41,8 +41,21 @@ struct MatchParams {
     int32_t Hq, W, max_kv_len;
     int32_t n_split;             // window slices per head = gridDim.z
     int32_t rows_per_split;      // multiple of 64 (match_kernel) / of 16 with rows_per_split * G <= 4096 (group kernel)
-    int32_t G;                   // heads per KV group (group kernel only)
+    int32_t G;                   // heads per KV group
+    // With a single window slice the kernel knows each head's final decision: it then also stores the start of the
+    // head's fresh range, so that an attention work-group can tell from a few scalar loads (no cross-lane
+    // reduction of the match results) whether it has anything to do.  nullptr when n_split > 1.
+    int32_t* head_start;         // [batch*Hq]
+    MatchView mv;                // threshold, band and distance cap of the acceptance rule (part / n_split unused)
 };
+
+// start of the fresh range of a head whose nearest window entry is (d2, np): max(0, np - B) on a hit, else 0;
+// clamped to the start of the last-B band like everywhere else
+__device__ __forceinline__ int head_start(const MatchView& mv, double d2, int np, int n) {
+    const int nb = n - mv.band > 0 ? n - mv.band : 0;
+    const int s = match_accept(mv, d2, np, n) ? (np - mv.band > 0 ? np - mv.band : 0) : 0;
+    return s < nb ? s : nb;
+}
 
 __device__ __forceinline__ double bf16_lo_to_f64(uint32_t pair) { return (double)bits_to_float(pair << 16); }
 __device__ __forceinline__ double bf16_hi_to_f64(uint32_t pair) { return (double)bits_to_float(pair & 0xffff0000u); }
@@ -132,6 +145,7 @@ __global__ __launch_bounds__(kMatchThreads) void match_kernel(const MatchParams 
         for (int w = 1; w < kWaves; ++w)
             if (better(s_d2[w], s_np[w], best_d2, best_np)) { best_d2 = s_d2[w]; best_np = s_np[w]; best_j = s_j[w]; }
         p.part[(int64_t)bh * p.n_split + sp] = MatchPartial{best_d2, best_np, best_j};
+        if (p.head_start != nullptr) p.head_start[bh] = head_start(p.mv, best_d2, best_np, n);
     }
 }
 
@@ -202,6 +216,7 @@ __global__ __launch_bounds__(kMatchThreads) void match_group_kernel(const MatchP
         for (int w = 1; w < kWaves; ++w)
             if (better(s_d2[w], s_np[w], best_d2, best_np)) { best_d2 = s_d2[w]; best_np = s_np[w]; best_j = s_j[w]; }
         p.part[((int64_t)b * p.Hq + g * G + tid) * p.n_split + sp] = MatchPartial{best_d2, best_np, best_j};
+        if (p.head_start != nullptr) p.head_start[b * p.Hq + g * G + tid] = head_start(p.mv, best_d2, best_np, n);
     }
 }
 

@@ -63,7 +63,8 @@ def test_device_bytes_accounts_rings_and_workspace(lib):
     n_slots = (131200 + 1023) // 1024 + (128 + 1023) // 1024 + 1
     work = 4 * 32 * n_slots * (128 + 1) * 4
     # the rest is small: match slice results (64 x 16 B per head), write-back staging, counters
-    assert total - rings - work == 4 * 32 * (64 * 16 + 129 * 4 + 3 * 8) + 4 * 8 * 2 * 8 + 2 * 8
+    # and one word per head (+ 32 of padding) for the fresh-range start the match kernel stores
+    assert total - rings - work == 4 * 32 * (64 * 16 + 129 * 4 + 3 * 8 + 4) + 32 * 4 + 4 * 8 * 2 * 8 + 2 * 8
 
 
 @pytest.mark.parametrize("kw,code", [
