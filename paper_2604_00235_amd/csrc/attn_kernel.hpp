@@ -74,7 +74,18 @@ struct KVTile {
 
 template <int HT>   // number of 16-head tiles: 1 (G <= 16) or 2 (G <= 32)
 __global__ __launch_bounds__(256, (HT == 1 ? 2 : 1)) void attn_kernel(const AttnParams p) {
-    const int b = blockIdx.z, g = blockIdx.y, x = blockIdx.x;
+    // Grid = (KV groups = requests x kv heads, work-item slots).  Work-groups are dispatched in linear order and dealt
+    // to the 8 XCDs round-robin.  A slot level is dispatched for all groups before the next one (neighbours then read
+    // neighbouring heads of the same pages; measured 165 vs 174 us on 8 x 8 groups of 32768 tokens and 174 vs 200 us
+    // on 32 x 8 groups of 8450 tokens against a slot-fastest order, whose unused slots sit between long work items),
+    // from the last slot down (the band and the newest chunks, where a hit has its work, start first), and the groups
+    // are rotated by one position per level, so that the chunks of one group go to all XCDs in turn (without the
+    // rotation a group with a miss keeps one XCD busy while others idle: 244 vs 154 us at 89 % hits).
+    const int Hkv = p.Hq / p.G;
+    const int pairs = gridDim.x;
+    const int x = gridDim.y - 1 - blockIdx.y;
+    const int q = (int)((blockIdx.x + blockIdx.y) % (unsigned)pairs);
+    const int b = q / Hkv, g = q - b * Hkv;
     const int tid = threadIdx.x, l = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave index as a scalar: tile positions and page bases stay in SGPRs
     const int r16 = l & 15, kg = l >> 4;
@@ -156,8 +167,8 @@ __global__ __launch_bounds__(256, (HT == 1 ? 2 : 1)) void attn_kernel(const Attn
     // counted by the group's first work-group, which always exists.  One writer per address and step, so the
     // atomics only make the adds fire-and-forget.
     if (x == 0 && tid == 0 && p.st_read != nullptr) {
-        atomicAdd(&p.st_read[b * gridDim.y + g], (unsigned long long)(n - gs));
-        atomicAdd(&p.st_full[b * gridDim.y + g], (unsigned long long)n);
+        atomicAdd(&p.st_read[b * Hkv + g], (unsigned long long)(n - gs));
+        atomicAdd(&p.st_full[b * Hkv + g], (unsigned long long)n);
     }
     int lo, hi;
     if (is_mid) {

@@ -76,6 +76,7 @@ int validate_config(const mac_attn_config* c, Layout* L) {
     const int band_span = c->band < c->max_kv_len ? c->band : c->max_kv_len;
     L->n_band_slots = band_span == 0 ? 0 : (band_span + chunk - 1) / chunk + 1;
     L->n_slots = L->n_mid_slots + L->n_band_slots;
+    if (L->n_slots > 65535) return MAC_ATTN_ERR_INVALID_ARG;      // grid dimension y
     int sh = 0;
     while ((1 << sh) < c->page_size) ++sh;
     L->page_shift = sh;
@@ -240,7 +241,7 @@ int launch_attention(mac_attn_ctx* ctx, const mac_attn_step_args* a, bool mac_mo
     p.st_read = mac_mode ? ctx->stats + 3 * bh : nullptr;
     p.st_full = mac_mode ? ctx->stats + 3 * bh + (int64_t)c.max_batch * c.num_kv_heads : nullptr;
     const int gx = mac_mode ? L.n_slots : L.n_mid_slots;
-    dim3 grid(gx, c.num_kv_heads, a->batch), block(256);
+    dim3 grid(c.num_kv_heads * a->batch, gx), block(256);
     if (L.G <= 16)
         hipLaunchKernelGGL(mac::attn_kernel<1>, grid, block, 0, stream, p);
     else
