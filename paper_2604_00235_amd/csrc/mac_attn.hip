@@ -32,8 +32,8 @@ int hip_fail(hipError_t e, const char* what) {
 // 512 work-groups the chip holds), within [512, 2048]; and at least 64 tokens per head of the group, so that
 // the partial a work item writes (516 B per head) stays below ~1.5 % of the K/V it reads (512 B per token) --
 // at 32 heads per KV head (MQA) a 512-token item would write 6 %, and measured 153 us against 112 us at 2048.
-// (4096-token items stream a full-length step 1.7 % faster on 32 groups of 131072 tokens, but balance worse when
-// most groups reuse a prefix -- 160 us against 154 us at 89 % hits -- and on many short requests.)
+// (4096-token items stream a full-length step 1-3 % faster (11 % for MQA), but balance worse when most groups
+// reuse a prefix and a few do not: 168 us against 156 us at 89 % hits on 32 groups of 131072 tokens.)
 int default_chunk(int64_t groups, int64_t max_kv_len, int heads_per_group) {
     const int64_t target = groups * max_kv_len / 2048;
     int chunk = 512;
