@@ -29,7 +29,7 @@ KV_BYTES_PER_TOKEN_HEAD = 512   # K row + V row, bf16, d = 128
 # HBM bytes per attention-kernel launch from two rocprofv3 --pmc runs of this command with its default arguments
 # (FETCH_SIZE x 2.0000 + WRITE_SIZE x 1.0000, scale factors from a 1 GiB copy; profiles/attn_kernel_C3_128k_pmc_traffic.txt).
 # Only valid for exactly that workload and step range, so it is reported for no other.
-PROFILED_TRAFFIC = {("C3_rho97", 40, 8): {"mac": 2.03310e9, "full": 2.16312e9}}
+PROFILED_TRAFFIC = {("C3_rho97", 40, 8): {"mac": 2.03274e9, "full": 2.16283e9}}
 
 
 def log(msg: str):
