@@ -61,6 +61,7 @@ struct AttnParams {
     int32_t chunk;               // tokens per work item, multiple of 32, <= 4096
     int32_t n_mid_slots, n_slots;
     int32_t max_kv_len;
+    int32_t group_fastest;       // dispatch order, see the kernel
     float scale_log2;            // sm_scale * log2(e)
     const int32_t* head_start;   // [batch*Hq + 32] start of each head's fresh range if the match kernel stored it, else null
     unsigned long long* st_read; // [batch*Hkv] KV tokens streamed per group (counter); null for full decode
@@ -74,17 +75,25 @@ struct KVTile {
 
 template <int HT>   // number of 16-head tiles: 1 (G <= 16) or 2 (G <= 32)
 __global__ __launch_bounds__(256, (HT == 1 ? 2 : 1)) void attn_kernel(const AttnParams p) {
-    // Grid = (KV groups = requests x kv heads, work-item slots).  Work-groups are dispatched in linear order and dealt
-    // to the 8 XCDs round-robin.  A slot level is dispatched for all groups before the next one (neighbours then read
-    // neighbouring heads of the same pages; measured 165 vs 174 us on 8 x 8 groups of 32768 tokens and 174 vs 200 us
-    // on 32 x 8 groups of 8450 tokens against a slot-fastest order, whose unused slots sit between long work items),
-    // from the last slot down (the band and the newest chunks, where a hit has its work, start first), and the groups
-    // are rotated by one position per level, so that the chunks of one group go to all XCDs in turn (without the
-    // rotation a group with a miss keeps one XCD busy while others idle: 244 vs 154 us at 89 % hits).
+    // Work-groups are dispatched in linear order and dealt to the 8 XCDs round-robin; slots always run from the last
+    // one down (the band and the newest chunks, where a hit has its work, start first).  Two orders (p.group_fastest):
+    //  1: grid = (KV groups, slots).  A slot level is dispatched for all groups before the next one: neighbours read
+    //     neighbouring heads of the same pages, and the unused slots of max_kv_len do not sit between long work items
+    //     (measured 165 vs 174 us on 8 x 8 groups of 32768 tokens, 174 vs 200 us on 32 x 8 groups of 8450 tokens).
+    //     The groups are rotated by one position per level, so that the chunks of one group go to all XCDs in turn
+    //     (without the rotation a group with a miss keeps one XCD busy while others idle: 244 vs 154 us at 89 % hits).
+    //  0: grid = (slots, KV groups).  All slots of a group are dispatched in one burst.  With few groups that serves a
+    //     miss of one group faster: in order 1 its work items are spread over the whole dispatch sequence, most of
+    //     which is work-groups with nothing to do (batch 1, 120K, 1-3 of 8 groups missing: 42 vs 54 us per step).
     const int Hkv = p.Hq / p.G;
-    const int pairs = gridDim.x;
-    const int x = gridDim.y - 1 - blockIdx.y;
-    const int q = (int)((blockIdx.x + blockIdx.y) % (unsigned)pairs);
+    int x, q;
+    if (p.group_fastest) {
+        x = gridDim.y - 1 - blockIdx.y;
+        q = (int)((blockIdx.x + blockIdx.y) % gridDim.x);
+    } else {
+        x = gridDim.x - 1 - blockIdx.x;
+        q = blockIdx.y;
+    }
     const int b = q / Hkv, g = q - b * Hkv;
     const int tid = threadIdx.x, l = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave index as a scalar: tile positions and page bases stay in SGPRs

@@ -34,6 +34,9 @@ int hip_fail(hipError_t e, const char* what) {
 // at 32 heads per KV head (MQA) a 512-token item would write 6 %, and measured 153 us against 112 us at 2048.
 // (4096-token items stream a full-length step 1-3 % faster (11 % for MQA), but balance worse when most groups
 // reuse a prefix and a few do not: 168 us against 156 us at 89 % hits on 32 groups of 131072 tokens.)
+// KV groups (requests x kv heads) from which the attention grid is dispatched group-fastest (see attn_kernel)
+constexpr int kGroupFastestFrom = 64;
+
 int default_chunk(int64_t groups, int64_t max_kv_len, int heads_per_group) {
     const int64_t target = groups * max_kv_len / 2048;
     int chunk = 512;
@@ -76,7 +79,7 @@ int validate_config(const mac_attn_config* c, Layout* L) {
     const int band_span = c->band < c->max_kv_len ? c->band : c->max_kv_len;
     L->n_band_slots = band_span == 0 ? 0 : (band_span + chunk - 1) / chunk + 1;
     L->n_slots = L->n_mid_slots + L->n_band_slots;
-    if (L->n_slots > 65535) return MAC_ATTN_ERR_INVALID_ARG;      // grid dimension y
+    if (L->n_slots > 65535) return MAC_ATTN_ERR_INVALID_ARG;      // a grid dimension
     int sh = 0;
     while ((1 << sh) < c->page_size) ++sh;
     L->page_shift = sh;
@@ -241,7 +244,10 @@ int launch_attention(mac_attn_ctx* ctx, const mac_attn_step_args* a, bool mac_mo
     p.st_read = mac_mode ? ctx->stats + 3 * bh : nullptr;
     p.st_full = mac_mode ? ctx->stats + 3 * bh + (int64_t)c.max_batch * c.num_kv_heads : nullptr;
     const int gx = mac_mode ? L.n_slots : L.n_mid_slots;
-    dim3 grid(c.num_kv_heads * a->batch, gx), block(256);
+    const int pairs = c.num_kv_heads * a->batch;
+    p.group_fastest = pairs >= kGroupFastestFrom ? 1 : 0;
+    const dim3 grid = p.group_fastest ? dim3(pairs, gx) : dim3(gx, pairs);
+    const dim3 block(256);
     if (L.G <= 16)
         hipLaunchKernelGGL(mac::attn_kernel<1>, grid, block, 0, stream, p);
     else
