@@ -35,7 +35,7 @@ int hip_fail(hipError_t e, const char* what) {
 // (4096-token items stream a full-length step 1-3 % faster (11 % for MQA), but balance worse when most groups
 // reuse a prefix and a few do not: 168 us against 156 us at 89 % hits on 32 groups of 131072 tokens.)
 // KV groups (requests x kv heads) from which the attention grid is dispatched group-fastest (see attn_kernel)
-constexpr int kGroupFastestFrom = 64;
+constexpr int kGroupFastestFrom = 16;
 
 int default_chunk(int64_t groups, int64_t max_kv_len, int heads_per_group) {
     const int64_t target = groups * max_kv_len / 2048;
