@@ -138,12 +138,13 @@ def test_error_paths_on_device():
     mac.close()
 
 
-@pytest.mark.parametrize("hq,hkv,window,batch", [(32, 8, 1024, 1), (16, 2, 1024, 1), (32, 1, 256, 2), (8, 2, 200, 3)])
+@pytest.mark.parametrize("hq,hkv,window,batch", [(32, 8, 1024, 1), (16, 2, 1024, 1), (32, 1, 256, 2), (8, 2, 200, 3),
+                                                 (8, 2, 4096, 1)])
 def test_recurring_queries_large_window_split_match(hq, hkv, window, batch):
     """Second query model (reuse gaps of tens to hundreds of tokens with skew inside a KV group, whole-group misses):
     exercises large windows, where the matcher cuts the window into slices (16 slices at W=1024 and batch 1) and
     the consumers finish the argmin, including groups that need more than one wave pass (G x slices > 64) and a
-    window that is not a multiple of the slice size."""
+    window that is not a multiple of the slice size, and the largest window (32 slices)."""
     from tests.gpu_harness import run_parity
     cfg = WorkloadConfig(name=f"recur{hq}_{hkv}_{window}", batch=batch, num_q_heads=hq, num_kv_heads=hkv, context=1500,
                          steps=150, window=window, band=48, threshold=T_DEFAULT, rho=0.0, seed=21, period=40,
