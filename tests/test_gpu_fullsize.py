@@ -20,21 +20,21 @@ from paper_2604_00235_amd.workload import CONFIGS, Workload, WorkloadConfig, bf1
 pytestmark = pytest.mark.gpu
 
 
-def _group_oracle(cfg: WorkloadConfig, kvp_g: np.ndarray):
+def _group_oracle(cfg: WorkloadConfig, kvp_g: np.ndarray, **variant):
     from oracle.mac_oracle import Oracle
     ps, d = cfg.page_size, cfg.head_dim
     return Oracle(num_q_heads=cfg.group, num_kv_heads=1, head_dim=d, page_size=ps, window=cfg.window,
-                  band=cfg.band, threshold=cfg.threshold, strides=(2 * ps * d, ps * d, ps * d, d), max_slots=1)
+                  band=cfg.band, threshold=cfg.threshold, strides=(2 * ps * d, ps * d, ps * d, d), max_slots=1, **variant)
 
 
-def run_fullsize(cfg: WorkloadConfig, steps: int, groups, full_heads):
+def run_fullsize(cfg: WorkloadConfig, steps: int, groups, full_heads, **variant):
     from oracle.mac_oracle import Oracle
     from tests.gpu_harness import GpuRun, check_rows, say
     say(f"[fullsize] {cfg.name}: batch={cfg.batch} Hq/Hkv={cfg.num_q_heads}/{cfg.num_kv_heads} context={cfg.context} "
         f"steps={steps} W={cfg.window} B={cfg.band} T={cfg.threshold:.4g} groups={groups}")
     cfg = scaled(cfg, steps=steps)
     wl = Workload(cfg, device="cuda:0")
-    run = GpuRun(cfg, wl)                       # default chunk_tokens, as bench.py
+    run = GpuRun(cfg, wl, **variant)            # default chunk_tokens, as bench.py
     kvp = bf16_bits(wl.kv_pages)
     bt = wl.block_table.cpu().numpy()
     slots = wl.slot_ids.cpu().numpy()
@@ -42,12 +42,12 @@ def run_fullsize(cfg: WorkloadConfig, steps: int, groups, full_heads):
     # matcher-only oracle for all heads (rings of queries only)
     morc = Oracle(num_q_heads=cfg.num_q_heads, num_kv_heads=cfg.num_kv_heads, head_dim=cfg.head_dim,
                   page_size=cfg.page_size, window=cfg.window, band=cfg.band, threshold=cfg.threshold,
-                  strides=wl.strides, max_slots=cfg.batch)
+                  strides=wl.strides, max_slots=cfg.batch, **variant)
     # full oracles for the sampled groups
     gorc = {}
     for (b, g) in groups:
         kv_g = np.ascontiguousarray(kvp[:, :, g:g + 1])
-        gorc[(b, g)] = (_group_oracle(cfg, kv_g), kv_g, bt[b:b + 1].copy())
+        gorc[(b, g)] = (_group_oracle(cfg, kv_g, **variant), kv_g, bt[b:b + 1].copy())
     worst = 0.0
     hits = 0
     for s, (q_pre, q_rope, kv_lens) in enumerate(wl):
@@ -106,6 +106,14 @@ def test_c2_llama_32k_full_size():
 def test_c3_long_context_128k_full_size(name):
     hits, st = run_fullsize(CONFIGS[name], steps=10, groups=[(1, 2), (3, 7)], full_heads=[(2, 9)])
     assert 0 < hits < st["head_steps"]
+
+
+def test_c3_long_context_128k_one_reuse_point_per_group():
+    """The headline workload with group-granular matching (the extra leg of bench.py's sweep): a group hits as a
+    whole, so about half of the KV reads go away at the threshold that gives 49 % per-head hits."""
+    hits, st = run_fullsize(CONFIGS["C3_rho97"], steps=10, groups=[(0, 3), (2, 6)], full_heads=[(1, 20)], group_match=True)
+    assert 0 < hits < st["head_steps"] and hits % 4 == 0
+    assert st["kv_tokens_read"] < 0.75 * st["kv_tokens_full"]
 
 
 def test_c4_mqa_64k_full_size_all_miss_and_matched():
