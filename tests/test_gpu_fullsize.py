@@ -102,6 +102,14 @@ def test_c2_llama_32k_full_size():
     assert hits == st["head_steps"] - 8 * 32          # every step after the first hits
 
 
+def test_c2_ragged_lengths_mixed_hits():
+    """C2 geometry with request lengths 32768, 29767, ..., 11761 (not multiples of anything) and a threshold near
+    the lag-1 distance, so that groups with and without a miss, and slots past the end of short requests, mix."""
+    cfg = scaled(CONFIGS["C2"], ragged=3001, threshold=2.8)
+    hits, st = run_fullsize(cfg, steps=10, groups=[(0, 1), (7, 4)], full_heads=[(5, 30)])
+    assert 0 < hits < st["head_steps"]
+
+
 @pytest.mark.parametrize("name", ["C3_rho97", "C3_rho99"])
 def test_c3_long_context_128k_full_size(name):
     hits, st = run_fullsize(CONFIGS[name], steps=10, groups=[(1, 2), (3, 7)], full_heads=[(2, 9)])
