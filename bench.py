@@ -363,7 +363,7 @@ def main():
                          "a per-config summary to the JSON line as 'configs_report'")
     ap.add_argument("--paper-table", action="store_true",
                     help="also run the analogue of the paper's fine-grained latency table (batch 1, 32K/60K/120K x KV "
-                         "budgets 1/5/10/20 %, K 1024, r 256) and add it to the JSON line as 'paper_table'")
+                         "budgets 1/5/10/20 %%, K 1024, r 256) and add it to the JSON line as 'paper_table'")
     ap.add_argument("--match-table", action="store_true",
                     help="also run the Match-vs-Attention kernel micro-benchmark (GQA 8-2 / 32-8 / 40-10 x 512 / 1024 / "
                          "2048 tokens) and add it to the JSON line as 'match_table'")

@@ -123,6 +123,8 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode == 2 and "ONE GPU" in r.stderr and not r.stdout.strip()
+    h = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--help"], capture_output=True, text=True)
+    assert h.returncode == 0 and "--paper-table" in h.stdout
 
 
 def test_workload_streams_are_reproducible_and_independent():
