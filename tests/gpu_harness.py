@@ -39,7 +39,7 @@ def check_rows(got: np.ndarray, ref: np.ndarray, what: str):
     return float(max_abs), float(rel[den > 0].max()) if (den > 0).any() else 0.0
 
 
-class GpuRun:
+class DeviceRun:
     """One library context + device buffers for a workload living on cuda:0."""
 
     def __init__(self, cfg: WorkloadConfig, wl: Workload, chunk_tokens: int = 0, strides=None, kv_pages=None,
@@ -86,7 +86,7 @@ def run_parity(cfg: WorkloadConfig, chunk_tokens: int = 0, check_full: bool = Tr
         f"page={cfg.page_size} chunk={chunk_tokens} fused={fuse_epilogue} max_gap={max_gap} group_match={group_match} "
         f"seed={cfg.seed}")
     wl = Workload(cfg, device="cuda:0")
-    run = GpuRun(cfg, wl, chunk_tokens, fuse_epilogue=fuse_epilogue, max_gap=max_gap, group_match=group_match)
+    run = DeviceRun(cfg, wl, chunk_tokens, fuse_epilogue=fuse_epilogue, max_gap=max_gap, group_match=group_match)
     orc = make_oracle(cfg, wl, max_gap=max_gap, group_match=group_match)
     kvp = bf16_bits(wl.kv_pages)
     bt = wl.block_table.cpu().numpy()

@@ -29,12 +29,12 @@ def _group_oracle(cfg: WorkloadConfig, kvp_g: np.ndarray, **variant):
 
 def run_fullsize(cfg: WorkloadConfig, steps: int, groups, full_heads, **variant):
     from oracle.mac_oracle import Oracle
-    from tests.gpu_harness import GpuRun, check_rows, say
+    from tests.gpu_harness import DeviceRun, check_rows, say
     say(f"[fullsize] {cfg.name}: batch={cfg.batch} Hq/Hkv={cfg.num_q_heads}/{cfg.num_kv_heads} context={cfg.context} "
         f"steps={steps} W={cfg.window} B={cfg.band} T={cfg.threshold:.4g} groups={groups}")
     cfg = scaled(cfg, steps=steps)
     wl = Workload(cfg, device="cuda:0")
-    run = GpuRun(cfg, wl, **variant)            # default chunk_tokens, as bench.py
+    run = DeviceRun(cfg, wl, **variant)            # default chunk_tokens, as bench.py
     kvp = bf16_bits(wl.kv_pages)
     bt = wl.block_table.cpu().numpy()
     slots = wl.slot_ids.cpu().numpy()
@@ -145,11 +145,11 @@ def test_c5_full_length_16384_steps():
     groups through every step (outputs and decisions), and checks the decisions of ALL 2048 heads on every 64th
     step and on the three steps from each regime shift on (its matcher rings are kept up to date at every step)."""
     from oracle.mac_oracle import Oracle
-    from tests.gpu_harness import GpuRun, check_rows, say
+    from tests.gpu_harness import DeviceRun, check_rows, say
     cfg = CONFIGS["C5"]
     say(f"[fullsize] C5 full length: batch={cfg.batch} Hq/Hkv={cfg.num_q_heads}/{cfg.num_kv_heads} steps={cfg.steps}")
     wl = Workload(cfg, device="cuda:0")
-    run = GpuRun(cfg, wl)
+    run = DeviceRun(cfg, wl)
     kvp = bf16_bits(wl.kv_pages)
     bt = wl.block_table.cpu().numpy()
     slots = wl.slot_ids.cpu().numpy()

@@ -80,7 +80,7 @@ def test_edge_cases(kw):
 
 def test_strided_kv_layout_and_group_sizes():
     """The cache layout is given by strides: token-major pages [page, 2, tok, head, d]; G = 1, 2, 16."""
-    from tests.gpu_harness import GpuRun, check_rows
+    from tests.gpu_harness import DeviceRun, check_rows
     from tests.helpers import make_oracle
     for hq, hkv in [(4, 4), (4, 2), (16, 1)]:
         cfg = WorkloadConfig(name="strided", batch=2, num_q_heads=hq, num_kv_heads=hkv, context=333, steps=3,
@@ -89,7 +89,7 @@ def test_strided_kv_layout_and_group_sizes():
         nhd = wl.kv_pages.permute(0, 1, 3, 2, 4).contiguous()      # [page, 2, tok, head, d]
         ps, d = cfg.page_size, cfg.head_dim
         strides = (2 * ps * hkv * d, ps * hkv * d, d, hkv * d)
-        run = GpuRun(cfg, wl, chunk_tokens=64, strides=strides, kv_pages=nhd)
+        run = DeviceRun(cfg, wl, chunk_tokens=64, strides=strides, kv_pages=nhd)
         orc = make_oracle(cfg, wl, strides=strides)
         kvp, bt, slots = bf16_bits(nhd), wl.block_table.cpu().numpy(), wl.slot_ids.cpu().numpy()
         for q_pre, q_rope, kv_lens in wl:
@@ -103,12 +103,12 @@ def test_strided_kv_layout_and_group_sizes():
 def test_bitwise_determinism_and_reset():
     """Fixed chunking and merge order: two runs give bit-identical outputs and counters; a reset in mid-stream
     forces a miss on the next step (rings start empty)."""
-    from tests.gpu_harness import GpuRun
+    from tests.gpu_harness import DeviceRun
     cfg = scaled(CONFIGS["C2"], name="det", batch=2, context=900, steps=10, window=8)
     outs = []
     for rep in range(2):
         wl = Workload(cfg, device="cuda:0")
-        run = GpuRun(cfg, wl, chunk_tokens=128)
+        run = DeviceRun(cfg, wl, chunk_tokens=128)
         seq = []
         for s, (q_pre, q_rope, kv_lens) in enumerate(wl):
             if s == 6:
@@ -202,11 +202,11 @@ def test_group_granular_matching_with_cap_ar1_queries():
 def test_bf16_output_is_the_rounded_fp32_output():
     """out_dtype = bf16: the same step on two contexts, one per output type; the bf16 result must be the fp32
     result rounded to nearest even (torch's conversion is the reference rounding), for decode_step and full_decode."""
-    from tests.gpu_harness import GpuRun
+    from tests.gpu_harness import DeviceRun
     cfg = scaled(CONFIGS["C2"], name="bf16out", batch=2, context=700, steps=6, window=8, band=32, threshold=2.8)
     wl = Workload(cfg, device="cuda:0")
-    r32 = GpuRun(cfg, wl, chunk_tokens=128)
-    r16 = GpuRun(cfg, wl, chunk_tokens=128, out_bf16=True)
+    r32 = DeviceRun(cfg, wl, chunk_tokens=128)
+    r16 = DeviceRun(cfg, wl, chunk_tokens=128, out_bf16=True)
     for q_pre, q_rope, kv_lens in wl:
         for mode in ("full", "mac"):
             for run in (r32, r16):
