@@ -110,19 +110,38 @@ __global__ __launch_bounds__(kMatchThreads) void match_kernel(const MatchParams 
     double best_d2 = INFINITY;
     int best_np = -1, best_j = -1;
     const int j_begin = sp * p.rows_per_split, j_end = min(W, j_begin + p.rows_per_split);
-    for (int j0 = j_begin; j0 < j_end; j0 += kMatchRowsPerPass) {
-        const int j = j0 + quad;
+    // Several passes of 64 rows per trip, all their row loads issued before the arithmetic, so that a work-group
+    // keeps more bytes in flight (the kernel is bound by latency x occupancy, not by the fp64 units).
+    auto row_of = [&](int j0, int& j, int& np, u32x4 (&v)[4]) {
+        j = j0 + quad;
         const int jc = j < W ? j : W - 1;                      // keep the speculative loads inside the ring
-        const int np = npos[jc];
+        np = npos[jc];
         const uint16_t* rp = ring + (int64_t)jc * kHeadDim;
-        u32x4 v[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) v[i] = *reinterpret_cast<const u32x4*>(rp + 32 * i);
+    };
+    auto take = [&](int j, int np, const u32x4 (&v)[4]) {
         const bool valid = j < j_end && np >= np_lo && np <= np_hi;
         double d2 = lane_sq_dist(q, v);
         d2 += __shfl_xor(d2, 1);
         d2 += __shfl_xor(d2, 2);
         if (valid && better(d2, np, best_d2, best_np)) { best_d2 = d2; best_np = np; best_j = j; }
+    };
+    constexpr int kPassesInFlight = 2;
+    int j0 = j_begin;
+    for (; j0 + (kPassesInFlight - 1) * kMatchRowsPerPass < j_end; j0 += kPassesInFlight * kMatchRowsPerPass) {
+        int jj[kPassesInFlight], nn[kPassesInFlight];
+        u32x4 vv[kPassesInFlight][4];
+#pragma unroll
+        for (int t = 0; t < kPassesInFlight; ++t) row_of(j0 + t * kMatchRowsPerPass, jj[t], nn[t], vv[t]);
+#pragma unroll
+        for (int t = 0; t < kPassesInFlight; ++t) take(jj[t], nn[t], vv[t]);
+    }
+    for (; j0 < j_end; j0 += kMatchRowsPerPass) {
+        int ja, npa;
+        u32x4 va[4];
+        row_of(j0, ja, npa, va);
+        take(ja, npa, va);
     }
     // wave butterfly over the 16 quads (all 4 lanes of a quad hold the same triple)
 #pragma unroll
