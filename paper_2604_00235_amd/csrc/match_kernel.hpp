@@ -188,20 +188,38 @@ __global__ __launch_bounds__(kMatchThreads) void match_group_kernel(const MatchP
     const int items = rows * G;                                  // <= kMatchGroupItems (host)
     __shared__ double s_pair[kMatchGroupItems];
 
-    for (int i0 = 0; i0 < items; i0 += kMatchRowsPerPass) {
-        const int i = i0 + quad;
-        const int ic = i < items ? i : items - 1;                // keeps the loads of idle quads inside the slice
-        const int r = ic / G, h = g * G + (ic - r * G);
-        double q[32];
-        load_query_f64(p.q_pre + ((int64_t)b * p.Hq + h) * kHeadDim + 8 * sub, q);
-        const uint16_t* rp = p.ring_q + ((slot * p.Hq + h) * W + j_begin + r) * (int64_t)kHeadDim + 8 * sub;
-        u32x4 v[4];
+    // two pairs per quad and trip, their loads issued before the arithmetic (as in match_kernel)
+    for (int i0 = 0; i0 < items; i0 += 2 * kMatchRowsPerPass) {
+        u32x4 qv[2][4], v[2][4];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) v[k] = *reinterpret_cast<const u32x4*>(rp + 32 * k);
-        double d2 = lane_sq_dist(q, v);
-        d2 += __shfl_xor(d2, 1);
-        d2 += __shfl_xor(d2, 2);
-        if (i < items && sub == 0) s_pair[i] = d2;
+        for (int t = 0; t < 2; ++t) {
+            const int i = i0 + t * kMatchRowsPerPass + quad;
+            const int ic = i < items ? i : items - 1;            // keeps the loads of idle quads inside the slice
+            const int r = ic / G, h = g * G + (ic - r * G);
+            const uint16_t* qp = p.q_pre + ((int64_t)b * p.Hq + h) * kHeadDim + 8 * sub;
+            const uint16_t* rp = p.ring_q + ((slot * p.Hq + h) * W + j_begin + r) * (int64_t)kHeadDim + 8 * sub;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                qv[t][k] = *reinterpret_cast<const u32x4*>(qp + 32 * k);
+                v[t][k] = *reinterpret_cast<const u32x4*>(rp + 32 * k);
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int i = i0 + t * kMatchRowsPerPass + quad;
+            double q[32];
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    q[8 * k + 2 * e] = bf16_lo_to_f64(qv[t][k][e]);
+                    q[8 * k + 2 * e + 1] = bf16_hi_to_f64(qv[t][k][e]);
+                }
+            double d2 = lane_sq_dist(q, v[t]);
+            d2 += __shfl_xor(d2, 1);
+            d2 += __shfl_xor(d2, 2);
+            if (i < items && sub == 0) s_pair[i] = d2;
+        }
     }
     __syncthreads();
 
