@@ -74,7 +74,7 @@ struct KVTile {
 };
 
 template <int HT>   // number of 16-head tiles: 1 (G <= 16) or 2 (G <= 32)
-__global__ __launch_bounds__(256, (HT == 1 ? 2 : 1)) void attn_kernel(const AttnParams p) {
+__global__ __launch_bounds__(256, 2) void attn_kernel(const AttnParams p) {
     // Work-groups are dispatched in linear order and dealt to the 8 XCDs round-robin; slots always run from the last
     // one down (the band and the newest chunks, where a hit has its work, start first).  Two orders (p.group_fastest):
     //  1: grid = (KV groups, slots).  A slot level is dispatched for all groups before the next one: neighbours read
@@ -191,21 +191,51 @@ __global__ __launch_bounds__(256, (HT == 1 ? 2 : 1)) void attn_kernel(const Attn
     if (lo >= hi) return;
     const int maxstart = max(gmax, lo);                       // tiles at or above it need no start mask
 
+    // Shared memory.  s_O carries the waves' states to the merge at the end.  With two head tiles (HT == 2) a wave
+    // keeps only one tile's output accumulators in registers: during the stream s_O[w] holds both tiles'
+    // accumulators in register layout ([tile][column block j][lane] x 16 B: conflict-free) and each tile is loaded,
+    // updated and stored back per K/V tile; the queries (B operands of S = K Q^T) of all 32 heads sit in s_q, rows
+    // padded to 272 B so that the 16 rows read by one instruction fall into different banks.  That keeps the
+    // kernel at the register budget of the one-tile variant (two waves per SIMD, two work-groups per CU), which
+    // matters more than the extra shared-memory traffic: with all 64 accumulators in registers the kernel needs
+    // ~440 registers, runs one wave per SIMD and leaves the CU idle during every work-group's prologue and epilogue.
+    __shared__ float s_O[4][HT * 16 * kHeadDim];
+    __shared__ float s_m[4][HT * 16];
+    __shared__ float s_l[4][HT * 16];
+    constexpr int kQRowBytes = 2 * kHeadDim + 16;
+    __shared__ __attribute__((aligned(16))) char s_q[HT == 2 ? 32 * kQRowBytes : 16];
+
     // per-lane head data for each head tile: first token this head attends to, and its query (B operand)
     int hstart[HT];
-    bf16x8 qreg[HT][4];
+    bf16x8 qreg[HT == 1 ? 1 : 1][4];                          // HT == 1: the tile's query; HT == 2: unused
 #pragma unroll
     for (int ht = 0; ht < HT; ++ht) {
         const int hh = ht * 16 + r16;
-        const bool valid = hh < G;
-        hstart[ht] = valid ? max(lo, my_start[ht]) : lo;
-        const uint16_t* qp = p.q_rope + (int64_t)(hbase + (valid ? hh : 0)) * kHeadDim + 8 * kg;
+        hstart[ht] = hh < G ? max(lo, my_start[ht]) : lo;
+    }
+    if constexpr (HT == 1) {
+        const bool valid = r16 < G;
+        const uint16_t* qp = p.q_rope + (int64_t)(hbase + (valid ? r16 : 0)) * kHeadDim + 8 * kg;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             u32x4 v = *reinterpret_cast<const u32x4*>(qp + 32 * c);
             if (!valid) v = u32x4{0u, 0u, 0u, 0u};
-            qreg[ht][c] = __builtin_bit_cast(bf16x8, v);
+            qreg[0][c] = __builtin_bit_cast(bf16x8, v);
         }
+    } else {
+        // 32 rows x 16 chunks of 16 B = 512 chunks, two per thread; rows of heads beyond G are zero
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int idx = tid + 256 * t, row = idx >> 4, ch = idx & 15;
+            u32x4 v = u32x4{0u, 0u, 0u, 0u};
+            if (row < G) v = *reinterpret_cast<const u32x4*>(p.q_rope + (int64_t)(hbase + row) * kHeadDim + 8 * ch);
+            *reinterpret_cast<u32x4*>(s_q + row * kQRowBytes + 16 * ch) = v;
+        }
+        // this wave's accumulators of both tiles start at zero
+        char* acc_img = reinterpret_cast<char*>(&s_O[w][0]);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) *reinterpret_cast<f32x4*>(acc_img + 1024 * i + 16 * l) = f32x4{0.f, 0.f, 0.f, 0.f};
+        __syncthreads();
     }
 
     // this wave's tiles of the chunk that intersect [lo, hi): k = k_first .. k_last
@@ -255,28 +285,40 @@ __global__ __launch_bounds__(256, (HT == 1 ? 2 : 1)) void attn_kernel(const Attn
     // online-softmax state of this wave: running max (log2 domain), this lane's share of the running sum,
     // and the unnormalised output: acc[ht][j][i] = O[head ht*16 + 4kg + i][d = 8*r16 + j]
     float m_run[HT], l_run[HT];
-    f32x4 acc[HT][8];
+    f32x4 acc[8];                                             // HT == 2: the tile being updated, see s_O above
 #pragma unroll
     for (int ht = 0; ht < HT; ++ht) {
         m_run[ht] = -INFINITY;
         l_run[ht] = 0.f;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) acc[ht][j] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     auto compute_tile = [&](int k, const KVTile& T) {
         const int t0 = (chunk_tile0 + w + 4 * k) * kTileTokens;
         const bool need_mask = (t0 < maxstart) || (t0 + kTileTokens > hi);   // wave-uniform
-        u32x4 a_hi[HT], a_lo[HT];
 #pragma unroll
         for (int ht = 0; ht < HT; ++ht) {
+            // the tile's queries: registers, or shared memory (row = head, 16-byte chunk 4c + kg of k-step c)
+            bf16x8 qop[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                if constexpr (HT == 1) qop[c] = qreg[0][c];
+                else qop[c] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(
+                                  s_q + (ht * 16 + r16) * kQRowBytes + 64 * c + 16 * kg));
+            }
+            char* const acc_img = reinterpret_cast<char*>(&s_O[w][0]) + 8192 * ht + 16 * l;
+            if constexpr (HT == 2) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[j] = *reinterpret_cast<const f32x4*>(acc_img + 1024 * j);
+            }
             float sc[8];
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
                 f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int c = 0; c < 4; ++c)
-                    s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, T.k[u][c]), qreg[ht][c], s, 0, 0, 0);
+                    s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, T.k[u][c]), qop[c], s, 0, 0, 0);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) sc[4 * u + i] = s[i] * p.scale_log2;
             }
@@ -308,7 +350,7 @@ __global__ __launch_bounds__(256, (HT == 1 ? 2 : 1)) void attn_kernel(const Attn
                 for (int i = 0; i < 4; ++i) {
                     const float a = __shfl(alpha, 4 * kg + i);             // lane 4kg+i holds head 4kg+i
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) acc[ht][j][i] *= a;
+                    for (int j = 0; j < 8; ++j) acc[j][i] *= a;
                 }
             }
             m_run[ht] = m_new;
@@ -320,24 +362,30 @@ __global__ __launch_bounds__(256, (HT == 1 ? 2 : 1)) void attn_kernel(const Attn
                 hb[e] = bits;
                 lb[e] = float_to_bits(pv[e] - bits_to_float(bits & 0xffff0000u));
             }
+            u32x4 a_hi, a_lo;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                a_hi[ht][q] = pack_hi16(hb[2 * q], hb[2 * q + 1]);
-                a_lo[ht][q] = pack_hi16(lb[2 * q], lb[2 * q + 1]);
+                a_hi[q] = pack_hi16(hb[2 * q], hb[2 * q + 1]);
+                a_lo[q] = pack_hi16(lb[2 * q], lb[2 * q + 1]);
             }
-        }
+            // O += P V (with two head tiles the V operands are formed once per tile: registers are the scarcer resource)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int c = j >> 1;
-            u32x4 bj;
+            for (int j = 0; j < 8; ++j) {
+                const int c = j >> 1;
+                u32x4 bj;
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-                bj[q] = (j & 1) ? pack_hi16(T.v[2 * q][c], T.v[2 * q + 1][c]) : pack_lo16(T.v[2 * q][c], T.v[2 * q + 1][c]);
-            const bf16x8 bop = __builtin_bit_cast(bf16x8, bj);
+                for (int q = 0; q < 4; ++q)
+                    bj[q] = (j & 1) ? pack_hi16(T.v[2 * q][c], T.v[2 * q + 1][c]) : pack_lo16(T.v[2 * q][c], T.v[2 * q + 1][c]);
+                const bf16x8 bop = __builtin_bit_cast(bf16x8, bj);
+                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a_hi), bop, acc[j], 0, 0, 0);
+                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a_lo), bop, acc[j], 0, 0, 0);
+            }
+            if constexpr (HT == 2) {
 #pragma unroll
-            for (int ht = 0; ht < HT; ++ht) {
-                acc[ht][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a_hi[ht]), bop, acc[ht][j], 0, 0, 0);
-                acc[ht][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a_lo[ht]), bop, acc[ht][j], 0, 0, 0);
+                for (int j = 0; j < 8; ++j) *reinterpret_cast<f32x4*>(acc_img + 1024 * j) = acc[j];
+                // one tile after the other: interleaving them would need both accumulator sets in registers again
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
     };
@@ -362,9 +410,18 @@ __global__ __launch_bounds__(256, (HT == 1 ? 2 : 1)) void attn_kernel(const Attn
     }
 
     // merge the 4 waves' states through LDS and write the normalised partial of every real head
-    __shared__ float s_O[4][HT * 16][kHeadDim];
-    __shared__ float s_m[4][HT * 16];
-    __shared__ float s_l[4][HT * 16];
+    f32x4 fin[HT][8];
+    if constexpr (HT == 1) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) fin[0][j] = acc[j];
+    } else {
+        // both tiles' accumulators leave the register-layout image before the same memory takes the merge layout
+        const char* const acc_img = reinterpret_cast<const char*>(&s_O[w][0]) + 16 * l;
+#pragma unroll
+        for (int ht = 0; ht < HT; ++ht)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) fin[ht][j] = *reinterpret_cast<const f32x4*>(acc_img + 8192 * ht + 1024 * j);
+    }
 #pragma unroll
     for (int ht = 0; ht < HT; ++ht) {
         float lsum = l_run[ht];
@@ -378,9 +435,9 @@ __global__ __launch_bounds__(256, (HT == 1 ? 2 : 1)) void attn_kernel(const Attn
         for (int i = 0; i < 4; ++i) {
             const int head = ht * 16 + 4 * kg + i;
             if (head < G) {
-                float* dst = &s_O[w][head][8 * r16];
-                *reinterpret_cast<f32x4*>(dst) = f32x4{acc[ht][0][i], acc[ht][1][i], acc[ht][2][i], acc[ht][3][i]};
-                *reinterpret_cast<f32x4*>(dst + 4) = f32x4{acc[ht][4][i], acc[ht][5][i], acc[ht][6][i], acc[ht][7][i]};
+                float* dst = &s_O[w][head * kHeadDim + 8 * r16];
+                *reinterpret_cast<f32x4*>(dst) = f32x4{fin[ht][0][i], fin[ht][1][i], fin[ht][2][i], fin[ht][3][i]};
+                *reinterpret_cast<f32x4*>(dst + 4) = f32x4{fin[ht][4][i], fin[ht][5][i], fin[ht][6][i], fin[ht][7][i]};
             }
         }
     }
@@ -395,7 +452,7 @@ __global__ __launch_bounds__(256, (HT == 1 ? 2 : 1)) void attn_kernel(const Attn
             for (int ww = 0; ww < 4; ++ww) {
                 const float f = exp2_fast(s_m[ww][h] - M);
                 L += s_l[ww][h] * f;
-                a += s_O[ww][h][dd] * f;
+                a += s_O[ww][h * kHeadDim + dd] * f;
             }
             o = a / L;
             lse = (M + __log2f(L)) * kLn2;
