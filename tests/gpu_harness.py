@@ -55,11 +55,32 @@ class DeviceRun:
         self.kv_pages = wl.kv_pages if kv_pages is None else kv_pages
         self.strides = wl.strides if strides is None else strides
         B, Hq, d = cfg.batch, cfg.num_q_heads, cfg.head_dim
-        self.out = torch.zeros((B, Hq, d), dtype=torch.bfloat16 if out_bf16 else torch.float32, device=dev)
-        self.lse = torch.zeros((B, Hq), dtype=torch.float32, device=dev)
-        self.pos = torch.zeros((B, Hq), dtype=torch.int32, device=dev)
-        self.d2 = torch.zeros((B, Hq), dtype=torch.float64, device=dev)
+        # caller-owned outputs sit between guard zones holding a pattern: a write outside an output shows up there
+        self._guards = []
+        self.out = self._guarded((B, Hq, d), torch.bfloat16 if out_bf16 else torch.float32, dev)
+        self.lse = self._guarded((B, Hq), torch.float32, dev)
+        self.pos = self._guarded((B, Hq), torch.int32, dev)
+        self.d2 = self._guarded((B, Hq), torch.float64, dev)
         self.stream = torch.cuda.current_stream().cuda_stream
+
+    GUARD_BYTES = 4096
+
+    def _guarded(self, shape, dtype, dev):
+        n = int(np.prod(shape))
+        esz = torch.empty((), dtype=dtype).element_size()
+        g = self.GUARD_BYTES // esz
+        raw = torch.empty(n + 2 * g, dtype=dtype, device=dev)
+        raw.view(torch.uint8).fill_(0xA5)
+        view = raw[g:g + n].view(shape)
+        view.zero_()
+        self._guards.append((raw, g, n))
+        return view
+
+    def check_guards(self):
+        for raw, g, n in self._guards:
+            b = raw.view(torch.uint8)
+            esz = raw.element_size()
+            assert bool((b[:g * esz] == 0xA5).all()) and bool((b[(g + n) * esz:] == 0xA5).all()), "write outside an output buffer"
 
     def args(self, q_pre, q_rope, kv_lens):
         return self.mac.make_args(kv_lens=kv_lens, q_rope=q_rope, kv_pages=self.kv_pages, strides=self.strides,
@@ -69,12 +90,14 @@ class DeviceRun:
     def mac_step(self, q_pre, q_rope, kv_lens):
         self.mac.decode_step(self.args(q_pre, q_rope, kv_lens), self.stream)
         torch.cuda.synchronize()
+        self.check_guards()
         return (self.out.float().cpu().numpy().copy(), self.lse.cpu().numpy().copy(), self.pos.cpu().numpy().copy(),
                 self.d2.cpu().numpy().copy())
 
     def full(self, q_rope, kv_lens):
         self.mac.full_decode(self.args(None, q_rope, kv_lens), self.stream)
         torch.cuda.synchronize()
+        self.check_guards()
         return self.out.float().cpu().numpy().copy(), self.lse.cpu().numpy().copy()
 
 
