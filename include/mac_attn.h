@@ -38,6 +38,7 @@ extern "C" {
 #define MAC_ATTN_ERR_UNSUPPORTED (-2)   /* valid request this build cannot serve (e.g. head_dim != 128) */
 #define MAC_ATTN_ERR_HIP         (-3)   /* a HIP runtime call failed; see mac_attn_last_hip_error        */
 #define MAC_ATTN_ERR_OOM         (-4)   /* device allocation failed                                      */
+#define MAC_ATTN_ERR_CORRUPT     (-5)   /* mac_attn_check_guards found an overwritten guard zone         */
 
 typedef struct mac_attn_ctx mac_attn_ctx;   /* opaque: owns rings, split-K workspace and counters */
 
@@ -130,6 +131,11 @@ int mac_attn_reset(mac_attn_ctx* ctx, const int32_t* slot_ids /*host*/, int32_t 
  * Waits for all work on the context's device first. */
 int mac_attn_ring_peek(mac_attn_ctx* ctx, int32_t slot, int32_t j, int32_t h,
                        uint16_t* q_pre /*host*/, float* summary /*host*/, float* lse /*host*/, int32_t* n_p /*host*/);
+
+/* Diagnostic: every device buffer of the context (rings, workspace, counters) lies between two 256-byte guard
+ * zones filled with a pattern at init.  Waits for all work on the context's device, reads the zones back and
+ * returns MAC_ATTN_ERR_CORRUPT if a kernel wrote into one, else 0.  (Not part of the paper's operator.) */
+int mac_attn_check_guards(mac_attn_ctx* ctx);
 
 /* Bytes of ring state per (ring set, head, entry): bf16 query + fp32 summary row + fp32 ln-LSE
  * (Sec. 5.9 "Auxiliary HBM overhead").  Pure host arithmetic. */

@@ -18,11 +18,13 @@ MAC_ATTN_ERR_INVALID_ARG = -1
 MAC_ATTN_ERR_UNSUPPORTED = -2
 MAC_ATTN_ERR_HIP = -3
 MAC_ATTN_ERR_OOM = -4
+MAC_ATTN_ERR_CORRUPT = -5
 
 EXPORTS = (
     "mac_attn_init", "mac_attn_decode_step", "mac_attn_full_decode", "mac_attn_stats", "mac_attn_reset",
     "mac_attn_ring_peek", "mac_attn_ring_entry_bytes", "mac_attn_device_bytes", "mac_attn_set_timing",
     "mac_attn_kernel_us", "mac_attn_destroy", "mac_attn_strerror", "mac_attn_last_hip_error",
+    "mac_attn_check_guards",
 )
 
 
@@ -99,6 +101,8 @@ def load_library() -> C.CDLL:
     lib.mac_attn_ring_entry_bytes.restype = C.c_int64
     lib.mac_attn_device_bytes.argtypes = [P(mac_attn_config)]
     lib.mac_attn_device_bytes.restype = C.c_int64
+    lib.mac_attn_check_guards.argtypes = [C.c_void_p]
+    lib.mac_attn_check_guards.restype = C.c_int
     lib.mac_attn_set_timing.argtypes = [C.c_void_p, C.c_int]
     lib.mac_attn_set_timing.restype = C.c_int
     lib.mac_attn_kernel_us.argtypes = [C.c_void_p, P(C.c_double), P(C.c_int64)]
@@ -137,6 +141,10 @@ def mac_attn_stats(ctx, reset: bool = False) -> mac_attn_stats_t:
     st = mac_attn_stats_t()
     _check(load_library().mac_attn_stats(ctx, C.byref(st), int(reset)), "mac_attn_stats")
     return st
+
+
+def mac_attn_check_guards(ctx) -> None:
+    _check(load_library().mac_attn_check_guards(ctx), "mac_attn_check_guards")
 
 
 def mac_attn_reset(ctx, slot_ids=None) -> None:
@@ -221,6 +229,9 @@ class MacAttention:
 
     def reset(self, slot_ids=None):
         mac_attn_reset(self.ctx, slot_ids)
+
+    def check_guards(self):
+        mac_attn_check_guards(self.ctx)
 
     def ring_peek(self, slot: int, j: int, h: int):
         return mac_attn_ring_peek(self.ctx, slot, j, h, self.cfg.head_dim)

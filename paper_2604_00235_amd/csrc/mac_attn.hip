@@ -34,6 +34,12 @@ int hip_fail(hipError_t e, const char* what) {
 // at 32 heads per KV head (MQA) a 512-token item would write 6 %, and measured 153 us against 112 us at 2048.
 // (4096-token items stream a full-length step 1-3 % faster (11 % for MQA), but balance worse when most groups
 // reuse a prefix and a few do not: 168 us against 156 us at 89 % hits on 32 groups of 131072 tokens.)
+// Every device buffer of a context lies between two guard zones of this many bytes holding kGuardByte;
+// mac_attn_check_guards reports a write that strayed into one.
+constexpr int64_t kGuardBytes = 256;
+constexpr int kGuardByte = 0xA5;
+constexpr int kNumBuffers = 10;
+
 // KV groups (requests x kv heads) from which the attention grid is dispatched group-fastest (see attn_kernel)
 constexpr int kGroupFastestFrom = 16;
 
@@ -51,7 +57,7 @@ struct Layout {            // derived sizes, pure host arithmetic
     int64_t part_O_bytes, part_lse_bytes, match_bytes, rect_bytes, stats_bytes, head_start_bytes;
     int64_t total() const {
         return ring_q_bytes + ring_O_bytes + ring_lse_bytes + ring_npos_bytes + part_O_bytes + part_lse_bytes +
-               match_bytes + rect_bytes + stats_bytes + head_start_bytes;
+               match_bytes + rect_bytes + stats_bytes + head_start_bytes + 2 * kGuardBytes * kNumBuffers;
     }
 };
 
@@ -126,6 +132,9 @@ struct mac_attn_ctx {
     // counters
     unsigned long long* stats = nullptr;
     hipStream_t last_stream = nullptr;
+    // allocations as returned by hipMalloc (the pointers above point kGuardBytes into them) and their payload sizes
+    void* raw[kNumBuffers] = {};
+    int64_t payload[kNumBuffers] = {};
     // timing
     bool timing = false;
     std::vector<TimedCall> timed;
@@ -334,6 +343,7 @@ const char* mac_attn_strerror(int code) {
         case MAC_ATTN_ERR_UNSUPPORTED: return "unsupported configuration";
         case MAC_ATTN_ERR_HIP: return "HIP runtime error";
         case MAC_ATTN_ERR_OOM: return "out of device memory";
+        case MAC_ATTN_ERR_CORRUPT: return "a guard zone around a device buffer of the context was overwritten";
         default: return "unknown error code";
     }
 }
@@ -357,9 +367,7 @@ void mac_attn_destroy(mac_attn_ctx* ctx) {
     int cur = -1;
     if (hipGetDevice(&cur) == hipSuccess && cur != ctx->cfg.device) (void)hipSetDevice(ctx->cfg.device);
     (void)hipDeviceSynchronize();
-    void* bufs[] = {ctx->ring_q, ctx->ring_O, ctx->ring_lse, ctx->ring_npos, ctx->part_O, ctx->part_lse,
-                    ctx->m_part, ctx->rect, ctx->stats, ctx->head_start};
-    for (void* b : bufs)
+    for (void* b : ctx->raw)
         if (b != nullptr) (void)hipFree(b);
     for (TimedCall& t : ctx->timed)
         for (hipEvent_t e : t.ev) (void)hipEventDestroy(e);
@@ -395,9 +403,19 @@ int mac_attn_init(const mac_attn_config* cfg, mac_attn_ctx** out_ctx) {
         {reinterpret_cast<void**>(&ctx->stats), L.stats_bytes, true},
         {reinterpret_cast<void**>(&ctx->head_start), L.head_start_bytes, true},
     };
-    for (auto& a : allocs) {
-        hipError_t e = hipMalloc(a.p, (size_t)a.bytes);
-        if (e == hipSuccess && a.zero) e = hipMemset(*a.p, 0, (size_t)a.bytes);
+    static_assert(sizeof(allocs) / sizeof(allocs[0]) == kNumBuffers, "kNumBuffers");
+    for (int i = 0; i < kNumBuffers; ++i) {
+        auto& a = allocs[i];
+        char* base = nullptr;
+        hipError_t e = hipMalloc(reinterpret_cast<void**>(&base), (size_t)(a.bytes + 2 * kGuardBytes));
+        if (e == hipSuccess) {
+            ctx->raw[i] = base;
+            ctx->payload[i] = a.bytes;
+            *a.p = base + kGuardBytes;
+            e = hipMemset(base, kGuardByte, (size_t)kGuardBytes);
+            if (e == hipSuccess) e = hipMemset(base + kGuardBytes + a.bytes, kGuardByte, (size_t)kGuardBytes);
+            if (e == hipSuccess && a.zero) e = hipMemset(*a.p, 0, (size_t)a.bytes);
+        }
         if (e != hipSuccess) {
             rc = hip_fail(e, "hipMalloc/hipMemset");
             mac_attn_destroy(ctx);
@@ -508,6 +526,22 @@ int mac_attn_decode_step(mac_attn_ctx* ctx, const mac_attn_step_args* args, void
     }
     t.finish();
     return t.rc;
+}
+
+int mac_attn_check_guards(mac_attn_ctx* ctx) {
+    if (ctx == nullptr) return MAC_ATTN_ERR_INVALID_ARG;
+    int rc = ensure_device(ctx);
+    if (rc != MAC_ATTN_OK) return rc;
+    HIP_TRY(hipDeviceSynchronize());
+    unsigned char host[2 * kGuardBytes];
+    for (int i = 0; i < kNumBuffers; ++i) {
+        const char* base = static_cast<const char*>(ctx->raw[i]);
+        HIP_TRY(hipMemcpy(host, base, (size_t)kGuardBytes, hipMemcpyDeviceToHost));
+        HIP_TRY(hipMemcpy(host + kGuardBytes, base + kGuardBytes + ctx->payload[i], (size_t)kGuardBytes, hipMemcpyDeviceToHost));
+        for (unsigned char v : host)
+            if (v != kGuardByte) return MAC_ATTN_ERR_CORRUPT;
+    }
+    return MAC_ATTN_OK;
 }
 
 int mac_attn_stats(mac_attn_ctx* ctx, mac_attn_stats_t* out, int reset) {

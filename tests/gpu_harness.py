@@ -77,6 +77,7 @@ class DeviceRun:
         return view
 
     def check_guards(self):
+        self.mac.check_guards()          # the library's own buffers (rings, workspace, counters)
         for raw, g, n in self._guards:
             b = raw.view(torch.uint8)
             esz = raw.element_size()

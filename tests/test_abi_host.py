@@ -64,7 +64,8 @@ def test_device_bytes_accounts_rings_and_workspace(lib):
     work = 4 * 32 * n_slots * (128 + 1) * 4
     # the rest is small: match slice results (64 x 16 B per head), write-back staging, counters
     # and one word per head (+ 32 of padding) for the fresh-range start the match kernel stores
-    assert total - rings - work == 4 * 32 * (64 * 16 + 129 * 4 + 3 * 8 + 4) + 32 * 4 + 4 * 8 * 2 * 8 + 2 * 8
+    # each of the 10 buffers lies between two 256-byte guard zones
+    assert total - rings - work == 4 * 32 * (64 * 16 + 129 * 4 + 3 * 8 + 4) + 32 * 4 + 4 * 8 * 2 * 8 + 2 * 8 + 10 * 512
 
 
 @pytest.mark.parametrize("kw,code", [
@@ -102,7 +103,8 @@ def test_null_arguments_and_error_strings(lib):
     assert lib.mac_attn_stats(None, None, 0) == mb.MAC_ATTN_ERR_INVALID_ARG
     assert lib.mac_attn_reset(None, None, 0) == mb.MAC_ATTN_ERR_INVALID_ARG
     lib.mac_attn_destroy(None)
-    for code in (0, -1, -2, -3, -4, -99):
+    assert lib.mac_attn_check_guards(None) == mb.MAC_ATTN_ERR_INVALID_ARG
+    for code in (0, -1, -2, -3, -4, -5, -99):
         assert lib.mac_attn_strerror(code)
     assert lib.mac_attn_strerror(-1) == b"invalid argument"
 
