@@ -39,6 +39,8 @@ extern "C" {
 #define MAC_ATTN_ERR_HIP         (-3)   /* a HIP runtime call failed; see mac_attn_last_hip_error        */
 #define MAC_ATTN_ERR_OOM         (-4)   /* device allocation failed                                      */
 #define MAC_ATTN_ERR_CORRUPT     (-5)   /* mac_attn_check_guards found an overwritten guard zone         */
+#define MAC_ATTN_ERR_TOO_LARGE   (-6)   /* mac_attn_full_decode_static: the call needs more than
+                                           MAC_ATTN_STATIC_SCRATCH_BYTES of split-K workspace            */
 
 typedef struct mac_attn_ctx mac_attn_ctx;   /* opaque: owns rings, split-K workspace and counters */
 
@@ -117,6 +119,33 @@ int mac_attn_decode_step(mac_attn_ctx* ctx, const mac_attn_step_args* args /*hos
 /* Plain full decode attention over [0, n) with the same split-K kernels (the miss path, and the baseline
  * the speed-up is reported against); reads and changes no ring state.  Sec. 2, Sec. 3.2.1. */
 int mac_attn_full_decode(mac_attn_ctx* ctx, const mac_attn_step_args* args /*host*/, void* hip_stream);
+
+/* Full decode for callers that cannot allocate device memory or create a context (code under HIP graph capture,
+ * serving loops and harnesses that forbid hipMalloc): the same kernels and the same result as
+ * mac_attn_full_decode, but with no context -- the geometry comes in `geo`, and the split-K partials go to a
+ * static device array of MAC_ATTN_STATIC_SCRATCH_BYTES that every GPU the library runs on holds until the process
+ * ends.  The call allocates nothing (no hipMalloc / hipFree, no context) and only enqueues two kernels on the stream.
+ *   workspace needed = batch * Hq * ceil(max_kv_len / chunk) * 516 bytes, chunk = geo->chunk_tokens, or for 0 the
+ *   default rule of mac_attn_config.chunk_tokens applied to batch * Hkv * max_kv_len; a call that needs more
+ *   returns MAC_ATTN_ERR_TOO_LARGE and enqueues nothing.
+ * Arguments as for mac_attn_full_decode (args->q_pre, slot_ids, match_* are ignored).  Nothing in the array has to
+ * survive between calls and nothing is cleared: every partial a call reads it has written itself.  All calls on one
+ * GPU share that GPU's array, so calls that overlap in time on one GPU (two streams, two threads) race; calls on
+ * one stream are ordered and safe. */
+#define MAC_ATTN_STATIC_SCRATCH_BYTES (16u << 20)
+typedef struct mac_attn_static_geometry {
+    int32_t device;        /* HIP device ordinal (made current by the call), 0 .. 63                              */
+    int32_t num_q_heads;   /* Hq                                                                                  */
+    int32_t num_kv_heads;  /* Hkv; Hq % Hkv == 0, G = Hq/Hkv <= 32                                                */
+    int32_t head_dim;      /* must be 128                                                                         */
+    int32_t page_size;     /* tokens per KV page: a power of two >= 16                                            */
+    float   sm_scale;      /* softmax scale; <= 0 selects 1/sqrt(head_dim)                                        */
+    int32_t max_kv_len;    /* upper bound of kv_len: fixes the launch grid and the workspace layout               */
+    int32_t chunk_tokens;  /* tokens per split-K work item: multiple of 32 in [32, 4096], or 0 for the default    */
+    int32_t out_dtype;     /* 0 = fp32, 1 = bf16                                                                  */
+} mac_attn_static_geometry;
+int mac_attn_full_decode_static(const mac_attn_static_geometry* geo /*host*/, const mac_attn_step_args* args /*host*/,
+                                void* hip_stream);
 
 /* Wait for all work on the context's device (steps may have been replayed from a captured graph on any stream),
  * then read the counters into *out; reset != 0 clears them. */

@@ -19,12 +19,14 @@ MAC_ATTN_ERR_UNSUPPORTED = -2
 MAC_ATTN_ERR_HIP = -3
 MAC_ATTN_ERR_OOM = -4
 MAC_ATTN_ERR_CORRUPT = -5
+MAC_ATTN_ERR_TOO_LARGE = -6
+MAC_ATTN_STATIC_SCRATCH_BYTES = 16 << 20
 
 EXPORTS = (
     "mac_attn_init", "mac_attn_decode_step", "mac_attn_full_decode", "mac_attn_stats", "mac_attn_reset",
     "mac_attn_ring_peek", "mac_attn_ring_entry_bytes", "mac_attn_device_bytes", "mac_attn_set_timing",
     "mac_attn_kernel_us", "mac_attn_destroy", "mac_attn_strerror", "mac_attn_last_hip_error",
-    "mac_attn_check_guards",
+    "mac_attn_check_guards", "mac_attn_full_decode_static",
 )
 
 
@@ -47,6 +49,14 @@ class mac_attn_step_args(C.Structure):
         ("stride_page", C.c_int64), ("stride_kv", C.c_int64), ("stride_head", C.c_int64), ("stride_tok", C.c_int64),
         ("block_table", C.c_void_p), ("block_table_stride", C.c_int32),
         ("out", C.c_void_p), ("out_lse", C.c_void_p), ("match_pos", C.c_void_p), ("match_d2", C.c_void_p),
+    ]
+
+
+class mac_attn_static_geometry(C.Structure):
+    _fields_ = [
+        ("device", C.c_int32), ("num_q_heads", C.c_int32), ("num_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+        ("page_size", C.c_int32), ("sm_scale", C.c_float), ("max_kv_len", C.c_int32), ("chunk_tokens", C.c_int32),
+        ("out_dtype", C.c_int32),
     ]
 
 
@@ -90,6 +100,8 @@ def load_library() -> C.CDLL:
     lib.mac_attn_decode_step.restype = C.c_int
     lib.mac_attn_full_decode.argtypes = [C.c_void_p, P(mac_attn_step_args), C.c_void_p]
     lib.mac_attn_full_decode.restype = C.c_int
+    lib.mac_attn_full_decode_static.argtypes = [P(mac_attn_static_geometry), P(mac_attn_step_args), C.c_void_p]
+    lib.mac_attn_full_decode_static.restype = C.c_int
     lib.mac_attn_stats.argtypes = [C.c_void_p, P(mac_attn_stats_t), C.c_int]
     lib.mac_attn_stats.restype = C.c_int
     lib.mac_attn_reset.argtypes = [C.c_void_p, P(C.c_int32), C.c_int32]
@@ -135,6 +147,11 @@ def mac_attn_decode_step(ctx, args: mac_attn_step_args, stream: int = 0) -> None
 
 def mac_attn_full_decode(ctx, args: mac_attn_step_args, stream: int = 0) -> None:
     _check(load_library().mac_attn_full_decode(ctx, C.byref(args), C.c_void_p(stream)), "mac_attn_full_decode")
+
+
+def mac_attn_full_decode_static(geo: mac_attn_static_geometry, args: mac_attn_step_args, stream: int = 0) -> None:
+    _check(load_library().mac_attn_full_decode_static(C.byref(geo), C.byref(args), C.c_void_p(stream)),
+           "mac_attn_full_decode_static")
 
 
 def mac_attn_stats(ctx, reset: bool = False) -> mac_attn_stats_t:

@@ -5,6 +5,7 @@
 
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -12,6 +13,10 @@
 #include "attn_kernel.hpp"
 #include "match_kernel.hpp"
 #include "merge_kernel.hpp"
+
+// Split-K partials of mac_attn_full_decode_static: one copy per GPU the library runs on, held until the process
+// ends.  In host code this name is only a handle for hipGetSymbolAddress; kernels get the address it returns.
+static __device__ __align__(256) unsigned char scratch[MAC_ATTN_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -28,12 +33,25 @@ int hip_fail(hipError_t e, const char* what) {
         if (e_ != hipSuccess) return hip_fail(e_, #expr);    \
     } while (0)
 
-// Default tokens per work item: a full-length step should have about 2000 work items (4 rounds of the
-// 512 work-groups the chip holds), within [512, 2048]; and at least 64 tokens per head of the group, so that
-// the partial a work item writes (516 B per head) stays below ~1.5 % of the K/V it reads (512 B per token) --
-// at 32 heads per KV head (MQA) a 512-token item would write 6 %, and measured 153 us against 112 us at 2048.
-// (4096-token items stream a full-length step 1-3 % faster (11 % for MQA), but balance worse when most groups
-// reuse a prefix and a few do not: 168 us against 156 us at 89 % hits on 32 groups of 131072 tokens.)
+// Address of this GPU's copy of `scratch`, looked up once per device (each GPU holds the array at an address of
+// its own).  `device` must be the current device.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(int device, void** out) {
+    if (device < 0 || device >= kMaxDevices) return MAC_ATTN_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[device] == nullptr) {
+        void* ptr = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (ptr == nullptr) return MAC_ATTN_ERR_HIP;
+        g_scratch_ptr[device] = ptr;
+    }
+    *out = g_scratch_ptr[device];
+    return MAC_ATTN_OK;
+}
+
 // Every device buffer of a context lies between two guard zones of this many bytes holding kGuardByte;
 // mac_attn_check_guards reports a write that strayed into one.
 constexpr int64_t kGuardBytes = 256;
@@ -43,6 +61,12 @@ constexpr int kNumBuffers = 10;
 // KV groups (requests x kv heads) from which the attention grid is dispatched group-fastest (see attn_kernel)
 constexpr int kGroupFastestFrom = 16;
 
+// Default tokens per work item: a full-length step should have about 2000 work items (4 rounds of the
+// 512 work-groups the chip holds), within [512, 2048]; and at least 64 tokens per head of the group, so that
+// the partial a work item writes (516 B per head) stays below ~1.5 % of the K/V it reads (512 B per token) --
+// at 32 heads per KV head (MQA) a 512-token item would write 6 %, and measured 153 us against 112 us at 2048.
+// (4096-token items stream a full-length step 1-3 % faster (11 % for MQA), but balance worse when most groups
+// reuse a prefix and a few do not: 168 us against 156 us at 89 % hits on 32 groups of 131072 tokens.)
 int default_chunk(int64_t groups, int64_t max_kv_len, int heads_per_group) {
     const int64_t target = groups * max_kv_len / 2048;
     int chunk = 512;
@@ -344,6 +368,8 @@ const char* mac_attn_strerror(int code) {
         case MAC_ATTN_ERR_HIP: return "HIP runtime error";
         case MAC_ATTN_ERR_OOM: return "out of device memory";
         case MAC_ATTN_ERR_CORRUPT: return "a guard zone around a device buffer of the context was overwritten";
+        case MAC_ATTN_ERR_TOO_LARGE:
+            return "the call needs more split-K workspace than the static buffer of mac_attn_full_decode_static holds";
         default: return "unknown error code";
     }
 }
@@ -384,6 +410,10 @@ int mac_attn_init(const mac_attn_config* cfg, mac_attn_ctx** out_ctx) {
     HIP_TRY(hipGetDeviceCount(&ndev));
     if (cfg->device >= ndev) return MAC_ATTN_ERR_INVALID_ARG;
     HIP_TRY(hipSetDevice(cfg->device));
+    {   // set-up of mac_attn_full_decode_static on this device, so that its first call has nothing left to look up
+        void* unused = nullptr;
+        if ((rc = static_scratch(cfg->device, &unused)) != MAC_ATTN_OK) return rc;
+    }
     mac_attn_ctx* ctx = new (std::nothrow) mac_attn_ctx();
     if (ctx == nullptr) return MAC_ATTN_ERR_OOM;
     ctx->cfg = *cfg;
@@ -448,6 +478,48 @@ int mac_attn_full_decode(mac_attn_ctx* ctx, const mac_attn_step_args* args, void
     t.skip(3);
     t.finish();
     return t.rc;
+}
+
+int mac_attn_full_decode_static(const mac_attn_static_geometry* geo, const mac_attn_step_args* args, void* hip_stream) {
+    if (geo == nullptr || args == nullptr) return MAC_ATTN_ERR_INVALID_ARG;
+    // a context on the stack (nothing is allocated): the configuration of a full decode, and the static array as its
+    // split-K workspace
+    mac_attn_ctx tmp;
+    mac_attn_config& c = tmp.cfg;
+    std::memset(&c, 0, sizeof(c));
+    c.device = geo->device;
+    c.max_slots = c.max_batch = args->batch;
+    c.num_q_heads = geo->num_q_heads;
+    c.num_kv_heads = geo->num_kv_heads;
+    c.head_dim = geo->head_dim;
+    c.page_size = geo->page_size;
+    c.window = 1;
+    c.sm_scale = geo->sm_scale;
+    c.max_kv_len = geo->max_kv_len;
+    c.chunk_tokens = geo->chunk_tokens;
+    c.out_dtype = geo->out_dtype;
+    int rc = validate_config(&c, &tmp.L);
+    if (rc != MAC_ATTN_OK) return rc;
+    if ((rc = validate_args(&tmp, args, /*need_pre=*/false)) != MAC_ATTN_OK) return rc;
+    const Layout& L = tmp.L;
+    const int64_t bh = (int64_t)args->batch * c.num_q_heads;
+    const int64_t part_O_bytes = bh * L.n_mid_slots * mac::kHeadDim * 4, part_lse_bytes = bh * L.n_mid_slots * 4;
+    if (part_O_bytes + part_lse_bytes > (int64_t)MAC_ATTN_STATIC_SCRATCH_BYTES) return MAC_ATTN_ERR_TOO_LARGE;
+    int ndev = 0;
+    HIP_TRY(hipGetDeviceCount(&ndev));
+    if (c.device >= ndev) return MAC_ATTN_ERR_INVALID_ARG;
+    if ((rc = ensure_device(&tmp)) != MAC_ATTN_OK) return rc;
+    void* base = nullptr;
+    if ((rc = static_scratch(c.device, &base)) != MAC_ATTN_OK) return rc;
+    tmp.sm_scale = c.sm_scale > 0.f ? c.sm_scale : 1.0f / std::sqrt((float)c.head_dim);
+    tmp.T2 = 0.0;
+    // band = 0, so the layout has no band work items: a head's partials are n_mid_slots rows apart
+    tmp.part_O = static_cast<float*>(base);
+    tmp.part_lse = reinterpret_cast<float*>(static_cast<char*>(base) + part_O_bytes);
+    // Every partial the merge reads is written by this call's attention kernel first, so nothing has to be cleared.
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if ((rc = launch_attention(&tmp, args, false, stream)) != MAC_ATTN_OK) return rc;
+    return launch_merge(&tmp, args, false, false, stream);
 }
 
 int mac_attn_decode_step(mac_attn_ctx* ctx, const mac_attn_step_args* args, void* hip_stream) {
