@@ -22,7 +22,9 @@
  *     synchronisation, no device-to-host copy.  The library borrows the argument buffers until the stream
  *     has executed the enqueued work.  One context must not be used from two streams/threads at once.
  *   - Device-resident values (kv_lens, slot_ids, block_table) cannot be validated by the host; kv_len is
- *     clamped to [0, max_kv_len] on the device, slot ids and page ids must be in range.
+ *     clamped to [0, max_kv_len] on the device, slot ids and page ids must be in range.  Only the pages
+ *     block_table lists for the first ceil(kv_len / page_size) logical pages of a request are read, and of the
+ *     last one only the rows below kv_len: other pages and rows may hold anything (NaN included).
  */
 #ifndef MAC_ATTN_H
 #define MAC_ATTN_H
@@ -50,9 +52,9 @@ typedef struct mac_attn_config {
     int32_t max_slots;     /* number of per-request ring sets (>= 1)                                      */
     int32_t max_batch;     /* largest batch of one call (1 .. max_slots)                                  */
     int32_t num_q_heads;   /* Hq                                                                          */
-    int32_t num_kv_heads;  /* Hkv; Hq % Hkv == 0, group size G = Hq/Hkv in {1..16, 32}                    */
+    int32_t num_kv_heads;  /* Hkv; Hq % Hkv == 0, group size G = Hq/Hkv in 1 .. 32                        */
     int32_t head_dim;      /* must be 128                                                                 */
-    int32_t page_size;     /* tokens per KV page: a multiple of 16                                        */
+    int32_t page_size;     /* tokens per KV page: a power of two >= 16                                    */
     int32_t window;        /* W >= 1 (paper's K), at most 4096                                            */
     int32_t band;          /* B >= 0 (paper's r)                                                          */
     float   threshold;     /* T: absolute pre-RoPE L2 distance (paper: sqrt(2d)(1 - tau));
@@ -148,11 +150,15 @@ int mac_attn_full_decode_static(const mac_attn_static_geometry* geo /*host*/, co
                                 void* hip_stream);
 
 /* Wait for all work on the context's device (steps may have been replayed from a captured graph on any stream),
- * then read the counters into *out; reset != 0 clears them. */
+ * then read the counters into *out; reset != 0 clears them.  The counters are the quantities the paper reports per
+ * run: acceptance (hit) rate and skipped-prefix ratio (Sec. 5.3 "Setup and metrics"), reuse gap and KV tokens read
+ * when a KV group streams from the smallest start among its heads (Sec. 5.8), and the match / miss tallies App. B.3
+ * recommends monitoring. */
 int mac_attn_stats(mac_attn_ctx* ctx, mac_attn_stats_t* out /*host*/, int reset);
 
 /* Empty the rings of the given ring sets (a new request takes over the slot); null/n <= 0 = all sets.
- * Waits for all work on the context's device first. */
+ * Sec. 4.1: the rings are per request, indexed by the request's own length, so a slot handed to a new request must
+ * start with no entries (its first step misses).  Waits for all work on the context's device first. */
 int mac_attn_reset(mac_attn_ctx* ctx, const int32_t* slot_ids /*host*/, int32_t n);
 
 /* Test/diagnostic accessor: copy ring entry j (0 <= j < W) of ring set `slot`, head h, to host buffers

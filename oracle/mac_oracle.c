@@ -27,7 +27,7 @@
  *     of "total minus band"), so summaries chain across consecutive hits;
  *   - every step inserts, hit or miss; rings start empty.
  * Two variants beyond the per-head test (both off by default):
- *   - distance cap (appendix on prefill, "Recommendations" (i); Sec. C "Common issues" (2)): the nearest
+ *   - distance cap (appendix on prefill, "Recommendations" (i); App. B.3 "Common issues" (2)): the nearest
  *     candidate is accepted only if it also lies at most max_gap positions back, n - n_p <= max_gap;
  *   - one reuse point per KV group instead of per query head (the paper matches per query head, Sec. 4;
  *     this variant removes the skew inside a group of Sec. 5.8): the distance of a candidate is that of

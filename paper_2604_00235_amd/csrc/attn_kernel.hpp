@@ -243,8 +243,14 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnParams p) {
     const int d_lo = tt_lo - chunk_tile0 - w, d_hi = tt_hi - chunk_tile0 - w;
     const int k_first = d_lo > 0 ? (d_lo + 3) >> 2 : 0;
     const int k_end = d_hi >= 0 ? (d_hi >> 2) + 1 : 0;        // one past the last; <= 32 because chunk <= 4096
-    // a sub-tile wholly past the end reads page 0 (always allocated) instead of an unknown table entry
-    if ((chunk_tile0 + w + 4 * pk) * kTileTokens + 16 * pu >= n) mypid = 0;
+    // A sub-tile wholly past the end (only the second one of a request's last tile can be) has no table entry of its
+    // own: it re-reads the tile's first sub-tile, whose rows are real data of this request (its scores are masked, but
+    // its V rows still enter the P V product with weight 0, so they must be finite: no page the request does not own is
+    // ever touched).
+    {
+        const int first_sub = __shfl(mypid, l & ~1);
+        if ((chunk_tile0 + w + 4 * pk) * kTileTokens + 16 * pu >= n) mypid = first_sub;
+    }
     const int page_mask = (1 << p.page_shift) - 1;
     const uint16_t* kv_g = p.kv_pages + (int64_t)g * p.stride_head;
 
@@ -265,9 +271,9 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnParams p) {
         const int t0 = (chunk_tile0 + w + 4 * k) * kTileTokens;
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
-            const bool past = t0 + 16 * u >= n;
-            const int tb = past ? 0 : t0 + 16 * u;
-            const uint32_t lim_b = (uint32_t)(past ? 15 : min(15, n - 1 - tb)) * tok_bytes;   // last valid row, in bytes
+            const bool past = t0 + 16 * u >= n;                   // then u == 1 and t0 < n: the tile intersects [lo, hi)
+            const int tb = past ? t0 : t0 + 16 * u;
+            const uint32_t lim_b = (uint32_t)min(15, n - 1 - tb) * tok_bytes;                 // last valid row, in bytes
             const int pid = __builtin_amdgcn_readlane(mypid, 2 * k + u);
             const char* base = reinterpret_cast<const char*>(kv_g + (int64_t)pid * p.stride_page +
                                                              (int64_t)(tb & page_mask) * p.stride_tok);

@@ -200,21 +200,89 @@ def test_group_granular_matching_with_cap_ar1_queries():
 
 
 def test_bf16_output_is_the_rounded_fp32_output():
-    """out_dtype = bf16: the same step on two contexts, one per output type; the bf16 result must be the fp32
-    result rounded to nearest even (torch's conversion is the reference rounding), for decode_step and full_decode."""
-    from tests.gpu_harness import DeviceRun
+    """out_dtype = bf16: the same step on two contexts, one per output type.  The fp32 context is checked against the
+    oracle (decisions, decode_step and full_decode outputs); the bf16 result must be that fp32 result rounded to
+    nearest even (torch's conversion is the reference rounding)."""
+    from tests.gpu_harness import DeviceRun, check_rows
+    from tests.helpers import make_oracle
     cfg = scaled(CONFIGS["C2"], name="bf16out", batch=2, context=700, steps=6, window=8, band=32, threshold=2.8)
     wl = Workload(cfg, device="cuda:0")
     r32 = DeviceRun(cfg, wl, chunk_tokens=128)
     r16 = DeviceRun(cfg, wl, chunk_tokens=128, out_bf16=True)
-    for q_pre, q_rope, kv_lens in wl:
+    orc = make_oracle(cfg, wl)
+    kvp, bt, slots = bf16_bits(wl.kv_pages), wl.block_table.cpu().numpy(), wl.slot_ids.cpu().numpy()
+    for s, (q_pre, q_rope, kv_lens) in enumerate(wl):
+        lens = kv_lens.cpu().numpy()
         for mode in ("full", "mac"):
             for run in (r32, r16):
                 a = run.args(q_pre if mode == "mac" else None, q_rope, kv_lens)
                 (run.mac.decode_step if mode == "mac" else run.mac.full_decode)(a, run.stream)
             torch.cuda.synchronize()
+            r32.check_guards()
+            r16.check_guards()
+            if mode == "full":
+                ref_out, _ = orc.full_decode(lens, bf16_bits(q_rope), kvp, bt)
+            else:
+                ref = orc.mac_step(slots, lens, bf16_bits(q_pre), bf16_bits(q_rope), kvp, bt)
+                ref_out = ref["out"]
+                assert np.array_equal(r32.pos.cpu().numpy(), ref["match_pos"])
+            check_rows(r32.out.cpu().numpy(), ref_out, f"bf16out step {s} {mode} (fp32 context)")
             assert r16.out.dtype == torch.bfloat16
             assert torch.equal(r16.out, r32.out.to(torch.bfloat16)), mode
         assert torch.equal(r16.pos, r32.pos)
     r32.mac.close()
     r16.mac.close()
+
+
+@pytest.mark.parametrize("group", [17, 20, 24, 31])
+def test_group_sizes_between_17_and_31(group):
+    """Two 16-head tiles of which the second is partly filled (the remaining rows carry zero queries and are never
+    stored): mixed hits and misses inside the group, ragged lengths, several work items."""
+    from tests.gpu_harness import run_parity
+    cfg = WorkloadConfig(name=f"G{group}", batch=2, num_q_heads=group * 2, num_kv_heads=2, context=1200, steps=12,
+                         window=8, band=40, threshold=2.8, rho=0.97, seed=31, ragged=19)
+    r = run_parity(cfg, chunk_tokens=256, check_ring_every=2)
+    assert 0 < r["hits"] < r["head_steps"]
+
+
+@pytest.mark.parametrize("page_size,context", [(16, 1024 + 3), (16, 2048 + 10), (64, 1024 + 9), (32, 777)])
+def test_memory_the_request_does_not_own_may_hold_nan(page_size, context):
+    """Only the pages a request's block table lists, and of its last page only the rows below kv_len, are the
+    request's data.  Here every other byte of the cache is a NaN / Inf pattern: physical page 0 belongs to nobody, and
+    in each request's last page the rows past the end are poisoned before every step.  Lengths are chosen so that the
+    second 16-token half of the last 32-token tile lies wholly past the end (kv_len mod 32 in 1..16) on some steps."""
+    from tests.gpu_harness import DeviceRun, check_rows
+    from tests.helpers import make_oracle
+    cfg = WorkloadConfig(name="poison", batch=2, num_q_heads=8, num_kv_heads=2, context=context, steps=6, window=4, band=24,
+                         threshold=T_DEFAULT, rho=0.97, seed=41, page_size=page_size, ragged=32)
+    wl = Workload(cfg, device="cuda:0")
+    pages = torch.cat([torch.zeros_like(wl.kv_pages[:1]), wl.kv_pages]).contiguous()
+    bad = torch.tensor([0x7FC0, 0x7F80, 0xFF80, 0xFFFF], dtype=torch.int32).to(torch.int16).to("cuda:0")
+    pages[0].view(torch.int16).view(-1, 4)[:] = bad                      # page 0: NaN, +Inf, -Inf, NaN
+    wl.block_table = (wl.block_table + 1).contiguous()
+    wl.kv_pages = pages
+    run = DeviceRun(cfg, wl, chunk_tokens=256)
+    orc = make_oracle(cfg, wl)
+    bt, slots = wl.block_table.cpu().numpy(), wl.slot_ids.cpu().numpy()
+    hits = 0
+    for s, (q_pre, q_rope, kv_lens) in enumerate(wl):
+        lens = kv_lens.cpu().numpy()
+        clean = pages.clone()
+        for b in range(cfg.batch):                                      # rows [n, end of the last page) of request b
+            n = int(lens[b])
+            if n % page_size:
+                pg = int(bt[b, (n - 1) // page_size])
+                pages[pg, :, :, n % page_size:] = float("nan")
+        kvp = bf16_bits(pages)
+        f_out, f_lse = run.full(q_rope, kv_lens)
+        o_out, o_lse = orc.full_decode(lens, bf16_bits(q_rope), kvp, bt)
+        check_rows(f_out, o_out, f"poison step {s} full_decode")
+        g_out, g_lse, g_pos, _ = run.mac_step(q_pre, q_rope, kv_lens)
+        ref = orc.mac_step(slots, lens, bf16_bits(q_pre), bf16_bits(q_rope), kvp, bt)
+        assert np.array_equal(g_pos, ref["match_pos"])
+        check_rows(g_out, ref["out"], f"poison step {s} decode_step")
+        assert np.abs(g_lse - ref["lse"]).max() < 1e-3
+        hits += int((g_pos >= 0).sum())
+        pages.copy_(clean)                                              # the poisoned rows are later tokens' data
+    assert hits > 0
+    run.mac.close()

@@ -518,16 +518,3 @@ def test_stats_definitions():
     assert (st.kv_tokens_read, st.kv_tokens_full) == (read, full)
     assert st.sum_skip_frac == pytest.approx(skip, rel=1e-12)
     assert 0 < hits < st.head_steps
-
-
-def test_aux_memory_matches_paper_overhead_table():
-    """Sec. 5.9: rings cost about 5 % of the KV cache at K=1024, L=120K and 1.2 / 2.3 / 4.7 / 9.4 % at 128K for
-    K = 256 / 512 / 1024 / 2048 (Llama-3.1-8B geometry).  One ring entry per head = bf16 query (256 B) +
-    fp32 summary row (512 B) + fp32 ln-LSE (4 B) = 772 B; KV = 2 * 8 heads * 128 * 2 B = 4096 B per token."""
-    entry = 128 * 2 + 128 * 4 + 4
-    kv_per_token = 2 * 8 * 128 * 2
-    assert entry == 772
-    assert round(100 * 1024 * 32 * entry / (120 * 1024 * kv_per_token), 1) == 5.0
-    for K, pct in [(256, 1.2), (512, 2.4), (1024, 4.7), (2048, 9.4)]:
-        got = 100 * K * 32 * entry / (128 * 1024 * kv_per_token)
-        assert abs(got - pct) < 0.06, (K, got)     # the paper prints 2.3 for K=512 (its own rounding of 2.36)
