@@ -136,9 +136,11 @@ def run_config(name: str, steps: int, warmup: int, torch, mb, wl_mod, keep_kv=No
         "kernel_us": {"match": k_us[0] / k_n, "attention": k_us[1] / k_n, "merge": k_us[2] / k_n,
                       "writeback": k_us[3] / k_n},
         "full_kernel_us": {"attention": f_us[1] / f_n, "merge": f_us[2] / f_n},
-        # algorithmic bytes of the attention kernel per launch: K+V rows actually streamed (per KV group, from the
-        # group's smallest start), measured by the library's own counters over the event-timed steps
-        "attn_bytes_per_launch": KV_BYTES_PER_TOKEN_HEAD * st2["kv_tokens_read"] / k_n,
+        # algorithmic bytes of the split-K attention kernel per launch: K+V rows it streamed (per KV group, from the
+        # smallest start among the heads the match kernel did not finish itself), from the library's own counters
+        # over the event-timed steps; what the match kernel's hit path read per head is reported beside it
+        "attn_bytes_per_launch": KV_BYTES_PER_TOKEN_HEAD * st2["kv_tokens_split"] / k_n,
+        "fused_kv_bytes_per_step": KV_BYTES_PER_TOKEN_HEAD * st2["kv_tokens_fused"] / k_n,
         "full_attn_bytes_per_launch": KV_BYTES_PER_TOKEN_HEAD * full_tokens / f_n,
         "kv_len_mid": n_mid,
         "graph_us_per_step": graph_us,

@@ -73,6 +73,10 @@ typedef struct mac_attn_config {
                               d^2, hit iff D^2 < G * T^2; match_pos / match_d2 of every head of the group
                               carry the group's n_p / D^2.  Removes the skew inside a group (Sec. 5.8)     */
     int32_t out_dtype;     /* type of `out`: 0 = fp32, 1 = bf16 (rounded to nearest even)                 */
+    int32_t fused_hit_span;/* per-head matching only: a head that hits and whose fresh range [max(0, n_p - B), n)
+                              has at most this many tokens is finished by the match kernel's own work-group
+                              (attention over the range, merge with the prefix, ring append: Sec. 3.5 steps 1-3
+                              in one launch).  0 = default (1024), -1 = never, at most 2048                  */
 } mac_attn_config;
 
 /* Arguments of one decode step for a batch of requests. */
@@ -108,6 +112,10 @@ typedef struct mac_attn_stats_t {
     uint64_t kv_tokens_read;   /* sum over (request, kv head) of n - min over the group's heads of start   */
     uint64_t kv_tokens_full;   /* sum over (request, kv head) of n: what full attention would stream       */
     double   sum_skip_frac;    /* sum over (request, head) of (n_p - B)_+ / n, misses counted as 0         */
+    uint64_t kv_tokens_split;  /* what the split-K attention kernel streamed: sum over (request, kv head) of
+                                  n - min start over the group's heads that the match kernel did not finish    */
+    uint64_t kv_tokens_fused;  /* what the match kernel's hit path read: sum over the heads it finished of
+                                  n - start (per head, mostly from cache: a group's heads read the same rows)  */
 } mac_attn_stats_t;
 
 /* Create a context: allocates the rings (empty), the split-K workspace and the counters on cfg->device.

@@ -37,7 +37,7 @@ class mac_attn_config(C.Structure):
         ("page_size", C.c_int32), ("window", C.c_int32), ("band", C.c_int32),
         ("threshold", C.c_float), ("sm_scale", C.c_float),
         ("max_kv_len", C.c_int32), ("chunk_tokens", C.c_int32), ("fuse_epilogue", C.c_int32),
-        ("max_gap", C.c_int32), ("group_match", C.c_int32), ("out_dtype", C.c_int32),
+        ("max_gap", C.c_int32), ("group_match", C.c_int32), ("out_dtype", C.c_int32), ("fused_hit_span", C.c_int32),
     ]
 
 
@@ -64,7 +64,7 @@ class mac_attn_stats_t(C.Structure):
     _fields_ = [
         ("steps", C.c_uint64), ("head_steps", C.c_uint64), ("hits", C.c_uint64), ("misses", C.c_uint64),
         ("sum_gap", C.c_uint64), ("kv_tokens_read", C.c_uint64), ("kv_tokens_full", C.c_uint64),
-        ("sum_skip_frac", C.c_double),
+        ("sum_skip_frac", C.c_double), ("kv_tokens_split", C.c_uint64), ("kv_tokens_fused", C.c_uint64),
     ]
 
     def as_dict(self):
@@ -216,10 +216,12 @@ class MacAttention:
     def __init__(self, *, num_q_heads: int, num_kv_heads: int, window: int, band: int, threshold: float,
                  max_kv_len: int, max_slots: int, max_batch: Optional[int] = None, head_dim: int = 128,
                  page_size: int = 16, sm_scale: float = 0.0, chunk_tokens: int = 0, fuse_epilogue: bool = True,
-                 max_gap: int = 0, group_match: bool = False, out_bf16: bool = False, device: int = 0):
+                 max_gap: int = 0, group_match: bool = False, out_bf16: bool = False, fused_hit_span: int = 0,
+                 device: int = 0):
         self.cfg = mac_attn_config(device, max_slots, max_batch or max_slots, num_q_heads, num_kv_heads, head_dim,
                                    page_size, window, band, threshold, sm_scale, max_kv_len, chunk_tokens,
-                                   int(fuse_epilogue), int(max_gap), int(group_match), int(out_bf16))
+                                   int(fuse_epilogue), int(max_gap), int(group_match), int(out_bf16),
+                                   int(fused_hit_span))
         self.ctx = mac_attn_init(self.cfg)
 
     def make_args(self, *, kv_lens, q_rope, kv_pages, strides, block_table, out, slot_ids=None, q_pre=None,

@@ -47,7 +47,8 @@ namespace mac {
 
 struct AttnParams {
     const int32_t* kv_lens;      // [batch]
-    MatchView mv;                // per-head match results (part == nullptr: full decode, every head starts at 0)
+    const int32_t* head_start;   // [batch*Hq + 32] first key of each head's fresh range, | kHeadDone if the matcher has
+                                 // finished the head; null = full decode (every head starts at 0)
     const uint16_t* q_rope;      // [batch, Hq, 128] bf16
     const uint16_t* kv_pages;    // paged cache, bf16
     int64_t stride_page, stride_kv, stride_head, stride_tok;   // elements
@@ -55,17 +56,22 @@ struct AttnParams {
     int32_t bt_stride;
     float* part_O;               // [batch*Hq, n_slots, 128] normalised partial outputs
     float* part_lse;             // [batch*Hq, n_slots]      natural-log LSE of each partial
-    int32_t Hq, G;
+    int32_t batch, Hq, G;
     int32_t page_shift;          // log2(page_size)
     int32_t band;                // B; 0 for full decode (no band work items)
-    int32_t chunk;               // tokens per work item, multiple of 32, <= 4096
+    int32_t chunk_fixed;         // > 0: tokens per work item fixed by the caller (multiple of 32, <= 4096);
+                                 // 0: chosen per launch from the work the step has, within [chunk_min, 4096]
+    int32_t chunk_min;           // multiple of 32; the partial slots are laid out for it
     int32_t n_mid_slots, n_slots;
     int32_t max_kv_len;
-    int32_t group_fastest;       // dispatch order, see the kernel
     float scale_log2;            // sm_scale * log2(e)
-    const int32_t* head_start;   // [batch*Hq + 32] start of each head's fresh range if the match kernel stored it, else null
-    unsigned long long* st_read; // [batch*Hkv] KV tokens streamed per group (counter); null for full decode
+    int32_t* step_chunk;         // [1] tokens per work item of this launch, for the merge kernel (chunk_fixed == 0)
+    int32_t* work_counter;       // [1] work items handed out beyond the first gridDim.x; zero at launch (the merge
+                                 // kernel that follows every launch clears it)
+    unsigned long long* st_read; // [batch*Hkv] KV tokens the method streams per group (from the smallest start of all
+                                 // its heads); null for full decode
     unsigned long long* st_full; // [batch*Hkv] KV tokens a full decode would stream
+    unsigned long long* st_split;   // [batch*Hkv] KV tokens this kernel streams (heads the matcher finished excluded)
 };
 
 struct KVTile {
@@ -73,124 +79,67 @@ struct KVTile {
     u32x4 v[8];      // [e = 4*sub-tile + i] 8 d-columns of token 16*sub + 4i + kg
 };
 
-template <int HT>   // number of 16-head tiles: 1 (G <= 16) or 2 (G <= 32)
-__global__ __launch_bounds__(256, 2) void attn_kernel(const AttnParams p) {
-    // Work-groups are dispatched in linear order and dealt to the 8 XCDs round-robin; slots always run from the last
-    // one down (the band and the newest chunks, where a hit has its work, start first).  Two orders (p.group_fastest):
-    //  1: grid = (KV groups, slots).  A slot level is dispatched for all groups before the next one: neighbours read
-    //     neighbouring heads of the same pages, and the unused slots of max_kv_len do not sit between long work items
-    //     (measured 165 vs 174 us on 8 x 8 groups of 32768 tokens, 174 vs 200 us on 32 x 8 groups of 8450 tokens).
-    //     The groups are rotated by one position per level, so that the chunks of one group go to all XCDs in turn
-    //     (without the rotation a group with a miss keeps one XCD busy while others idle: 244 vs 154 us at 89 % hits).
-    //  0: grid = (slots, KV groups).  All slots of a group are dispatched in one burst.  With few groups that serves a
-    //     miss of one group faster: in order 1 its work items are spread over the whole dispatch sequence, most of
-    //     which is work-groups with nothing to do (batch 1, 120K, 1-3 of 8 groups missing: 42 vs 54 us per step).
-    const int Hkv = p.Hq / p.G;
-    int x, q;
-    if (p.group_fastest) {
-        x = gridDim.y - 1 - blockIdx.y;
-        q = (int)((blockIdx.x + blockIdx.y) % gridDim.x);
-    } else {
-        x = gridDim.x - 1 - blockIdx.x;
-        q = blockIdx.y;
-    }
-    const int b = q / Hkv, g = q - b * Hkv;
-    const int tid = threadIdx.x, l = tid & 63;
-    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave index as a scalar: tile positions and page bases stay in SGPRs
-    const int r16 = l & 15, kg = l >> 4;
-    const int G = p.G;
-    const int C = p.chunk;
-    const int tiles_per_chunk = C >> 5;
-    const bool is_mid = x < p.n_mid_slots;
+// Fresh ranges of one KV group: n, band start, smallest / largest start among the heads this kernel serves (gs, gmax),
+// smallest start among all heads (gs_all: what the method streams per KV group, Sec. 5.8 -- a counter only).
+struct GroupSpan {
+    int n, nb, gs, gmax, gs_all;
+    bool any;                    // some head of the group is served by this kernel
+};
 
-    // Page ids of this wave's 16-token sub-tiles, one per lane: lane i <-> (k = i/2, sub-tile i%2), where the
-    // wave's k-th tile of the chunk is chunk_tile0 + w + 4k.  For a mid chunk the chunk's position follows from
-    // blockIdx alone, so the ids are requested before kv_lens arrives (one dependent memory round trip less);
-    // entries at or past the end of the request (possibly uninitialised) are discarded below.
-    const int pk = l >> 1, pu = l & 1;
-    int chunk_tile0 = x * tiles_per_chunk;
-    int mypid = 0;
-    auto fetch_pid = [&]() {
-        const int tok = (chunk_tile0 + w + 4 * pk) * kTileTokens + 16 * pu;
-        if (w + 4 * pk < tiles_per_chunk)
-            mypid = p.block_table[(int64_t)b * p.bt_stride + min(tok >> p.page_shift, p.bt_stride - 1)];
-    };
-    if (is_mid) fetch_pid();
-
-    const int n = clampi(p.kv_lens[b], 0, p.max_kv_len);
-    const int nb = n - p.band > 0 ? n - p.band : 0;          // the band is [nb, n)
-    const int hbase = b * p.Hq + g * G;
-    if (!is_mid) {                                           // a band chunk's position needs kv_len only
-        chunk_tile0 = (nb / C + (x - p.n_mid_slots)) * tiles_per_chunk;
-        fetch_pid();
-    }
-
-    // With the heads' starts stored by the match kernel, a work-group without work finds that out from G scalar
-    // loads issued together with kv_len, without the cross-lane reduction of the match results below.
-    if (p.head_start != nullptr && x != 0) {
+__device__ __forceinline__ GroupSpan group_span(const AttnParams& p, int b, int hbase) {
+    GroupSpan s;
+    s.n = clampi(p.kv_lens[b], 0, p.max_kv_len);
+    s.nb = s.n - p.band > 0 ? s.n - p.band : 0;              // the band is [nb, n)
+    s.gs = 0; s.gmax = 0; s.gs_all = 0;
+    s.any = true;
+    if (p.head_start != nullptr) {
         // (the array is padded by 32 entries, so that blocks of 16 loads can be issued without a bound check)
-        int gs0 = nb;
-        for (int i0 = 0; i0 < G; i0 += 16) {
+        s.gs = s.nb; s.gs_all = s.nb;
+        s.any = false;
+        for (int i0 = 0; i0 < p.G; i0 += 16) {
             int t[16];
 #pragma unroll
             for (int j = 0; j < 16; ++j) t[j] = p.head_start[hbase + i0 + j];
 #pragma unroll
             for (int j = 0; j < 16; ++j)
-                if (i0 + j < G) gs0 = min(gs0, t[j]);
+                if (i0 + j < p.G) {
+                    const int sv = min(t[j] & (kHeadDone - 1), s.nb);
+                    s.gs_all = min(s.gs_all, sv);
+                    if (!(t[j] & kHeadDone)) {
+                        s.any = true;
+                        s.gs = min(s.gs, sv);
+                        s.gmax = max(s.gmax, sv);
+                    }
+                }
         }
-        int lo0, hi0;
-        if (is_mid) {
-            lo0 = max(gs0, x * C);
-            hi0 = min(nb, (x + 1) * C);
-        } else {
-            const int c0 = nb / C + (x - p.n_mid_slots);
-            lo0 = max(nb, c0 * C);
-            hi0 = min(n, (c0 + 1) * C);
-        }
-        if (lo0 >= hi0) return;
     }
+    return s;
+}
 
-    // smallest and largest start among the group's heads
-    int gs = 0, gmax = 0;
-    int my_start[HT];                                        // start of the head this lane holds in each head tile
-#pragma unroll
-    for (int ht = 0; ht < HT; ++ht) my_start[ht] = 0;
-    if (p.mv.part != nullptr) {
-        gs = nb;
-        const int hpp = 64 / p.mv.n_split;                   // heads decided per pass of the wave
-        for (int base = 0; base < G; base += hpp) {
-            const int cnt = min(hpp, G - base);
-            const MatchDecision md = match_decide_wave(p.mv, hbase + base, cnt, l, n);
-            const int s = clampi(md.start, 0, nb);
-            for (int i = 0; i < cnt; ++i) {                  // lane i * n_split holds head base + i
-                const int si = __builtin_amdgcn_readlane(s, i * p.mv.n_split);
-                gs = min(gs, si);
-                gmax = max(gmax, si);
-#pragma unroll
-                for (int ht = 0; ht < HT; ++ht)
-                    if (base + i == ht * 16 + r16) my_start[ht] = si;
-            }
-        }
-    }
-    // KV tokens streamed by this step for the group (read once per group from its smallest start, Sec. 5.8):
-    // counted by the group's first work-group, which always exists.  One writer per address and step, so the
-    // atomics only make the adds fire-and-forget.
-    if (x == 0 && tid == 0 && p.st_read != nullptr) {
-        atomicAdd(&p.st_read[b * Hkv + g], (unsigned long long)(n - gs));
-        atomicAdd(&p.st_full[b * Hkv + g], (unsigned long long)n);
-    }
-    int lo, hi;
-    if (is_mid) {
-        lo = max(gs, x * C);
-        hi = min(nb, (x + 1) * C);
-    } else {
-        const int c = nb / C + (x - p.n_mid_slots);
-        lo = max(nb, c * C);
-        hi = min(n, (c + 1) * C);
-    }
-    if (lo >= hi) return;
-    const int maxstart = max(gmax, lo);                       // tiles at or above it need no start mask
+// Work items of a group for C tokens per item: the range [gs, nb) cut on the global grid of C tokens ("mid" items, chunk
+// indices gs/C .. ceil(nb/C)-1) and the band [nb, n) cut on the same grid ("band" items).
+__device__ __forceinline__ int mid_items(const GroupSpan& s, int C) { return s.nb > s.gs ? (s.nb + C - 1) / C - s.gs / C : 0; }
+__device__ __forceinline__ int band_items(const GroupSpan& s, int C) { return s.n > s.nb ? (s.n + C - 1) / C - s.nb / C : 0; }
 
+constexpr int kAttnRoundsMin = 2;        // work items per work-group a launch aims at, at least
+constexpr int kAttnChunkPref = 2048;     // tokens per work item once the chip is full (more rounds instead of longer items)
+constexpr int kAttnChunkMax = 4096;
+
+template <int HT> struct AttnCaps { static constexpr int kMaxGroups = HT == 1 ? 4096 : 512; };
+
+template <int HT>
+__device__ __forceinline__ void attn_item(const AttnParams& p, int C, int q, int k, float (&s_O)[4][HT * 16 * kHeadDim],
+                                          float (&s_m)[4][HT * 16], float (&s_l)[4][HT * 16], char* s_q, int (&s_skip)[HT * 16]);
+
+// The planner of the paper (Sec. 4.2 K2 (1), App. B.2 "Load balancing": work-groups in proportion to span) runs inside
+// the kernel: every work-group derives the same list of work items from kv_lens and the heads' starts -- one thread
+// per KV group, a block-wide sum for the step's total span, from it the tokens per item (so that a step with little
+// work still spreads over the chip and a step with much work takes a whole number of rounds), a block-wide prefix sum
+// of the groups' item counts -- and then takes items: its own index first, further ones from a counter.  The grid is
+// the number of work-groups the chip holds, not the number of items max_kv_len could have, so a step whose heads were
+// all finished by the matcher costs one short round trip per resident work-group.
+template <int HT>   // number of 16-head tiles: 1 (G <= 16) or 2 (G <= 32)
+__global__ __launch_bounds__(256, 2) void attn_kernel(const AttnParams p) {
     // Shared memory.  s_O carries the waves' states to the merge at the end.  With two head tiles (HT == 2) a wave
     // keeps only one tile's output accumulators in registers: during the stream s_O[w] holds both tiles'
     // accumulators in register layout ([tile][column block j][lane] x 16 B: conflict-free) and each tile is loaded,
@@ -204,17 +153,158 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnParams p) {
     __shared__ float s_l[4][HT * 16];
     constexpr int kQRowBytes = 2 * kHeadDim + 16;
     __shared__ __attribute__((aligned(16))) char s_q[HT == 2 ? 32 * kQRowBytes : 16];
+    __shared__ int s_skip[HT * 16];
+    __shared__ int s_prefix[AttnCaps<HT>::kMaxGroups + 1];   // work items before group q
+    __shared__ long long s_tok[4];
+    __shared__ int s_cnt[4];
+    __shared__ int s_next;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int Hkv = p.Hq / p.G, NG = p.batch * Hkv;
+    const int P = gridDim.x;
+
+    // ---- plan, pass 1: the step's total span and the number of groups with work
+    int C = p.chunk_fixed;
+    if (C == 0) {
+        long long tok = 0;
+        int act = 0;
+        for (int q = tid; q < NG; q += 256) {
+            const int b = q / Hkv, g = q - b * Hkv;
+            const GroupSpan s = group_span(p, b, b * p.Hq + g * p.G);
+            if (s.any && s.n > s.gs) { tok += s.n - s.gs; ++act; }
+        }
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            tok += __shfl_xor(tok, off);
+            act += __shfl_xor(act, off);
+        }
+        if (lane == 0) { s_tok[wv] = tok; s_cnt[wv] = act; }
+        __syncthreads();
+        tok = s_tok[0] + s_tok[1] + s_tok[2] + s_tok[3];
+        act = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
+        __syncthreads();
+        // rounds: as many as items of the preferred size need, at least kAttnRoundsMin; every group adds up to two
+        // partial items (the grid of C tokens is global), which must fit into the last round, not start a new one
+        long long rounds = (tok + (long long)P * kAttnChunkPref - 1) / ((long long)P * kAttnChunkPref);
+        if (rounds < kAttnRoundsMin) rounds = kAttnRoundsMin;
+        long long target = rounds * P - 2 * act;
+        if (target < P / 2) target = P / 2;
+        long long c = (tok + target - 1) / target;
+        c = (c + 31) & ~31ll;
+        C = (int)(c < p.chunk_min ? p.chunk_min : (c > kAttnChunkMax ? kAttnChunkMax : c));
+    }
+    C = __builtin_amdgcn_readfirstlane(C);                   // uniform values in scalar registers: what derives from them stays there
+    // ---- plan, pass 2: items per group, prefix sums; the first work-group also keeps the per-group counters
+    int total = 0;
+    for (int q0 = 0; q0 < NG; q0 += 256) {
+        const int q = q0 + tid;
+        int items = 0;
+        if (q < NG) {
+            const int b = q / Hkv, g = q - b * Hkv;
+            const GroupSpan s = group_span(p, b, b * p.Hq + g * p.G);
+            if (s.any) items = mid_items(s, C) + band_items(s, C);
+            if (blockIdx.x == 0 && p.st_read != nullptr) {   // one writer per address and step: fire-and-forget adds
+                atomicAdd(&p.st_read[q], (unsigned long long)(s.n - s.gs_all));
+                atomicAdd(&p.st_full[q], (unsigned long long)s.n);
+                if (s.any) atomicAdd(&p.st_split[q], (unsigned long long)(s.n - s.gs));
+            }
+        }
+        int incl = items;                                    // inclusive scan inside the wave
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int v = __shfl_up(incl, off);
+            if (lane >= off) incl += v;
+        }
+        if (lane == 63) s_cnt[wv] = incl;
+        __syncthreads();
+        int before = total;
+        for (int ww = 0; ww < wv; ++ww) before += s_cnt[ww];
+        if (q < NG) s_prefix[q] = before + incl - items;
+        total += s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
+        __syncthreads();
+    }
+    if (tid == 0) {
+        s_prefix[NG] = total;
+        if (blockIdx.x == 0 && p.step_chunk != nullptr) *p.step_chunk = C;
+    }
+    __syncthreads();
+    total = __builtin_amdgcn_readfirstlane(s_prefix[NG]);
+
+    // ---- work items: the first one by position, further ones from the counter (requested while the current one runs)
+    int item = blockIdx.x;
+    while (item < total) {
+        int nxt = 0;
+        if (tid == 0) nxt = (int)atomicAdd(reinterpret_cast<unsigned int*>(p.work_counter), 1u);
+        int lo_q = 0, hi_q = NG;                             // the group: largest q with s_prefix[q] <= item
+        while (hi_q - lo_q > 1) {
+            const int mid = (lo_q + hi_q) >> 1;
+            if (s_prefix[mid] <= item) lo_q = mid; else hi_q = mid;
+        }
+        const int q = __builtin_amdgcn_readfirstlane(lo_q);
+        const int k = item - __builtin_amdgcn_readfirstlane(s_prefix[q]);
+        attn_item<HT>(p, C, q, k, s_O, s_m, s_l, s_q, s_skip);
+        if (tid == 0) s_next = nxt + P;
+        __syncthreads();
+        item = __builtin_amdgcn_readfirstlane(s_next);
+        __syncthreads();
+    }
+}
+
+// One work item: item `item_k` of KV group q with C tokens per item.  Contains barriers: called by the whole work-group.
+template <int HT>
+__device__ __forceinline__ void attn_item(const AttnParams& p, const int C, const int q, const int item_k,
+                                          float (&s_O)[4][HT * 16 * kHeadDim], float (&s_m)[4][HT * 16],
+                                          float (&s_l)[4][HT * 16], char* s_q, int (&s_skip)[HT * 16]) {
+    constexpr int kQRowBytes = 2 * kHeadDim + 16;
+    const int Hkv = p.Hq / p.G;
+    const int b = q / Hkv, g = q - b * Hkv;
+    const int tid = threadIdx.x, l = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave index as a scalar: tile positions and page bases stay in SGPRs
+    const int r16 = l & 15, kg = l >> 4;
+    const int G = p.G;
+    const int tiles_per_chunk = C >> 5;
+    const int hbase = b * p.Hq + g * G;
+    const GroupSpan sp = group_span(p, b, hbase);
+    const int n = sp.n, nb = sp.nb, gs = sp.gs, gmax = sp.gmax;
+    const int n_mid = mid_items(sp, C);
+    const bool is_mid = item_k < n_mid;
+    // chunk index on the global grid of C tokens, the item's token range, and its partial slot
+    const int x = is_mid ? gs / C + item_k : nb / C + (item_k - n_mid);
+    const int lo = is_mid ? max(gs, x * C) : max(nb, x * C);
+    const int hi = is_mid ? min(nb, (x + 1) * C) : min(n, (x + 1) * C);
+    const int slot = is_mid ? x : p.n_mid_slots + (item_k - n_mid);
+    if (lo >= hi) return;                                    // (the plan lists no empty item)
+
+    // Page ids of this wave's 16-token sub-tiles, one per lane: lane i <-> (k = i/2, sub-tile i%2), where the
+    // wave's k-th tile of the chunk is chunk_tile0 + w + 4k.
+    const int pk = l >> 1, pu = l & 1;
+    const int chunk_tile0 = x * tiles_per_chunk;
+    int mypid = 0;
+    {
+        const int tok = (chunk_tile0 + w + 4 * pk) * kTileTokens + 16 * pu;
+        if (w + 4 * pk < tiles_per_chunk)
+            mypid = p.block_table[(int64_t)b * p.bt_stride + min(tok >> p.page_shift, p.bt_stride - 1)];
+    }
+    int my_start[HT];                                        // start of the head this lane holds in each head tile,
+#pragma unroll                                               // | kHeadDone if the head needs nothing (or does not exist)
+    for (int ht = 0; ht < HT; ++ht) {
+        my_start[ht] = (ht * 16 + r16 < G) ? 0 : kHeadDone;
+        if (p.head_start != nullptr && ht * 16 + r16 < G) my_start[ht] = p.head_start[hbase + ht * 16 + r16];
+    }
+    const int maxstart = max(gmax, lo);                       // tiles at or above it need no start mask
 
     // per-lane head data for each head tile: first token this head attends to, and its query (B operand)
     int hstart[HT];
     bf16x8 qreg[HT == 1 ? 1 : 1][4];                          // HT == 1: the tile's query; HT == 2: unused
+    // a head that needs nothing here (finished by the matcher, or padding of the head tile) gets a zero query and no
+    // mask; its rows of the result are never stored
 #pragma unroll
     for (int ht = 0; ht < HT; ++ht) {
-        const int hh = ht * 16 + r16;
-        hstart[ht] = hh < G ? max(lo, my_start[ht]) : lo;
+        const bool skip = (my_start[ht] & kHeadDone) != 0;
+        hstart[ht] = skip ? lo : max(lo, min(my_start[ht], nb));
+        if (w == 0 && kg == 0) s_skip[ht * 16 + r16] = skip ? 1 : 0;
     }
     if constexpr (HT == 1) {
-        const bool valid = r16 < G;
+        const bool valid = !(my_start[0] & kHeadDone);
         const uint16_t* qp = p.q_rope + (int64_t)(hbase + (valid ? r16 : 0)) * kHeadDim + 8 * kg;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
@@ -228,7 +318,8 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnParams p) {
         for (int t = 0; t < 2; ++t) {
             const int idx = tid + 256 * t, row = idx >> 4, ch = idx & 15;
             u32x4 v = u32x4{0u, 0u, 0u, 0u};
-            if (row < G) v = *reinterpret_cast<const u32x4*>(p.q_rope + (int64_t)(hbase + row) * kHeadDim + 8 * ch);
+            const bool skip = row >= G || (p.head_start != nullptr && (p.head_start[hbase + (row < G ? row : 0)] & kHeadDone));
+            if (!skip) v = *reinterpret_cast<const u32x4*>(p.q_rope + (int64_t)(hbase + row) * kHeadDim + 8 * ch);
             *reinterpret_cast<u32x4*>(s_q + row * kQRowBytes + 16 * ch) = v;
         }
         // this wave's accumulators of both tiles start at zero
@@ -450,6 +541,7 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnParams p) {
     __syncthreads();
     for (int idx = tid; idx < G * kHeadDim; idx += 256) {
         const int h = idx >> 7, dd = idx & (kHeadDim - 1);
+        if (s_skip[h]) continue;
         float M = fmaxf(fmaxf(s_m[0][h], s_m[1][h]), fmaxf(s_m[2][h], s_m[3][h]));
         float o = 0.f, lse = -INFINITY;
         if (M != -INFINITY) {
@@ -463,9 +555,9 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnParams p) {
             o = a / L;
             lse = (M + __log2f(L)) * kLn2;
         }
-        const int64_t slot = (int64_t)(hbase + h) * p.n_slots + x;
-        p.part_O[slot * kHeadDim + dd] = o;
-        if (dd == 0) p.part_lse[slot] = lse;
+        const int64_t row = (int64_t)(hbase + h) * p.n_slots + slot;
+        p.part_O[row * kHeadDim + dd] = o;
+        if (dd == 0) p.part_lse[row] = lse;
     }
 }
 

@@ -36,6 +36,11 @@ __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_ex
 
 __device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
+// head_start[] holds, per (request, head), the first key of the head's fresh range; this flag is set when the per-head
+// matcher has already finished the head's whole step (hit with a short fresh range): the split-K attention kernel and
+// the merge kernel then skip the head.  Starts are below 2^30.
+constexpr int kHeadDone = 0x40000000;
+
 // Result of scanning one slice of a head's query-ring window: the nearest entry of the slice.
 struct MatchPartial {
     double d2;      // squared distance, +inf if the slice has no candidate
@@ -50,8 +55,7 @@ __device__ __forceinline__ bool better(double d2, int np, double od2, int onp) {
 
 // Where the per-slice results of the match kernel live and how to turn them into the decision.
 struct MatchView {
-    const MatchPartial* part;   // [batch*Hq, n_split]; nullptr = no matching (full decode)
-    int32_t n_split;
+    const MatchPartial* part;   // [batch*Hq] nearest entry of each head's window; nullptr = no matching (full decode)
     int32_t band;               // B
     int32_t max_gap;            // distance cap on n - n_p; 0 = none
     double T2;                  // (double)T * (double)T, times G when one reuse point is chosen per KV group
@@ -69,29 +73,27 @@ __device__ __forceinline__ bool match_accept(const MatchView& mv, double d2, int
     return np >= 1 && d2 < mv.T2 && (mv.max_gap <= 0 || n - np <= mv.max_gap);
 }
 
-// Final reduction over the slices and threshold test (paper Eq. (accept); Sec. 4.2 K1 "final reducer").
-// Every consumer (attention kernel, merge kernel) evaluates it itself from the same slice results, so the
-// decision needs no extra kernel and no inter-work-group synchronisation.
-//
-// One wave decides up to 64 / n_split consecutive heads at once: lane l holds slice l % n_split of head
-// bh0 + l / n_split (n_split is a power of two <= 64), one coalesced 16-byte load per lane, then a butterfly
-// inside each n_split-lane segment.  On return every lane of a segment holds its head's decision; lanes of
-// segments >= cnt hold a miss.  Must be called by all 64 lanes of the wave.  `n` is the request's kv_len (all heads
-// of one call belong to one request); it only enters through the optional distance cap n - n_p <= max_gap.
-__device__ __forceinline__ MatchDecision match_decide_wave(const MatchView& mv, int bh0, int cnt, int lane, int n) {
-    MatchDecision r{INFINITY, -1, -1, 0};
-    if (mv.part == nullptr) return r;
-    const int S = mv.n_split;
+// Nearest entry of a head's whole window from the slice results of the group matcher (paper Sec. 4.2 K1 "final
+// reducer").  One wave handles up to 64 / n_split consecutive heads at once: lane l holds slice l % n_split of head
+// bh0 + l / n_split (n_split is a power of two <= 64), one coalesced 16-byte load per lane, then a butterfly inside
+// each n_split-lane segment.  On return every lane of a segment holds its head's nearest entry; lanes of segments
+// >= cnt hold none.  Must be called by all 64 lanes of the wave.
+__device__ __forceinline__ MatchPartial match_nearest_wave(const MatchPartial* slices, int S, int bh0, int cnt, int lane) {
     const int seg = lane >> (31 - __builtin_clz(S));         // S is a power of two
     MatchPartial c{INFINITY, -1, -1};
-    if (seg < cnt) c = mv.part[(int64_t)bh0 * S + lane];
+    if (seg < cnt) c = slices[(int64_t)bh0 * S + lane];
     for (int off = S >> 1; off > 0; off >>= 1) {
         const double od2 = __shfl_xor(c.d2, off);
         const int onp = __shfl_xor(c.np, off);
         const int oj = __shfl_xor(c.j, off);
         if (better(od2, onp, c.d2, c.np)) { c.d2 = od2; c.np = onp; c.j = oj; }
     }
-    r.d2 = c.d2;
+    return c;
+}
+
+// The decision of a head from the nearest entry of its window (Eq. (accept)): threshold, then the optional distance cap.
+__device__ __forceinline__ MatchDecision decide(const MatchView& mv, const MatchPartial& c, int n) {
+    MatchDecision r{c.d2, -1, -1, 0};
     if (match_accept(mv, c.d2, c.np, n)) {
         r.np = c.np;
         r.j = c.j;

@@ -11,6 +11,7 @@
 #include <vector>
 
 #include "attn_kernel.hpp"
+#include "hit_kernel.hpp"
 #include "match_kernel.hpp"
 #include "merge_kernel.hpp"
 
@@ -56,17 +57,23 @@ int static_scratch(int device, void** out) {
 // mac_attn_check_guards reports a write that strayed into one.
 constexpr int64_t kGuardBytes = 256;
 constexpr int kGuardByte = 0xA5;
-constexpr int kNumBuffers = 10;
+constexpr int kNumBuffers = 12;
 
-// KV groups (requests x kv heads) from which the attention grid is dispatched group-fastest (see attn_kernel)
-constexpr int kGroupFastestFrom = 16;
+// Largest fresh range (tokens) of a hit that the per-head matcher finishes itself (see hit_kernel.hpp) by default
+constexpr int kDefaultFusedSpan = 1024;
 
-// Default tokens per work item: a full-length step should have about 2000 work items (4 rounds of the
-// 512 work-groups the chip holds), within [512, 2048]; and at least 64 tokens per head of the group, so that
-// the partial a work item writes (516 B per head) stays below ~1.5 % of the K/V it reads (512 B per token) --
-// at 32 heads per KV head (MQA) a 512-token item would write 6 %, and measured 153 us against 112 us at 2048.
-// (4096-token items stream a full-length step 1-3 % faster (11 % for MQA), but balance worse when most groups
-// reuse a prefix and a few do not: 168 us against 156 us at 89 % hits on 32 groups of 131072 tokens.)
+// Tokens per work item of the attention kernel.  With chunk_tokens = 0 the kernel chooses them per launch from the
+// work the step has (see attn_kernel.hpp), never below this minimum, for which the partial slots are laid out: 256
+// tokens, and at least 32 tokens per head of the group, so that the partial a work item writes (516 B per head) stays
+// small next to the K/V it reads (512 B per token).
+int min_chunk(int heads_per_group) {
+    int chunk = 256;
+    while (chunk < 32 * heads_per_group) chunk *= 2;
+    return chunk;
+}
+
+// Fixed tokens per work item for mac_attn_full_decode_static when the caller gives none: a full-length step should
+// have about 2000 work items, within [512, 2048], and at least 64 tokens per head of the group.
 int default_chunk(int64_t groups, int64_t max_kv_len, int heads_per_group) {
     const int64_t target = groups * max_kv_len / 2048;
     int chunk = 512;
@@ -75,13 +82,16 @@ int default_chunk(int64_t groups, int64_t max_kv_len, int heads_per_group) {
     return chunk;
 }
 
+constexpr int64_t kPlanBytes = 256;      // [0]: tokens per work item of the last launch; [16]: work-item counter (ints)
+
 struct Layout {            // derived sizes, pure host arithmetic
-    int G, chunk, n_mid_slots, n_band_slots, n_slots, page_shift, max_split;
+    int G, chunk_fixed, chunk_min, n_mid_slots, n_band_slots, n_slots, page_shift, max_split;
     int64_t ring_q_bytes, ring_O_bytes, ring_lse_bytes, ring_npos_bytes;
-    int64_t part_O_bytes, part_lse_bytes, match_bytes, rect_bytes, stats_bytes, head_start_bytes;
+    int64_t part_O_bytes, part_lse_bytes, slices_bytes, match_bytes, rect_bytes, stats_bytes, head_start_bytes;
     int64_t total() const {
         return ring_q_bytes + ring_O_bytes + ring_lse_bytes + ring_npos_bytes + part_O_bytes + part_lse_bytes +
-               match_bytes + rect_bytes + stats_bytes + head_start_bytes + 2 * kGuardBytes * kNumBuffers;
+               slices_bytes + match_bytes + rect_bytes + stats_bytes + head_start_bytes + kPlanBytes +
+               2 * kGuardBytes * kNumBuffers;
     }
 };
 
@@ -94,22 +104,26 @@ int validate_config(const mac_attn_config* c, Layout* L) {
     if (c->chunk_tokens < 0 || (c->fuse_epilogue != 0 && c->fuse_epilogue != 1)) return MAC_ATTN_ERR_INVALID_ARG;
     if (c->max_gap < 0 || (c->group_match != 0 && c->group_match != 1) || (c->out_dtype != 0 && c->out_dtype != 1))
         return MAC_ATTN_ERR_INVALID_ARG;
+    if (c->fused_hit_span < -1 || c->fused_hit_span > mac::kHitMaxSpan) return MAC_ATTN_ERR_INVALID_ARG;
+    if (c->max_kv_len >= mac::kHeadDone) return MAC_ATTN_ERR_INVALID_ARG;
     if (c->head_dim != mac::kHeadDim) return MAC_ATTN_ERR_UNSUPPORTED;
     const int G = c->num_q_heads / c->num_kv_heads;
     if (G > 32) return MAC_ATTN_ERR_UNSUPPORTED;
     if (c->page_size < 16 || (c->page_size & (c->page_size - 1)) != 0) return MAC_ATTN_ERR_UNSUPPORTED;
     if (c->window > 4096) return MAC_ATTN_ERR_UNSUPPORTED;
-    const int chunk = c->chunk_tokens == 0 ? default_chunk((int64_t)c->max_batch * c->num_kv_heads, c->max_kv_len, G)
-                                           : c->chunk_tokens;
+    const int chunk = c->chunk_tokens == 0 ? min_chunk(G) : c->chunk_tokens;
     if (chunk % mac::kTileTokens != 0 || chunk < 32 || chunk > 4096) return MAC_ATTN_ERR_INVALID_ARG;
     if ((int64_t)c->max_batch * c->num_q_heads > (1 << 24)) return MAC_ATTN_ERR_INVALID_ARG;
+    // the attention kernel plans its work items with one list entry per KV group in shared memory
+    const int64_t max_groups = G <= 16 ? mac::AttnCaps<1>::kMaxGroups : mac::AttnCaps<2>::kMaxGroups;
+    if ((int64_t)c->max_batch * c->num_kv_heads > max_groups) return MAC_ATTN_ERR_UNSUPPORTED;
     L->G = G;
-    L->chunk = chunk;
+    L->chunk_fixed = c->chunk_tokens;
+    L->chunk_min = chunk;
     L->n_mid_slots = (c->max_kv_len + chunk - 1) / chunk;
     const int band_span = c->band < c->max_kv_len ? c->band : c->max_kv_len;
     L->n_band_slots = band_span == 0 ? 0 : (band_span + chunk - 1) / chunk + 1;
     L->n_slots = L->n_mid_slots + L->n_band_slots;
-    if (L->n_slots > 65535) return MAC_ATTN_ERR_INVALID_ARG;      // a grid dimension
     int sh = 0;
     while ((1 << sh) < c->page_size) ++sh;
     L->page_shift = sh;
@@ -118,13 +132,15 @@ int validate_config(const mac_attn_config* c, Layout* L) {
     L->ring_q_bytes = entries * mac::kHeadDim * 2;
     L->ring_O_bytes = entries * mac::kHeadDim * 4;
     L->ring_lse_bytes = entries * 4;
-    L->ring_npos_bytes = (int64_t)c->max_slots * c->window * 4;
+    L->ring_npos_bytes = entries * 4;
     L->part_O_bytes = bh * L->n_slots * mac::kHeadDim * 4;
     L->part_lse_bytes = bh * L->n_slots * 4;
-    L->max_split = 64;                                      // window slices per head (power of two)
-    L->match_bytes = bh * L->max_split * (int64_t)sizeof(mac::MatchPartial);
+    L->max_split = 64;                                      // window slices of the group matcher (power of two)
+    L->slices_bytes = c->group_match ? bh * L->max_split * (int64_t)sizeof(mac::MatchPartial) : 16;
+    L->match_bytes = bh * (int64_t)sizeof(mac::MatchPartial);
     L->rect_bytes = bh * (mac::kHeadDim + 1) * 4;
-    L->stats_bytes = bh * 3 * 8 + (int64_t)c->max_batch * c->num_kv_heads * 2 * 8 + 2 * 8;
+    // counters: hits, gap, skip, fused tokens per (b, h); read, full, split tokens per (b, g); steps, head-steps
+    L->stats_bytes = bh * 4 * 8 + (int64_t)c->max_batch * c->num_kv_heads * 3 * 8 + 2 * 8;
     L->head_start_bytes = (bh + 32) * 4;                    // padded: read in blocks of 16 without a bound check
     return MAC_ATTN_OK;
 }
@@ -149,9 +165,12 @@ struct mac_attn_ctx {
     // per-step scratch
     float* part_O = nullptr;
     float* part_lse = nullptr;
-    mac::MatchPartial* m_part = nullptr;   // [bh, n_split] nearest entry per window slice (match kernel)
-    int32_t n_split = 1;                   // slices used by the current / last decode_step
-    int32_t* head_start = nullptr;         // [max_batch*Hq] fresh-range start per head, written by the match kernel when n_split == 1
+    mac::MatchPartial* m_slices = nullptr; // [bh, n_split] nearest entry per window slice (group matcher only)
+    mac::MatchPartial* m_part = nullptr;   // [bh] nearest entry of each head's window
+    int32_t* plan = nullptr;               // [0] tokens per work item of the last attention launch, [16] its work-item counter
+    int32_t grid_attn = 512;               // work-groups of the attention kernel: two per compute unit
+    int32_t fused_span = 0;                // largest fresh range the per-head matcher finishes itself (0 = none)
+    int32_t* head_start = nullptr;         // [max_batch*Hq + 32] fresh-range start per head (| kHeadDone), written by the matchers
     float* rect = nullptr;        // [bh*128] rows then [bh] lse
     // counters
     unsigned long long* stats = nullptr;
@@ -240,7 +259,6 @@ struct Timer {          // brackets the kernels of one call with events when tim
 mac::MatchView match_view(const mac_attn_ctx* ctx, bool mac_mode) {
     mac::MatchView mv;
     mv.part = mac_mode ? ctx->m_part : nullptr;
-    mv.n_split = ctx->n_split;
     mv.band = ctx->cfg.band;
     mv.T2 = ctx->T2;
     mv.max_gap = ctx->cfg.max_gap;
@@ -252,7 +270,7 @@ int launch_attention(mac_attn_ctx* ctx, const mac_attn_step_args* a, bool mac_mo
     const Layout& L = ctx->L;
     mac::AttnParams p;
     p.kv_lens = a->kv_lens;
-    p.mv = match_view(ctx, mac_mode);
+    p.head_start = mac_mode ? ctx->head_start : nullptr;
     p.q_rope = static_cast<const uint16_t*>(a->q_rope);
     p.kv_pages = static_cast<const uint16_t*>(a->kv_pages);
     p.stride_page = a->stride_page;
@@ -263,24 +281,27 @@ int launch_attention(mac_attn_ctx* ctx, const mac_attn_step_args* a, bool mac_mo
     p.bt_stride = a->block_table_stride;
     p.part_O = ctx->part_O;
     p.part_lse = ctx->part_lse;
+    p.batch = a->batch;
     p.Hq = c.num_q_heads;
     p.G = L.G;
     p.page_shift = L.page_shift;
     p.band = mac_mode ? c.band : 0;
-    p.chunk = L.chunk;
+    p.chunk_fixed = L.chunk_fixed;
+    p.chunk_min = L.chunk_min;
     p.n_mid_slots = L.n_mid_slots;
     p.n_slots = L.n_slots;
     p.max_kv_len = c.max_kv_len;
     p.scale_log2 = ctx->sm_scale * mac::kLog2e;
+    p.step_chunk = ctx->plan;
+    p.work_counter = ctx->plan + 16;
     const int64_t bh = (int64_t)c.max_batch * c.num_q_heads;
-    p.head_start = (mac_mode && ctx->n_split == 1) ? ctx->head_start : nullptr;
-    p.st_read = mac_mode ? ctx->stats + 3 * bh : nullptr;
-    p.st_full = mac_mode ? ctx->stats + 3 * bh + (int64_t)c.max_batch * c.num_kv_heads : nullptr;
-    const int gx = mac_mode ? L.n_slots : L.n_mid_slots;
-    const int pairs = c.num_kv_heads * a->batch;
-    p.group_fastest = pairs >= kGroupFastestFrom ? 1 : 0;
-    const dim3 grid = p.group_fastest ? dim3(pairs, gx) : dim3(gx, pairs);
-    const dim3 block(256);
+    const int64_t bg = (int64_t)c.max_batch * c.num_kv_heads;
+    p.st_read = mac_mode ? ctx->stats + 4 * bh : nullptr;
+    p.st_full = mac_mode ? ctx->stats + 4 * bh + bg : nullptr;
+    p.st_split = mac_mode ? ctx->stats + 4 * bh + 2 * bg : nullptr;
+    // as many work-groups as the chip holds, fewer if the call cannot have that many work items
+    const int64_t max_items = (int64_t)a->batch * c.num_kv_heads * (mac_mode ? L.n_slots : L.n_mid_slots);
+    const dim3 grid((unsigned)std::min<int64_t>(ctx->grid_attn, std::max<int64_t>(max_items, 1))), block(256);
     if (L.G <= 16)
         hipLaunchKernelGGL(mac::attn_kernel<1>, grid, block, 0, stream, p);
     else
@@ -297,6 +318,8 @@ mac::MergeParams merge_params(mac_attn_ctx* ctx, const mac_attn_step_args* a, bo
     p.kv_lens = a->kv_lens;
     p.slot_ids = mac_mode ? a->slot_ids : nullptr;
     p.mv = match_view(ctx, mac_mode);
+    p.head_start = mac_mode ? ctx->head_start : nullptr;
+    p.emit_decision = c.group_match;                     // per-head matching reports its decisions itself
     p.out_match_pos = mac_mode ? a->match_pos : nullptr;
     p.out_match_d2 = mac_mode ? a->match_d2 : nullptr;
     p.st_hits = mac_mode ? ctx->stats : nullptr;
@@ -315,7 +338,9 @@ mac::MergeParams merge_params(mac_attn_ctx* ctx, const mac_attn_step_args* a, bo
     p.G = L.G;
     p.W = c.window;
     p.band = mac_mode ? c.band : 0;
-    p.chunk = L.chunk;
+    p.chunk_fixed = L.chunk_fixed;
+    p.step_chunk = ctx->plan;
+    p.work_counter = ctx->plan + 16;
     p.n_mid_slots = L.n_mid_slots;
     p.n_slots = L.n_slots;
     p.max_kv_len = c.max_kv_len;
@@ -335,6 +360,7 @@ mac::WritebackParams writeback_params(mac_attn_ctx* ctx, const mac_attn_step_arg
     p.ring_O = ctx->ring_O;
     p.ring_lse = ctx->ring_lse;
     p.ring_npos = ctx->ring_npos;
+    p.head_start = ctx->head_start;
     p.Hq = c.num_q_heads;
     p.W = c.window;
     p.max_kv_len = c.max_kv_len;
@@ -421,6 +447,12 @@ int mac_attn_init(const mac_attn_config* cfg, mac_attn_ctx** out_ctx) {
     ctx->sm_scale = cfg->sm_scale > 0.f ? cfg->sm_scale : 1.0f / std::sqrt((float)cfg->head_dim);
     ctx->T2 = (double)cfg->threshold * (double)cfg->threshold;
     if (cfg->group_match) ctx->T2 = ctx->T2 * (double)L.G;      // concatenated group query: D^2 < G T^2
+    {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, cfg->device) != hipSuccess) cus = 0;
+        ctx->grid_attn = 2 * (cus > 0 ? cus : 256);
+    }
+    ctx->fused_span = cfg->fused_hit_span == 0 ? kDefaultFusedSpan : (cfg->fused_hit_span < 0 ? 0 : cfg->fused_hit_span);
     struct { void** p; int64_t bytes; bool zero; } allocs[] = {
         {reinterpret_cast<void**>(&ctx->ring_q), L.ring_q_bytes, true},
         {reinterpret_cast<void**>(&ctx->ring_O), L.ring_O_bytes, true},
@@ -428,7 +460,9 @@ int mac_attn_init(const mac_attn_config* cfg, mac_attn_ctx** out_ctx) {
         {reinterpret_cast<void**>(&ctx->ring_npos), L.ring_npos_bytes, true},
         {reinterpret_cast<void**>(&ctx->part_O), L.part_O_bytes, false},
         {reinterpret_cast<void**>(&ctx->part_lse), L.part_lse_bytes, false},
+        {reinterpret_cast<void**>(&ctx->m_slices), L.slices_bytes, true},
         {reinterpret_cast<void**>(&ctx->m_part), L.match_bytes, true},
+        {reinterpret_cast<void**>(&ctx->plan), kPlanBytes, true},
         {reinterpret_cast<void**>(&ctx->rect), L.rect_bytes, true},
         {reinterpret_cast<void**>(&ctx->stats), L.stats_bytes, true},
         {reinterpret_cast<void**>(&ctx->head_start), L.head_start_bytes, true},
@@ -498,25 +532,33 @@ int mac_attn_full_decode_static(const mac_attn_static_geometry* geo, const mac_a
     c.max_kv_len = geo->max_kv_len;
     c.chunk_tokens = geo->chunk_tokens;
     c.out_dtype = geo->out_dtype;
+    if (c.chunk_tokens == 0 && c.num_kv_heads > 0 && c.num_q_heads > 0)      // fixed tokens per work item (see the header)
+        c.chunk_tokens = default_chunk((int64_t)args->batch * c.num_kv_heads, c.max_kv_len, c.num_q_heads / c.num_kv_heads);
     int rc = validate_config(&c, &tmp.L);
     if (rc != MAC_ATTN_OK) return rc;
     if ((rc = validate_args(&tmp, args, /*need_pre=*/false)) != MAC_ATTN_OK) return rc;
     const Layout& L = tmp.L;
     const int64_t bh = (int64_t)args->batch * c.num_q_heads;
+    // band = 0, so the layout has no band work items: a head's partials are n_mid_slots rows apart
     const int64_t part_O_bytes = bh * L.n_mid_slots * mac::kHeadDim * 4, part_lse_bytes = bh * L.n_mid_slots * 4;
-    if (part_O_bytes + part_lse_bytes > (int64_t)MAC_ATTN_STATIC_SCRATCH_BYTES) return MAC_ATTN_ERR_TOO_LARGE;
+    if (kPlanBytes + part_O_bytes + part_lse_bytes > (int64_t)MAC_ATTN_STATIC_SCRATCH_BYTES) return MAC_ATTN_ERR_TOO_LARGE;
     int ndev = 0;
     HIP_TRY(hipGetDeviceCount(&ndev));
     if (c.device >= ndev) return MAC_ATTN_ERR_INVALID_ARG;
     if ((rc = ensure_device(&tmp)) != MAC_ATTN_OK) return rc;
     void* base = nullptr;
     if ((rc = static_scratch(c.device, &base)) != MAC_ATTN_OK) return rc;
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c.device) != hipSuccess) cus = 0;
+    tmp.grid_attn = 2 * (cus > 0 ? cus : 256);
     tmp.sm_scale = c.sm_scale > 0.f ? c.sm_scale : 1.0f / std::sqrt((float)c.head_dim);
     tmp.T2 = 0.0;
-    // band = 0, so the layout has no band work items: a head's partials are n_mid_slots rows apart
-    tmp.part_O = static_cast<float*>(base);
-    tmp.part_lse = reinterpret_cast<float*>(static_cast<char*>(base) + part_O_bytes);
-    // Every partial the merge reads is written by this call's attention kernel first, so nothing has to be cleared.
+    // Layout of the array: the attention kernel's work-item counter first, then the partials.  The counter must be
+    // zero when a call starts: it is zero when the library is loaded, and the merge kernel of every call clears it.
+    // Every partial the merge reads is written by this call's attention kernel first, so nothing else is cleared.
+    tmp.plan = static_cast<int32_t*>(base);
+    tmp.part_O = reinterpret_cast<float*>(static_cast<char*>(base) + kPlanBytes);
+    tmp.part_lse = reinterpret_cast<float*>(static_cast<char*>(base) + kPlanBytes + part_O_bytes);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if ((rc = launch_attention(&tmp, args, false, stream)) != MAC_ATTN_OK) return rc;
     return launch_merge(&tmp, args, false, false, stream);
@@ -533,47 +575,90 @@ int mac_attn_decode_step(mac_attn_ctx* ctx, const mac_attn_step_args* args, void
     Timer t(ctx, stream);
     if (t.rc != MAC_ATTN_OK) return t.rc;
 
-    // 1. match
-    {
+    // 1. match; per head it also finishes the heads that hit with a short fresh range
+    const int64_t bg = (int64_t)c.max_batch * c.num_kv_heads;
+    unsigned long long* st_steps = ctx->stats + 4 * bh + 3 * bg;
+    if (!c.group_match) {
+        mac::HitParams p;
+        p.slot_ids = args->slot_ids;
+        p.kv_lens = args->kv_lens;
+        p.q_pre = static_cast<const uint16_t*>(args->q_pre);
+        p.ring_q = ctx->ring_q;
+        p.ring_O = ctx->ring_O;
+        p.ring_lse = ctx->ring_lse;
+        p.ring_npos = ctx->ring_npos;
+        p.part = ctx->m_part;
+        p.head_start = ctx->head_start;
+        p.st_steps = st_steps;
+        p.st_hits = ctx->stats;
+        p.st_gap = ctx->stats + bh;
+        p.st_skip = reinterpret_cast<double*>(ctx->stats + 2 * bh);
+        p.st_fused = ctx->stats + 3 * bh;
+        p.out_match_pos = args->match_pos;
+        p.out_match_d2 = args->match_d2;
+        p.mv = match_view(ctx, true);
+        p.batch = args->batch;
+        p.Hq = c.num_q_heads;
+        p.G = ctx->L.G;
+        p.W = c.window;
+        p.max_kv_len = c.max_kv_len;
+        p.fused_span = ctx->fused_span;
+        p.q_rope = static_cast<const uint16_t*>(args->q_rope);
+        p.kv_pages = static_cast<const uint16_t*>(args->kv_pages);
+        p.stride_page = args->stride_page;
+        p.stride_kv = args->stride_kv;
+        p.stride_head = args->stride_head;
+        p.stride_tok = args->stride_tok;
+        p.block_table = args->block_table;
+        p.bt_stride = args->block_table_stride;
+        p.page_shift = ctx->L.page_shift;
+        p.scale_log2 = ctx->sm_scale * mac::kLog2e;
+        p.out = args->out;
+        p.out_bf16 = c.out_dtype;
+        p.out_lse = args->out_lse;
+        // one work-group per head; the heads of a KV group are 8 ids apart (same XCD), groups padded to a multiple of 8
+        const int groups = args->batch * c.num_kv_heads;
+        const int grid = ((groups + 7) / 8) * 8 * ctx->L.G;
+        // few heads and a window of several 64-row passes: 1024-thread work-groups scan it in fewer round trips
+        if ((int64_t)args->batch * c.num_q_heads <= 128 && c.window > 256)
+            hipLaunchKernelGGL(mac::hit_kernel<1024>, dim3(grid), dim3(1024), 0, stream, p);
+        else
+            hipLaunchKernelGGL(mac::hit_kernel<256>, dim3(grid), dim3(256), 0, stream, p);
+        HIP_TRY(hipGetLastError());
+        t.done(0);
+    } else {
         mac::MatchParams p;
         p.slot_ids = args->slot_ids;
         p.kv_lens = args->kv_lens;
         p.q_pre = static_cast<const uint16_t*>(args->q_pre);
         p.ring_q = ctx->ring_q;
         p.ring_npos = ctx->ring_npos;
+        p.slices = ctx->m_slices;
         p.part = ctx->m_part;
-        p.st_steps = ctx->stats + 3 * bh + 2 * (int64_t)c.max_batch * c.num_kv_heads;
+        p.head_start = ctx->head_start;
+        p.st_steps = st_steps;
+        p.batch = args->batch;
         p.Hq = c.num_q_heads;
         p.W = c.window;
         p.max_kv_len = c.max_kv_len;
         p.G = ctx->L.G;
-        // window slices: a power of two, enough work-groups to fill the chip at small batch
+        // window slices: a power of two, enough work-groups to fill the chip at small batch; a slice holds at most
+        // kMatchGroupItems (row, head) pairs and at least 16 rows
         int split = 1;
-        if (!c.group_match) {
-            // per head: every slice keeps at least one 64-row pass
-            const int64_t heads = (int64_t)args->batch * c.num_q_heads;
-            while (split * 2 <= 64 && split * heads < 512 && (c.window + split * 2 - 1) / (split * 2) >= 64) split *= 2;
-            p.rows_per_split = (((c.window + split - 1) / split + 63) / 64) * 64;
-        } else {
-            // per KV group: a slice holds at most kMatchGroupItems (row, head) pairs and at least 16 rows
-            const int64_t groups = (int64_t)args->batch * c.num_kv_heads;
-            auto rows_of = [&](int sp) { return (((c.window + sp - 1) / sp + 15) / 16) * 16; };
-            while (split * 2 <= 64 && (rows_of(split) * p.G > mac::kMatchGroupItems ||
-                                       (split * groups < 512 && (c.window + split * 2 - 1) / (split * 2) >= 16)))
-                split *= 2;
-            p.rows_per_split = rows_of(split);
-        }
-        ctx->n_split = split;
+        const int64_t groups = (int64_t)args->batch * c.num_kv_heads;
+        auto rows_of = [&](int sp) { return (((c.window + sp - 1) / sp + 15) / 16) * 16; };
+        while (split * 2 <= 64 && (rows_of(split) * p.G > mac::kMatchGroupItems ||
+                                   (split * groups < 512 && (c.window + split * 2 - 1) / (split * 2) >= 16)))
+            split *= 2;
+        p.rows_per_split = rows_of(split);
         p.n_split = split;
-        p.head_start = split == 1 ? ctx->head_start : nullptr;
         p.mv = match_view(ctx, true);
-        if (!c.group_match) {
-            dim3 grid(c.num_q_heads, args->batch, split), block(mac::kMatchThreads);
-            hipLaunchKernelGGL(mac::match_kernel, grid, block, 0, stream, p);
-        } else {
-            dim3 grid(c.num_kv_heads, args->batch, split), block(mac::kMatchThreads);
-            hipLaunchKernelGGL(mac::match_group_kernel, grid, block, 0, stream, p);
-        }
+        dim3 grid(c.num_kv_heads, args->batch, split), block(mac::kMatchThreads);
+        hipLaunchKernelGGL(mac::match_group_kernel, grid, block, 0, stream, p);
+        HIP_TRY(hipGetLastError());
+        // final reducer: nearest entry of the whole window and the fresh-range start of every head
+        const int heads = args->batch * c.num_q_heads;
+        hipLaunchKernelGGL(mac::match_group_finalize_kernel, dim3((heads + 3) / 4), dim3(256), 0, stream, p);
         HIP_TRY(hipGetLastError());
         t.done(0);
     }
@@ -623,23 +708,25 @@ int mac_attn_stats(mac_attn_ctx* ctx, mac_attn_stats_t* out, int reset) {
     HIP_TRY(hipDeviceSynchronize());          // steps may have been replayed from a graph on any stream
     const mac_attn_config& c = ctx->cfg;
     const int64_t bh = (int64_t)c.max_batch * c.num_q_heads, bg = (int64_t)c.max_batch * c.num_kv_heads;
-    std::vector<unsigned long long> host((size_t)(3 * bh + 2 * bg + 2));
+    std::vector<unsigned long long> host((size_t)(4 * bh + 3 * bg + 2));
     HIP_TRY(hipMemcpy(host.data(), ctx->stats, (size_t)ctx->L.stats_bytes, hipMemcpyDeviceToHost));
     mac_attn_stats_t s;
     std::memset(&s, 0, sizeof(s));
-    s.steps = host[(size_t)(3 * bh + 2 * bg)];
-    s.head_steps = host[(size_t)(3 * bh + 2 * bg + 1)];
+    s.steps = host[(size_t)(4 * bh + 3 * bg)];
+    s.head_steps = host[(size_t)(4 * bh + 3 * bg + 1)];
     for (int64_t i = 0; i < bh; ++i) {          // fixed order: the double sum is reproducible
         s.hits += host[(size_t)i];
         s.sum_gap += host[(size_t)(bh + i)];
         double f;
         std::memcpy(&f, &host[(size_t)(2 * bh + i)], 8);
         s.sum_skip_frac += f;
+        s.kv_tokens_fused += host[(size_t)(3 * bh + i)];
     }
     s.misses = s.head_steps - s.hits;
     for (int64_t i = 0; i < bg; ++i) {
-        s.kv_tokens_read += host[(size_t)(3 * bh + i)];
-        s.kv_tokens_full += host[(size_t)(3 * bh + bg + i)];
+        s.kv_tokens_read += host[(size_t)(4 * bh + i)];
+        s.kv_tokens_full += host[(size_t)(4 * bh + bg + i)];
+        s.kv_tokens_split += host[(size_t)(4 * bh + 2 * bg + i)];
     }
     *out = s;
     if (reset) {
@@ -659,7 +746,8 @@ int mac_attn_reset(mac_attn_ctx* ctx, const int32_t* slot_ids, int32_t n) {
     } else {
         for (int i = 0; i < n; ++i)
             if (slot_ids[i] < 0 || slot_ids[i] >= ctx->cfg.max_slots) return MAC_ATTN_ERR_INVALID_ARG;
-        for (int i = 0; i < n; ++i) HIP_TRY(hipMemset(ctx->ring_npos + (int64_t)slot_ids[i] * W, 0, (size_t)W * 4));
+        const int64_t per_slot = (int64_t)ctx->cfg.num_q_heads * W;
+        for (int i = 0; i < n; ++i) HIP_TRY(hipMemset(ctx->ring_npos + (int64_t)slot_ids[i] * per_slot, 0, (size_t)per_slot * 4));
     }
     HIP_TRY(hipDeviceSynchronize());
     return MAC_ATTN_OK;
@@ -677,7 +765,7 @@ int mac_attn_ring_peek(mac_attn_ctx* ctx, int32_t slot, int32_t j, int32_t h, ui
     if (q_pre) HIP_TRY(hipMemcpy(q_pre, ctx->ring_q + e * mac::kHeadDim, mac::kHeadDim * 2, hipMemcpyDeviceToHost));
     if (summary) HIP_TRY(hipMemcpy(summary, ctx->ring_O + e * mac::kHeadDim, mac::kHeadDim * 4, hipMemcpyDeviceToHost));
     if (lse) HIP_TRY(hipMemcpy(lse, ctx->ring_lse + e, 4, hipMemcpyDeviceToHost));
-    if (n_p) HIP_TRY(hipMemcpy(n_p, ctx->ring_npos + (int64_t)slot * c.window + j, 4, hipMemcpyDeviceToHost));
+    if (n_p) HIP_TRY(hipMemcpy(n_p, ctx->ring_npos + e, 4, hipMemcpyDeviceToHost));
     return MAC_ATTN_OK;
 }
 

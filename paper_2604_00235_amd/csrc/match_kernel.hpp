@@ -1,30 +1,23 @@
-// Match: pre-RoPE squared-L2 nearest neighbour over the query ring, argmin and threshold (gfx950, wave64).
+// Pre-RoPE squared-L2 distances over the query ring: the arithmetic shared by the matchers, and the matcher that
+// picks one reuse point per KV group (gfx950, wave64).  The per-head matcher of the paper lives in hit_kernel.hpp.
 //
 // Paper: Eq. (accept) and Sec. 3.2.3 (single streaming pass over the last W queries), Sec. 3.5 step 1,
 // Sec. 4.2 "K1" (at most one reuse point per (request, head), then the threshold).
 // For request b (ring set slot_ids[b]) and query head h, over the ring entries created at lengths
 // n_p in [max(1, n - W), n - 1]:  d2_j = sum_i (q_i - ring_j,i)^2,  j* = argmin (ties -> larger n_p),
 // hit iff d2_j* < T^2.  On a hit the head's fresh range starts at s_h = max(0, n_p - B), else at 0.
-// This kernel produces the nearest entry of each window slice; match_decide_wave() finishes the argmin and applies
-// the threshold.
 //
 // Arithmetic.  The decision has to agree with an fp64 evaluation of the exact bf16 inputs, so each
 // difference is formed in fp64 (exact) and squared/accumulated with fp64 FMAs; the result is within a few
 // ulp(fp64) of the true real value, so decisions differ from any other fp64 evaluation only for candidates
-// that tie to ~1e-15 relative.  v_fma_f64 is full rate on this chip and the kernel stays bandwidth-bound.
+// that tie to ~1e-15 relative.  v_fma_f64 is full rate on this chip and the kernels stay bandwidth-bound.
 //
-// Mapping.  One work-group (256 threads = 4 waves, 64 ring rows per pass) per (head, request, window slice).
-// The host cuts the window into slices so that a small batch still yields ~512 work-groups (a single group
-// scanning a 1024-entry window needs 16 dependent passes, ~17 us; 16 slices take one pass each); the slices'
-// results are reduced and thresholded by the consumers (match_decide_wave).  Measured at 134 MB of ring (batch 32 x
-// 64 heads x 256 entries) 256-thread groups stream ~1.9x faster than 1024-thread ones.
-// The head's window is contiguous in the ring
-// ([slot][head][entry][d]).  A quad of 4 lanes owns one 256-byte row per iteration, lane `sub` reading the
-// 16-byte chunks sub, sub+4, sub+8, sub+12, so each load instruction of a wave fetches 16 rows x 64
-// contiguous bytes.  Rows are loaded without waiting for their n_p tag (the ring memory always exists; an
-// entry outside the window is simply discarded), which removes one dependent memory round trip.  The 4
-// partial sums are combined with two cross-lane adds, the per-lane running (d2, n_p) minimum with a
-// shuffle butterfly and one LDS exchange between the waves.
+// Access pattern.  A head's window is contiguous in the ring ([slot][head][entry][d]).  A quad of 4 lanes owns one
+// 256-byte row per pass, lane `sub` reading the 16-byte chunks sub, sub+4, sub+8, sub+12, so each load instruction
+// of a wave fetches 16 rows x 64 contiguous bytes.  Rows are loaded without waiting for their n_p tag (the ring
+// memory always exists; an entry outside the window is simply discarded), which removes one dependent memory
+// round trip.  The 4 partial sums of a row are combined with two cross-lane adds, the per-lane running (d2, n_p)
+// minimum with a shuffle butterfly and one exchange through shared memory between the waves.
 #pragma once
 #include "common.hpp"
 
@@ -35,18 +28,16 @@ struct MatchParams {
     const int32_t* kv_lens;      // [batch]
     const uint16_t* q_pre;       // [batch, Hq, 128] bf16
     const uint16_t* ring_q;      // [slots, Hq, W, 128] bf16
-    const int32_t* ring_npos;    // [slots, W]; 0 = empty entry
-    MatchPartial* part;          // [batch*Hq, n_split] nearest entry of each window slice
+    const int32_t* ring_npos;    // [slots, Hq, W]; 0 = empty entry (the heads of a request carry the same tags)
+    MatchPartial* slices;        // [batch*Hq, n_split] nearest entry of each window slice (group matcher)
+    MatchPartial* part;          // [batch*Hq] nearest entry of the whole window (written by the finalize kernel)
+    int32_t* head_start;         // [batch*Hq] start of each head's fresh range (written by the finalize kernel)
     unsigned long long* st_steps;   // [2]: decode steps, head-steps (device-side so that graph replays count too)
-    int32_t Hq, W, max_kv_len;
-    int32_t n_split;             // window slices per head = gridDim.z
-    int32_t rows_per_split;      // multiple of 64 (match_kernel) / of 16 with rows_per_split * G <= 4096 (group kernel)
+    int32_t batch, Hq, W, max_kv_len;
+    int32_t n_split;             // window slices per group = gridDim.z of the group matcher (power of two <= 64)
+    int32_t rows_per_split;      // multiple of 16 with rows_per_split * G <= kMatchGroupItems
     int32_t G;                   // heads per KV group
-    // With a single window slice the kernel knows each head's final decision: it then also stores the start of the
-    // head's fresh range, so that an attention work-group can tell from a few scalar loads (no cross-lane
-    // reduction of the match results) whether it has anything to do.  nullptr when n_split > 1.
-    int32_t* head_start;         // [batch*Hq]
-    MatchView mv;                // threshold, band and distance cap of the acceptance rule (part / n_split unused)
+    MatchView mv;                // threshold, band and distance cap of the acceptance rule (part unused)
 };
 
 // start of the fresh range of a head whose nearest window entry is (d2, np): max(0, np - B) on a hit, else 0;
@@ -92,87 +83,11 @@ __device__ __forceinline__ void load_query_f64(const uint16_t* row_plus_8sub, do
 constexpr int kMatchThreads = 256;
 constexpr int kMatchRowsPerPass = kMatchThreads / 4;
 
-__global__ __launch_bounds__(kMatchThreads) void match_kernel(const MatchParams p) {
-    const int h = blockIdx.x, b = blockIdx.y, sp = blockIdx.z;
-    const int tid = threadIdx.x, quad = tid >> 2, sub = tid & 3;
-    const int bh = b * p.Hq + h;
-    const int n = clampi(p.kv_lens[b], 0, p.max_kv_len);
-    const int64_t slot = p.slot_ids[b];
-    const int W = p.W;
-
-    // this lane's 32 query elements (chunks sub + 4i), widened once
-    double q[32];
-    load_query_f64(p.q_pre + (int64_t)bh * kHeadDim + 8 * sub, q);
-    const uint16_t* ring = p.ring_q + ((slot * p.Hq + h) * W) * (int64_t)kHeadDim + 8 * sub;
-    const int32_t* npos = p.ring_npos + slot * W;
-    const int np_lo = max(1, n - W), np_hi = n - 1;
-
-    double best_d2 = INFINITY;
-    int best_np = -1, best_j = -1;
-    const int j_begin = sp * p.rows_per_split, j_end = min(W, j_begin + p.rows_per_split);
-    // Several passes of 64 rows per trip, all their row loads issued before the arithmetic, so that a work-group
-    // keeps more bytes in flight (the kernel is bound by latency x occupancy, not by the fp64 units).
-    auto row_of = [&](int j0, int& j, int& np, u32x4 (&v)[4]) {
-        j = j0 + quad;
-        const int jc = j < W ? j : W - 1;                      // keep the speculative loads inside the ring
-        np = npos[jc];
-        const uint16_t* rp = ring + (int64_t)jc * kHeadDim;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) v[i] = *reinterpret_cast<const u32x4*>(rp + 32 * i);
-    };
-    auto take = [&](int j, int np, const u32x4 (&v)[4]) {
-        const bool valid = j < j_end && np >= np_lo && np <= np_hi;
-        double d2 = lane_sq_dist(q, v);
-        d2 += __shfl_xor(d2, 1);
-        d2 += __shfl_xor(d2, 2);
-        if (valid && better(d2, np, best_d2, best_np)) { best_d2 = d2; best_np = np; best_j = j; }
-    };
-    constexpr int kPassesInFlight = 2;
-    int j0 = j_begin;
-    for (; j0 + (kPassesInFlight - 1) * kMatchRowsPerPass < j_end; j0 += kPassesInFlight * kMatchRowsPerPass) {
-        int jj[kPassesInFlight], nn[kPassesInFlight];
-        u32x4 vv[kPassesInFlight][4];
-#pragma unroll
-        for (int t = 0; t < kPassesInFlight; ++t) row_of(j0 + t * kMatchRowsPerPass, jj[t], nn[t], vv[t]);
-#pragma unroll
-        for (int t = 0; t < kPassesInFlight; ++t) take(jj[t], nn[t], vv[t]);
-    }
-    for (; j0 < j_end; j0 += kMatchRowsPerPass) {
-        int ja, npa;
-        u32x4 va[4];
-        row_of(j0, ja, npa, va);
-        take(ja, npa, va);
-    }
-    // wave butterfly over the 16 quads (all 4 lanes of a quad hold the same triple)
-#pragma unroll
-    for (int off = 4; off < 64; off <<= 1) {
-        const double od2 = __shfl_xor(best_d2, off);
-        const int onp = __shfl_xor(best_np, off);
-        const int oj = __shfl_xor(best_j, off);
-        if (better(od2, onp, best_d2, best_np)) { best_d2 = od2; best_np = onp; best_j = oj; }
-    }
-    constexpr int kWaves = kMatchThreads / 64;
-    __shared__ double s_d2[kWaves];
-    __shared__ int s_np[kWaves], s_j[kWaves];
-    if ((tid & 63) == 0) { s_d2[tid >> 6] = best_d2; s_np[tid >> 6] = best_np; s_j[tid >> 6] = best_j; }
-    __syncthreads();
-    if (tid == 0) {
-        if (h == 0 && b == 0 && sp == 0) {
-            atomicAdd(&p.st_steps[0], 1ull);
-            atomicAdd(&p.st_steps[1], (unsigned long long)gridDim.x * gridDim.y);
-        }
-        for (int w = 1; w < kWaves; ++w)
-            if (better(s_d2[w], s_np[w], best_d2, best_np)) { best_d2 = s_d2[w]; best_np = s_np[w]; best_j = s_j[w]; }
-        p.part[(int64_t)bh * p.n_split + sp] = MatchPartial{best_d2, best_np, best_j};
-        if (p.head_start != nullptr) p.head_start[bh] = head_start(p.mv, best_d2, best_np, n);
-    }
-}
-
 // One reuse point per KV group: candidates are ranked by D2_j = sum over the group's heads of d2_{h,j} (the squared
 // distance of the group's concatenated queries), summed in head order.  One work-group per (KV group, request,
 // window slice).  The (row, head) pairs of the slice are dealt to the 64 quads, so all ring loads are independent;
 // the per-pair distances meet in shared memory, then thread r sums row r over the heads and the argmin proceeds as
-// in match_kernel.  The slice result is written for every head of the group, so the consumers need no change.
+// in the per-head matcher.  The slice result is written for every head of the group, so the consumers need no change.
 constexpr int kMatchGroupItems = 4096;   // (row, head) pairs per work-group: 32 KB of shared memory
 
 __global__ __launch_bounds__(kMatchThreads) void match_group_kernel(const MatchParams p) {
@@ -181,14 +96,14 @@ __global__ __launch_bounds__(kMatchThreads) void match_group_kernel(const MatchP
     const int G = p.G, W = p.W;
     const int n = clampi(p.kv_lens[b], 0, p.max_kv_len);
     const int64_t slot = p.slot_ids[b];
-    const int32_t* npos = p.ring_npos + slot * W;
+    const int32_t* npos = p.ring_npos + (slot * p.Hq + g * G) * W;       // tags of the group's first head
     const int np_lo = max(1, n - W), np_hi = n - 1;
     const int j_begin = sp * p.rows_per_split;
     const int rows = max(0, min(W, j_begin + p.rows_per_split) - j_begin);
     const int items = rows * G;                                  // <= kMatchGroupItems (host)
     __shared__ double s_pair[kMatchGroupItems];
 
-    // two pairs per quad and trip, their loads issued before the arithmetic (as in match_kernel)
+    // two pairs per quad and trip, their loads issued before the arithmetic (as in the per-head matcher)
     for (int i0 = 0; i0 < items; i0 += 2 * kMatchRowsPerPass) {
         u32x4 qv[2][4], v[2][4];
 #pragma unroll
@@ -252,8 +167,23 @@ __global__ __launch_bounds__(kMatchThreads) void match_group_kernel(const MatchP
         best_d2 = s_d2[0]; best_np = s_np[0]; best_j = s_j[0];
         for (int w = 1; w < kWaves; ++w)
             if (better(s_d2[w], s_np[w], best_d2, best_np)) { best_d2 = s_d2[w]; best_np = s_np[w]; best_j = s_j[w]; }
-        p.part[((int64_t)b * p.Hq + g * G + tid) * p.n_split + sp] = MatchPartial{best_d2, best_np, best_j};
-        if (p.head_start != nullptr) p.head_start[b * p.Hq + g * G + tid] = head_start(p.mv, best_d2, best_np, n);
+        p.slices[((int64_t)b * p.Hq + g * G + tid) * p.n_split + sp] = MatchPartial{best_d2, best_np, best_j};
+    }
+}
+
+// Final reducer of the group matcher: one wave per head combines the head's slice results into the nearest entry of
+// the whole window and stores it with the start of the head's fresh range, the form the attention and merge kernels
+// read (the per-head matcher writes the same two records itself).
+__global__ __launch_bounds__(256) void match_group_finalize_kernel(const MatchParams p) {
+    const int lane = threadIdx.x & 63;
+    const int bh = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (bh >= p.batch * p.Hq) return;
+    const int b = bh / p.Hq;
+    const int n = clampi(p.kv_lens[b], 0, p.max_kv_len);
+    const MatchPartial c = match_nearest_wave(p.slices, p.n_split, bh, 1, lane);
+    if (lane == 0) {
+        p.part[bh] = c;
+        p.head_start[bh] = head_start(p.mv, c.d2, c.np, n);
     }
 }
 

@@ -12,6 +12,9 @@
 // pre-RoPE query, the rectified summary row and its ln-LSE; the entry's n_p tag is set to n.  It runs after the
 // merge of the same head because the overwritten entry (n_p = n - W) is still a candidate of this step.
 //
+// A head whose whole step the per-head matcher has finished (hit with a short fresh range, see hit_kernel.hpp) is
+// flagged in head_start[]: its work-group leaves at once.
+//
 // Both steps exist as kernels of their own (merge_kernel, writeback_kernel: one work-group per (head, request))
 // and fused in merge_writeback_kernel (one launch less per step; the default).  Folding them further into the
 // attention kernel ("last work-group of a group merges") was tried and dropped: the device-scope release fence
@@ -30,7 +33,8 @@ struct WritebackParams {
     uint16_t* ring_q;            // [slots, Hq, W, 128]
     float* ring_O;               // [slots, Hq, W, 128]
     float* ring_lse;             // [slots, Hq, W]
-    int32_t* ring_npos;          // [slots, W]
+    int32_t* ring_npos;          // [slots, Hq, W]: every head carries its own n_p tags
+    const int32_t* head_start;   // [batch*Hq] or null: heads flagged kHeadDone were appended by the matcher already
     int32_t Hq, W, max_kv_len;
 };
 
@@ -38,6 +42,8 @@ struct MergeParams {
     const int32_t* kv_lens;
     const int32_t* slot_ids;     // null for full decode
     MatchView mv;                // per-head match results; part == nullptr for full decode
+    const int32_t* head_start;   // [batch*Hq] or null: heads flagged kHeadDone are finished, their work-group leaves
+    int32_t emit_decision;       // 1: this kernel reports the decisions (caller outputs, counters); 0: the matcher did
     int32_t* out_match_pos;      // optional caller outputs [batch*Hq] (MAC mode)
     double* out_match_d2;
     unsigned long long* st_hits; // per (b, h) accumulators, touched only by that (b, h)'s work-group; null for full decode
@@ -52,7 +58,10 @@ struct MergeParams {
     float* out_lse;              // optional [batch, Hq]
     float* rect_O;               // staging for a separate write-back kernel [batch*Hq, 128]; may be null
     float* rect_lse;             // [batch*Hq]
-    int32_t Hq, G, W, band, chunk, n_mid_slots, n_slots, max_kv_len;
+    int32_t Hq, G, W, band, n_mid_slots, n_slots, max_kv_len;
+    int32_t chunk_fixed;         // > 0: tokens per work item of the attention kernel, fixed by the caller;
+    const int32_t* step_chunk;   // 0: read here what the attention kernel chose for this step
+    int32_t* work_counter;       // the attention kernel's work-item counter: cleared here for the next launch
 };
 
 // 256 threads per (request, head).  Thread (c = tid/32, q = tid%32) accumulates the partials
@@ -95,7 +104,7 @@ __device__ __forceinline__ void writeback_head(const WritebackParams& p, int b, 
     p.ring_O[e * kHeadDim + d] = rect_o;
     if (d == 0) {
         p.ring_lse[e] = rect_l;
-        if (h == 0) p.ring_npos[slot * p.W + j] = n;
+        p.ring_npos[e] = n;
     }
 }
 
@@ -106,14 +115,13 @@ __device__ __forceinline__ void merge_head(const MergeParams& p, const Writeback
     const int tid = threadIdx.x;
     const int c = tid >> 5, q = tid & 31;
     const int bh = b * p.Hq + h;
+    if (bh == 0 && threadIdx.x == 0 && p.work_counter != nullptr) *p.work_counter = 0;
+    if (p.head_start != nullptr && (p.head_start[bh] & kHeadDone)) return;     // the whole work-group: before any barrier
     const int n = clampi(p.kv_lens[b], 0, p.max_kv_len);
     const int nb = n - p.band > 0 ? n - p.band : 0;
-    const int C = p.chunk;
-    MatchDecision md = match_decide_wave(p.mv, bh, 1, tid & 63, n);           // every wave decides this head itself;
-    md.d2 = __shfl(md.d2, 0);                                              // lane 0 holds it, the rest take it over
-    md.np = __shfl(md.np, 0);
-    md.j = __shfl(md.j, 0);
-    md.start = __shfl(md.start, 0);
+    const int C = p.chunk_fixed > 0 ? p.chunk_fixed : *p.step_chunk;
+    MatchDecision md{INFINITY, -1, -1, 0};
+    if (p.mv.part != nullptr) md = decide(p.mv, p.mv.part[bh], n);
     const int s = clampi(md.start, 0, nb);
     const int64_t pbase = (int64_t)bh * p.n_slots;
 
@@ -197,7 +205,7 @@ __device__ __forceinline__ void merge_head(const MergeParams& p, const Writeback
     }
 
     // The decision, for the caller and the counters (acceptance, reuse gap, skipped-prefix fraction).
-    if (p.mv.part != nullptr && tid < 64) {
+    if (p.mv.part != nullptr && p.emit_decision && tid < 64) {
         if (tid == 0) {
             if (p.out_match_pos) p.out_match_pos[bh] = md.np;
             if (p.out_match_d2) p.out_match_d2[bh] = md.d2;
@@ -226,6 +234,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_writeback_kernel(const Me
 __global__ __launch_bounds__(128) void writeback_kernel(const WritebackParams p) {
     const int h = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
     const int bh = b * p.Hq + h;
+    if (p.head_start != nullptr && (p.head_start[bh] & kHeadDone)) return;
     writeback_head(p, b, h, d, p.rect_O[(int64_t)bh * kHeadDim + d], p.rect_lse[bh]);
 }
 

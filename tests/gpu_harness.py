@@ -44,14 +44,14 @@ class DeviceRun:
 
     def __init__(self, cfg: WorkloadConfig, wl: Workload, chunk_tokens: int = 0, strides=None, kv_pages=None,
                  max_kv_len=None, fuse_epilogue: bool = True, max_gap: int = 0, group_match: bool = False,
-                 out_bf16: bool = False):
+                 out_bf16: bool = False, fused_hit_span: int = 0):
         self.cfg, self.wl = cfg, wl
         dev = wl.device
         self.mac = mb.MacAttention(num_q_heads=cfg.num_q_heads, num_kv_heads=cfg.num_kv_heads, window=cfg.window,
                                    band=cfg.band, threshold=cfg.threshold, max_kv_len=max_kv_len or cfg.max_kv_len,
                                    max_slots=cfg.batch, page_size=cfg.page_size, chunk_tokens=chunk_tokens,
                                    fuse_epilogue=fuse_epilogue, max_gap=max_gap, group_match=group_match,
-                                   out_bf16=out_bf16)
+                                   out_bf16=out_bf16, fused_hit_span=fused_hit_span)
         self.kv_pages = wl.kv_pages if kv_pages is None else kv_pages
         self.strides = wl.strides if strides is None else strides
         B, Hq, d = cfg.batch, cfg.num_q_heads, cfg.head_dim
@@ -103,14 +103,17 @@ class DeviceRun:
 
 
 def run_parity(cfg: WorkloadConfig, chunk_tokens: int = 0, check_full: bool = True, check_ring_every: int = 4,
-               label: str = "", fuse_epilogue: bool = True, max_gap: int = 0, group_match: bool = False):
+               label: str = "", fuse_epilogue: bool = True, max_gap: int = 0, group_match: bool = False,
+               fused_hit_span: int = 0):
     """All steps of `cfg` on both sides; returns summary dict.  Oracle inputs are host copies of the same bits."""
     say(f"[parity] {label or cfg.name}: batch={cfg.batch} Hq/Hkv={cfg.num_q_heads}/{cfg.num_kv_heads} "
         f"context={cfg.context} steps={cfg.steps} W={cfg.window} B={cfg.band} T={cfg.threshold:.4g} "
         f"page={cfg.page_size} chunk={chunk_tokens} fused={fuse_epilogue} max_gap={max_gap} group_match={group_match} "
+        f"fused_hit_span={fused_hit_span} "
         f"seed={cfg.seed}")
     wl = Workload(cfg, device="cuda:0")
-    run = DeviceRun(cfg, wl, chunk_tokens, fuse_epilogue=fuse_epilogue, max_gap=max_gap, group_match=group_match)
+    run = DeviceRun(cfg, wl, chunk_tokens, fuse_epilogue=fuse_epilogue, max_gap=max_gap, group_match=group_match,
+                    fused_hit_span=fused_hit_span)
     orc = make_oracle(cfg, wl, max_gap=max_gap, group_match=group_match)
     kvp = bf16_bits(wl.kv_pages)
     bt = wl.block_table.cpu().numpy()
@@ -151,7 +154,13 @@ def run_parity(cfg: WorkloadConfig, chunk_tokens: int = 0, check_full: bool = Tr
     for k in ("steps", "head_steps", "hits", "misses", "sum_gap", "kv_tokens_read", "kv_tokens_full"):
         assert gst[k] == ost[k], f"stats.{k}: gpu {gst[k]} oracle {ost[k]}"
     assert abs(gst["sum_skip_frac"] - ost["sum_skip_frac"]) <= 1e-9 * max(1.0, ost["sum_skip_frac"])
+    # where the work went: heads finished by the matcher read their own range; the split-K kernel never streams more
+    # than the method's per-group figure, and exactly that when the matcher finishes nothing
+    assert gst["kv_tokens_split"] <= gst["kv_tokens_read"]
+    if group_match or fused_hit_span < 0:
+        assert gst["kv_tokens_fused"] == 0 and gst["kv_tokens_split"] == gst["kv_tokens_read"]
     run.mac.close()
     say(f"[parity] ok: hits {hits}/{ost['head_steps']} worst max-abs {worst_abs:.2e} rel-L2 {worst_rel:.2e} "
         f"kv read {ost['kv_tokens_read']}/{ost['kv_tokens_full']}")
-    return {"hits": hits, "head_steps": ost["head_steps"], "max_abs": worst_abs, "rel_l2": worst_rel}
+    return {"hits": hits, "head_steps": ost["head_steps"], "max_abs": worst_abs, "rel_l2": worst_rel,
+            "kv_tokens_fused": gst["kv_tokens_fused"], "kv_tokens_split": gst["kv_tokens_split"]}

@@ -39,8 +39,8 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_struct_layouts_match_header():
     """Field order/size of the ctypes mirrors: int32/float fields packed as in the C structs."""
-    assert C.sizeof(mb.mac_attn_config) == 17 * 4
-    assert C.sizeof(mb.mac_attn_stats_t) == 8 * 8
+    assert C.sizeof(mb.mac_attn_config) == 18 * 4
+    assert C.sizeof(mb.mac_attn_stats_t) == 10 * 8
     a = mb.mac_attn_step_args
     assert a.stride_page.offset % 8 == 0 and a.block_table_stride.offset == a.block_table.offset + 8
     assert C.sizeof(a) == 8 + 5 * 8 + 4 * 8 + 8 + 8 + 4 * 8
@@ -68,14 +68,22 @@ def test_ring_entry_bytes_and_paper_overhead(lib):
 def test_device_bytes_accounts_rings_and_workspace(lib):
     cfg = _cfg()
     total = mb.mac_attn_device_bytes(cfg)
-    rings = 4 * 32 * 256 * 772 + 4 * 256 * 4
+    rings = 4 * 32 * 256 * (772 + 4)                  # entries x (query + summary + ln-LSE + n_p tag)
     assert total > rings
     n_slots = (131200 + 1023) // 1024 + (128 + 1023) // 1024 + 1
     work = 4 * 32 * n_slots * (128 + 1) * 4
-    # the rest is small: match slice results (64 x 16 B per head), write-back staging, counters
-    # and one word per head (+ 32 of padding) for the fresh-range start the match kernel stores
-    # each of the 10 buffers lies between two 256-byte guard zones
-    assert total - rings - work == 4 * 32 * (64 * 16 + 129 * 4 + 3 * 8 + 4) + 32 * 4 + 4 * 8 * 2 * 8 + 2 * 8 + 10 * 512
+    # the rest is small: the nearest entry per head (16 B; the group matcher's 64 slice results per head only with
+    # group_match), write-back staging, counters (4 per head, 3 per KV group, 2 per context), one word per head
+    # (+ 32 of padding) for the fresh-range start the matcher stores, 256 B for the attention kernel's plan;
+    # each of the 12 buffers lies between two 256-byte guard zones
+    assert total - rings - work == 4 * 32 * (16 + 129 * 4 + 4 * 8 + 4) + 16 + 32 * 4 + 4 * 8 * 3 * 8 + 2 * 8 + 256 + 12 * 512
+    grouped = mb.mac_attn_device_bytes(_cfg(group_match=1))
+    assert grouped - total == 4 * 32 * 64 * 16 - 16
+    # chunk_tokens = 0: the partial slots are laid out for the smallest work item the kernel may choose (256 tokens
+    # at 4 heads per KV head)
+    dyn = mb.mac_attn_device_bytes(_cfg(chunk_tokens=0))
+    n_slots_dyn = (131200 + 255) // 256 + (128 + 255) // 256 + 1
+    assert dyn - total == 4 * 32 * (n_slots_dyn - n_slots) * (128 + 1) * 4
 
 
 @pytest.mark.parametrize("kw,code", [
@@ -84,6 +92,7 @@ def test_device_bytes_accounts_rings_and_workspace(lib):
     (dict(page_size=8), mb.MAC_ATTN_ERR_UNSUPPORTED),
     (dict(num_q_heads=66, num_kv_heads=1), mb.MAC_ATTN_ERR_UNSUPPORTED),
     (dict(window=8192), mb.MAC_ATTN_ERR_UNSUPPORTED),
+    (dict(max_slots=1024, max_batch=1024), mb.MAC_ATTN_ERR_UNSUPPORTED),     # 8192 KV groups: beyond the planner's list
     (dict(num_q_heads=30), mb.MAC_ATTN_ERR_INVALID_ARG),
     (dict(window=0), mb.MAC_ATTN_ERR_INVALID_ARG),
     (dict(band=-1), mb.MAC_ATTN_ERR_INVALID_ARG),
@@ -97,6 +106,8 @@ def test_device_bytes_accounts_rings_and_workspace(lib):
     (dict(max_gap=-1), mb.MAC_ATTN_ERR_INVALID_ARG),
     (dict(group_match=2), mb.MAC_ATTN_ERR_INVALID_ARG),
     (dict(out_dtype=3), mb.MAC_ATTN_ERR_INVALID_ARG),
+    (dict(fused_hit_span=-2), mb.MAC_ATTN_ERR_INVALID_ARG),
+    (dict(fused_hit_span=4096), mb.MAC_ATTN_ERR_INVALID_ARG),
 ])
 def test_bad_configs_are_rejected_before_any_gpu_call(lib, kw, code):
     cfg = _cfg(**kw)

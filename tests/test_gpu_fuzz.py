@@ -37,6 +37,8 @@ def _draw(seed: int):
     variant = dict(max_gap=int(rng.choice([0, 0, 1, 3, 20])), group_match=bool(rng.integers(0, 3) == 0))
     chunk = int(rng.choice([0, 32, 64, 96, 256, 1024]))
     fused = bool(rng.integers(0, 4) != 0)
+    # largest fresh range the matcher finishes itself: default, never, and values that split the hits of one run
+    variant["fused_hit_span"] = int(rng.choice([0, -1, 9, 40, 100, 2048]))
     return WorkloadConfig(**kw), variant, chunk, fused
 
 

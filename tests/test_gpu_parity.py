@@ -23,15 +23,20 @@ def test_c1_tiny_config_exact():
     assert r["hits"] > 0
 
 
-@pytest.mark.parametrize("chunk,fused", [(0, True), (256, True), (256, False)])
-def test_llama_shape_reduced_mixed_hits(chunk, fused):
+@pytest.mark.parametrize("chunk,fused,span", [(0, True, 0), (256, True, -1), (256, False, 0), (256, False, -1),
+                                              (128, True, 66)])
+def test_llama_shape_reduced_mixed_hits(chunk, fused, span):
     """C2 geometry (32/8 heads) at a reduced, ragged context; threshold near the lag-1 distance so that hits
     and misses mix inside KV groups (per-head start masks, group-level spans)."""
     from tests.gpu_harness import run_parity
     cfg = scaled(CONFIGS["C2"], name="C2r", batch=3, context=2500, steps=24, window=16, band=64,
                  threshold=2.8, ragged=37)
-    r = run_parity(cfg, chunk_tokens=chunk, fuse_epilogue=fused)
+    r = run_parity(cfg, chunk_tokens=chunk, fuse_epilogue=fused, fused_hit_span=span)
     assert 0 < r["hits"] < r["head_steps"]
+    if span >= 0:
+        assert r["kv_tokens_fused"] > 0           # hits at gap 1: ranges of 65 tokens, finished by the matcher
+    if span == 66:
+        assert r["kv_tokens_fused"] < r["hits"] * 66      # ... and some longer ones left to the split-K path
 
 
 def test_mqa_threshold_zero_equals_full_attention():
@@ -42,22 +47,22 @@ def test_mqa_threshold_zero_equals_full_attention():
     assert r["hits"] == 0
 
 
-@pytest.mark.parametrize("fused", [True, False])
-def test_mqa_matched_threshold(fused):
+@pytest.mark.parametrize("fused,span", [(True, 0), (False, 0), (True, -1)])
+def test_mqa_matched_threshold(fused, span):
     """C4 run B (MQA, G=32) at reduced context with the config's threshold: all hits after the first step."""
     from tests.gpu_harness import run_parity
     cfg = scaled(CONFIGS["C4_hit"], name="C4b", batch=2, context=1400, steps=20, window=8, ragged=3)
-    r = run_parity(cfg, fuse_epilogue=fused)
+    r = run_parity(cfg, fuse_epilogue=fused, fused_hit_span=span)
     assert r["hits"] == r["head_steps"] - cfg.batch * cfg.num_q_heads
 
 
-@pytest.mark.parametrize("fused", [True, False])
-def test_continuous_generation_regime_shifts_and_ring_wrap(fused):
+@pytest.mark.parametrize("fused,span", [(True, 0), (False, 0), (True, -1), (False, 70)])
+def test_continuous_generation_regime_shifts_and_ring_wrap(fused, span):
     """C5 geometry (64/8 heads, G=8), regime shift every 8 steps, W=8 so the ring wraps 5 times."""
     from tests.gpu_harness import run_parity
     cfg = scaled(CONFIGS["C5"], name="C5r", batch=2, context=700, steps=40, window=8, band=64,
                  regime_shift_every=8)
-    r = run_parity(cfg, chunk_tokens=128, check_ring_every=1, fuse_epilogue=fused)
+    r = run_parity(cfg, chunk_tokens=128, check_ring_every=1, fuse_epilogue=fused, fused_hit_span=span)
     assert 0 < r["hits"] < r["head_steps"]
 
 
@@ -74,8 +79,8 @@ def test_edge_cases(kw):
     base = dict(name="edge", batch=2, num_q_heads=4, num_kv_heads=2, context=64, steps=8, window=4, band=8,
                 threshold=T_DEFAULT, rho=0.97, seed=5)
     base.update(kw)
-    for fused in (True, False):
-        run_parity(WorkloadConfig(**base), chunk_tokens=32, check_ring_every=1, fuse_epilogue=fused)
+    for fused, span in ((True, 0), (False, 0), (True, -1)):
+        run_parity(WorkloadConfig(**base), chunk_tokens=32, check_ring_every=1, fuse_epilogue=fused, fused_hit_span=span)
 
 
 def test_strided_kv_layout_and_group_sizes():
@@ -138,9 +143,10 @@ def test_error_paths_on_device():
     mac.close()
 
 
+@pytest.mark.parametrize("span", [0, -1, 100])
 @pytest.mark.parametrize("hq,hkv,window,batch", [(32, 8, 1024, 1), (16, 2, 1024, 1), (32, 1, 256, 2), (8, 2, 200, 3),
                                                  (8, 2, 4096, 1)])
-def test_recurring_queries_large_window_split_match(hq, hkv, window, batch):
+def test_recurring_queries_large_window_split_match(hq, hkv, window, batch, span):
     """Second query model (reuse gaps of tens to hundreds of tokens with skew inside a KV group, whole-group misses):
     exercises large windows, where the matcher cuts the window into slices (16 slices at W=1024 and batch 1) and
     the consumers finish the argmin, including groups that need more than one wave pass (G x slices > 64) and a
@@ -149,8 +155,10 @@ def test_recurring_queries_large_window_split_match(hq, hkv, window, batch):
     cfg = WorkloadConfig(name=f"recur{hq}_{hkv}_{window}", batch=batch, num_q_heads=hq, num_kv_heads=hkv, context=1500,
                          steps=150, window=window, band=48, threshold=T_DEFAULT, rho=0.0, seed=21, period=40,
                          period_std=4.0, query_noise=0.1, jump_prob=0.05, ragged=11 if batch > 1 else 0)
-    r = run_parity(cfg, chunk_tokens=256, check_full=False, check_ring_every=16)
+    r = run_parity(cfg, chunk_tokens=256, check_full=False, check_ring_every=16, fused_hit_span=span)
     assert 0.3 * r["head_steps"] < r["hits"] < r["head_steps"]
+    if span == 100:                                # reuse gaps of 36..44 + band 48: some ranges fit, wrapped ones do not
+        assert 0 < r["kv_tokens_fused"]
 
 
 # ----------------------------------------------------------------------------- variants of the match rule
