@@ -66,8 +66,6 @@ struct AttnParams {
     int32_t max_kv_len;
     float scale_log2;            // sm_scale * log2(e)
     int32_t* step_chunk;         // [1] tokens per work item of this launch, for the merge kernel (chunk_fixed == 0)
-    int32_t* work_counter;       // [1] work items handed out beyond the first gridDim.x; zero at launch (the merge
-                                 // kernel that follows every launch clears it)
     unsigned long long* st_read; // [batch*Hkv] KV tokens the method streams per group (from the smallest start of all
                                  // its heads); null for full decode
     unsigned long long* st_full; // [batch*Hkv] KV tokens a full decode would stream
@@ -121,105 +119,125 @@ __device__ __forceinline__ GroupSpan group_span(const AttnParams& p, int b, int 
 __device__ __forceinline__ int mid_items(const GroupSpan& s, int C) { return s.nb > s.gs ? (s.nb + C - 1) / C - s.gs / C : 0; }
 __device__ __forceinline__ int band_items(const GroupSpan& s, int C) { return s.n > s.nb ? (s.n + C - 1) / C - s.nb / C : 0; }
 
-constexpr int kAttnRoundsMin = 2;        // work items per work-group a launch aims at, at least
-constexpr int kAttnChunkPref = 2048;     // tokens per work item once the chip is full (more rounds instead of longer items)
-constexpr int kAttnChunkMax = 4096;
+constexpr int kAttnChunkMax = 4096;      // tokens per work item at most (a wave's page ids sit one per lane: 32 tiles x 2)
 
-template <int HT> struct AttnCaps { static constexpr int kMaxGroups = HT == 1 ? 4096 : 512; };
+template <int HT> struct AttnCaps { static constexpr int kMaxGroups = HT == 1 ? 2048 : 256; };
 
 template <int HT>
-__device__ __forceinline__ void attn_item(const AttnParams& p, int C, int q, int k, float (&s_O)[4][HT * 16 * kHeadDim],
-                                          float (&s_m)[4][HT * 16], float (&s_l)[4][HT * 16], char* s_q, int (&s_skip)[HT * 16]);
+__device__ __forceinline__ void attn_item(const AttnParams& p, int C, int q, int item_k, int n, int gs,
+                                          float (&s_O)[4][HT * 16 * kHeadDim], float (&s_m)[4][HT * 16],
+                                          float (&s_l)[4][HT * 16], char* s_q, int (&s_skip)[HT * 16]);
 
 // The planner of the paper (Sec. 4.2 K2 (1), App. B.2 "Load balancing": work-groups in proportion to span) runs inside
 // the kernel: every work-group derives the same list of work items from kv_lens and the heads' starts -- one thread
-// per KV group, a block-wide sum for the step's total span, from it the tokens per item (so that a step with little
-// work still spreads over the chip and a step with much work takes a whole number of rounds), a block-wide prefix sum
-// of the groups' item counts -- and then takes items: its own index first, further ones from a counter.  The grid is
-// the number of work-groups the chip holds, not the number of items max_kv_len could have, so a step whose heads were
-// all finished by the matcher costs one short round trip per resident work-group.
+// per KV group, a block-wide sum for the step's total span, from it the tokens per item, a block-wide prefix sum of
+// the groups' item counts -- and then takes the items blockIdx.x, blockIdx.x + gridDim.x, ...  The grid is the number
+// of work-groups the chip holds (two per compute unit), not the number of items max_kv_len could have, so a step
+// whose heads were all finished by the matcher costs one short round trip per resident work-group.
+//
+// Tokens per item.  Measured on full-length steps: the fewer and longer the items, the faster (each item costs a
+// prologue -- lengths, starts, page ids, queries, first tiles -- and an epilogue -- merge of the four waves, G
+// partial rows -- of a few microseconds that the other work-group of the compute unit only partly covers: 32 groups
+// of 131072 tokens take 335 us with 2752-token items, 341 us with 2080, 345 us with 1376), provided that the number
+// of items does not exceed a whole number of rounds of the grid by a few: items are assigned round-robin, so R rounds
+// plus a handful costs R + 1 (2048-token items, 2080 of them on 512 work-groups: 357 us).  So: R = the rounds that
+// items of the largest size need, C = total span / (R x grid) rounded up to a multiple of 32, and C grows until the
+// exact item count fits R rounds (the groups' ranges are cut on a global grid of C tokens, so every group adds up
+// to two short items).  A step with little work (a few groups without reuse among many with) gets R = 1 and items as
+// short as chunk_min, so that it still spreads over the chip.
 template <int HT>   // number of 16-head tiles: 1 (G <= 16) or 2 (G <= 32)
 __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnParams p) {
     // Shared memory.  s_O carries the waves' states to the merge at the end.  With two head tiles (HT == 2) a wave
     // keeps only one tile's output accumulators in registers: during the stream s_O[w] holds both tiles'
     // accumulators in register layout ([tile][column block j][lane] x 16 B: conflict-free) and each tile is loaded,
-    // updated and stored back per K/V tile; the queries (B operands of S = K Q^T) of all 32 heads sit in s_q, rows
-    // padded to 272 B so that the 16 rows read by one instruction fall into different banks.  That keeps the
-    // kernel at the register budget of the one-tile variant (two waves per SIMD, two work-groups per CU), which
-    // matters more than the extra shared-memory traffic: with all 64 accumulators in registers the kernel needs
-    // ~440 registers, runs one wave per SIMD and leaves the CU idle during every work-group's prologue and epilogue.
+    // updated and stored back per K/V tile.  The queries (B operands of S = K Q^T) sit in s_q, rows padded to 272 B
+    // so that the 16 rows read by one instruction fall into different banks.
     __shared__ float s_O[4][HT * 16 * kHeadDim];
     __shared__ float s_m[4][HT * 16];
     __shared__ float s_l[4][HT * 16];
     constexpr int kQRowBytes = 2 * kHeadDim + 16;
-    __shared__ __attribute__((aligned(16))) char s_q[HT == 2 ? 32 * kQRowBytes : 16];
+    __shared__ __attribute__((aligned(16))) char s_q[HT * 16 * kQRowBytes];
     __shared__ int s_skip[HT * 16];
-    __shared__ int s_prefix[AttnCaps<HT>::kMaxGroups + 1];   // work items before group q
-    __shared__ long long s_tok[4];
-    __shared__ int s_cnt[4];
-    __shared__ int s_next;
+    constexpr int kCap = AttnCaps<HT>::kMaxGroups;
+    __shared__ int s_prefix[kCap + 1];                       // work items before group q
+    __shared__ int s_gs[kCap], s_n[kCap];                    // start of the group's range (-1: nothing to do), kv_len
+    __shared__ long long s_sum[4];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int Hkv = p.Hq / p.G, NG = p.batch * Hkv;
     const int P = gridDim.x;
+    auto block_sum = [&](long long v) {                      // the same total in every thread
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) v += __shfl_xor(v, off);
+        if (lane == 0) s_sum[wv] = v;
+        __syncthreads();
+        v = s_sum[0] + s_sum[1] + s_sum[2] + s_sum[3];
+        __syncthreads();
+        return v;
+    };
+    auto items_of = [&](int q, int C) {
+        const int gs = s_gs[q], n = s_n[q];
+        if (gs < 0) return 0;
+        const int nb = n - p.band > 0 ? n - p.band : 0;
+        return (nb > gs ? (nb + C - 1) / C - gs / C : 0) + (n > nb ? (n + C - 1) / C - nb / C : 0);
+    };
 
-    // ---- plan, pass 1: the step's total span and the number of groups with work
+    // ---- plan: the groups' ranges, the step's total span; the first work-group also keeps the per-group counters
+    long long tok = 0;
+    for (int q = tid; q < NG; q += 256) {
+        const int b = q / Hkv, g = q - b * Hkv;
+        const GroupSpan s = group_span(p, b, b * p.Hq + g * p.G);
+        const bool work = s.any && s.n > s.gs;
+        s_gs[q] = work ? s.gs : -1;
+        s_n[q] = s.n;
+        if (work) tok += s.n - s.gs;
+        if (blockIdx.x == 0 && p.st_read != nullptr) {       // one writer per address and step: fire-and-forget adds
+            atomicAdd(&p.st_read[q], (unsigned long long)(s.n - s.gs_all));
+            atomicAdd(&p.st_full[q], (unsigned long long)s.n);
+            if (s.any) atomicAdd(&p.st_split[q], (unsigned long long)(s.n - s.gs));
+        }
+    }
+    tok = block_sum(tok);                                    // (its barrier also publishes s_gs / s_n)
+    if (tok == 0) return;
+    // ---- plan: tokens per item
     int C = p.chunk_fixed;
     if (C == 0) {
-        long long tok = 0;
-        int act = 0;
-        for (int q = tid; q < NG; q += 256) {
-            const int b = q / Hkv, g = q - b * Hkv;
-            const GroupSpan s = group_span(p, b, b * p.Hq + g * p.G);
-            if (s.any && s.n > s.gs) { tok += s.n - s.gs; ++act; }
+        long long R = (tok + (long long)P * kAttnChunkMax - 1) / ((long long)P * kAttnChunkMax);
+        auto chunk_for = [&](long long rounds) {
+            long long c = (tok + rounds * P - 1) / (rounds * P);
+            c = (c + 31) & ~31ll;
+            return (int)(c < p.chunk_min ? p.chunk_min : c);
+        };
+        C = chunk_for(R);
+        for (int tries = 0; tries < 6; ++tries) {
+            if (C > kAttnChunkMax) { ++R; C = chunk_for(R); }
+            long long items = 0;
+            for (int q = tid; q < NG; q += 256) items += items_of(q, C);
+            items = block_sum(items);
+            if (items <= R * P || C >= kAttnChunkMax) break;
+            // too many by `items - R P`: lengthen every item by its share of their tokens
+            const long long grow = ((items - R * P) * C + R * P - 1) / (R * P);
+            C += (int)((grow + 31) & ~31ll);
         }
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            tok += __shfl_xor(tok, off);
-            act += __shfl_xor(act, off);
-        }
-        if (lane == 0) { s_tok[wv] = tok; s_cnt[wv] = act; }
-        __syncthreads();
-        tok = s_tok[0] + s_tok[1] + s_tok[2] + s_tok[3];
-        act = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
-        __syncthreads();
-        // rounds: as many as items of the preferred size need, at least kAttnRoundsMin; every group adds up to two
-        // partial items (the grid of C tokens is global), which must fit into the last round, not start a new one
-        long long rounds = (tok + (long long)P * kAttnChunkPref - 1) / ((long long)P * kAttnChunkPref);
-        if (rounds < kAttnRoundsMin) rounds = kAttnRoundsMin;
-        long long target = rounds * P - 2 * act;
-        if (target < P / 2) target = P / 2;
-        long long c = (tok + target - 1) / target;
-        c = (c + 31) & ~31ll;
-        C = (int)(c < p.chunk_min ? p.chunk_min : (c > kAttnChunkMax ? kAttnChunkMax : c));
+        if (C > kAttnChunkMax) C = kAttnChunkMax;
     }
     C = __builtin_amdgcn_readfirstlane(C);                   // uniform values in scalar registers: what derives from them stays there
-    // ---- plan, pass 2: items per group, prefix sums; the first work-group also keeps the per-group counters
+    // ---- plan: prefix sums of the groups' item counts
     int total = 0;
     for (int q0 = 0; q0 < NG; q0 += 256) {
         const int q = q0 + tid;
-        int items = 0;
-        if (q < NG) {
-            const int b = q / Hkv, g = q - b * Hkv;
-            const GroupSpan s = group_span(p, b, b * p.Hq + g * p.G);
-            if (s.any) items = mid_items(s, C) + band_items(s, C);
-            if (blockIdx.x == 0 && p.st_read != nullptr) {   // one writer per address and step: fire-and-forget adds
-                atomicAdd(&p.st_read[q], (unsigned long long)(s.n - s.gs_all));
-                atomicAdd(&p.st_full[q], (unsigned long long)s.n);
-                if (s.any) atomicAdd(&p.st_split[q], (unsigned long long)(s.n - s.gs));
-            }
-        }
+        const int items = q < NG ? items_of(q, C) : 0;
         int incl = items;                                    // inclusive scan inside the wave
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
             const int v = __shfl_up(incl, off);
             if (lane >= off) incl += v;
         }
-        if (lane == 63) s_cnt[wv] = incl;
+        if (lane == 63) s_sum[wv] = incl;
         __syncthreads();
         int before = total;
-        for (int ww = 0; ww < wv; ++ww) before += s_cnt[ww];
+        for (int ww = 0; ww < wv; ++ww) before += (int)s_sum[ww];
         if (q < NG) s_prefix[q] = before + incl - items;
-        total += s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
+        total += (int)(s_sum[0] + s_sum[1] + s_sum[2] + s_sum[3]);
         __syncthreads();
     }
     if (tid == 0) {
@@ -229,11 +247,10 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnParams p) {
     __syncthreads();
     total = __builtin_amdgcn_readfirstlane(s_prefix[NG]);
 
-    // ---- work items: the first one by position, further ones from the counter (requested while the current one runs)
-    int item = blockIdx.x;
-    while (item < total) {
-        int nxt = 0;
-        if (tid == 0) nxt = (int)atomicAdd(reinterpret_cast<unsigned int*>(p.work_counter), 1u);
+    // ---- work items: item, item + gridDim.x, ...  (the items of a launch have the same size but for the ends of the
+    // groups' ranges, so a fixed assignment balances as well as handing them out one by one from a counter did:
+    // measured 433 vs 438 us on 32 groups of 131072 tokens)
+    for (int item = blockIdx.x; item < total; item += P) {
         int lo_q = 0, hi_q = NG;                             // the group: largest q with s_prefix[q] <= item
         while (hi_q - lo_q > 1) {
             const int mid = (lo_q + hi_q) >> 1;
@@ -241,30 +258,33 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnParams p) {
         }
         const int q = __builtin_amdgcn_readfirstlane(lo_q);
         const int k = item - __builtin_amdgcn_readfirstlane(s_prefix[q]);
-        attn_item<HT>(p, C, q, k, s_O, s_m, s_l, s_q, s_skip);
-        if (tid == 0) s_next = nxt + P;
-        __syncthreads();
-        item = __builtin_amdgcn_readfirstlane(s_next);
+        const int n = __builtin_amdgcn_readfirstlane(s_n[q]), gs = __builtin_amdgcn_readfirstlane(s_gs[q]);
+        attn_item<HT>(p, C, q, k, n, gs, s_O, s_m, s_l, s_q, s_skip);
         __syncthreads();
     }
 }
 
 // One work item: item `item_k` of KV group q with C tokens per item.  Contains barriers: called by the whole work-group.
 template <int HT>
-__device__ __forceinline__ void attn_item(const AttnParams& p, const int C, const int q, const int item_k,
-                                          float (&s_O)[4][HT * 16 * kHeadDim], float (&s_m)[4][HT * 16],
+__device__ __forceinline__ void attn_item(const AttnParams& p, const int C, const int q, const int item_k, const int n,
+                                          const int gs, float (&s_O)[4][HT * 16 * kHeadDim], float (&s_m)[4][HT * 16],
                                           float (&s_l)[4][HT * 16], char* s_q, int (&s_skip)[HT * 16]) {
     constexpr int kQRowBytes = 2 * kHeadDim + 16;
     const int Hkv = p.Hq / p.G;
     const int b = q / Hkv, g = q - b * Hkv;
-    const int tid = threadIdx.x, l = tid & 63;
+    // (the thread index passes through an empty asm statement: what is derived from it is then computed per work
+    // item instead of being kept in registers across the loop over work items, where none are to spare)
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const int l = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave index as a scalar: tile positions and page bases stay in SGPRs
     const int r16 = l & 15, kg = l >> 4;
     const int G = p.G;
     const int tiles_per_chunk = C >> 5;
     const int hbase = b * p.Hq + g * G;
-    const GroupSpan sp = group_span(p, b, hbase);
-    const int n = sp.n, nb = sp.nb, gs = sp.gs, gmax = sp.gmax;
+    const int nb = n - p.band > 0 ? n - p.band : 0;          // the band is [nb, n)
+    GroupSpan sp;
+    sp.n = n; sp.nb = nb; sp.gs = gs;
     const int n_mid = mid_items(sp, C);
     const bool is_mid = item_k < n_mid;
     // chunk index on the global grid of C tokens, the item's token range, and its partial slot
@@ -290,11 +310,17 @@ __device__ __forceinline__ void attn_item(const AttnParams& p, const int C, cons
         my_start[ht] = (ht * 16 + r16 < G) ? 0 : kHeadDone;
         if (p.head_start != nullptr && ht * 16 + r16 < G) my_start[ht] = p.head_start[hbase + ht * 16 + r16];
     }
-    const int maxstart = max(gmax, lo);                       // tiles at or above it need no start mask
+    // largest start among the heads served here: tiles at or above it need no start mask
+    int gmax = 0;
+#pragma unroll
+    for (int ht = 0; ht < HT; ++ht)
+        if (!(my_start[ht] & kHeadDone)) gmax = max(gmax, min(my_start[ht], nb));
+#pragma unroll
+    for (int off = 1; off < 16; off <<= 1) gmax = max(gmax, __shfl_xor(gmax, off));
+    const int maxstart = max(__builtin_amdgcn_readfirstlane(gmax), lo);
 
-    // per-lane head data for each head tile: first token this head attends to, and its query (B operand)
+    // per-lane head data for each head tile: first token this head attends to
     int hstart[HT];
-    bf16x8 qreg[HT == 1 ? 1 : 1][4];                          // HT == 1: the tile's query; HT == 2: unused
     // a head that needs nothing here (finished by the matcher, or padding of the head tile) gets a zero query and no
     // mask; its rows of the result are never stored
 #pragma unroll
@@ -303,29 +329,22 @@ __device__ __forceinline__ void attn_item(const AttnParams& p, const int C, cons
         hstart[ht] = skip ? lo : max(lo, min(my_start[ht], nb));
         if (w == 0 && kg == 0) s_skip[ht * 16 + r16] = skip ? 1 : 0;
     }
-    if constexpr (HT == 1) {
-        const bool valid = !(my_start[0] & kHeadDone);
-        const uint16_t* qp = p.q_rope + (int64_t)(hbase + (valid ? r16 : 0)) * kHeadDim + 8 * kg;
+    {
+        // queries to shared memory: HT * 16 rows x 16 chunks of 16 B, HT per thread; rows of heads that need nothing are zero
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            u32x4 v = *reinterpret_cast<const u32x4*>(qp + 32 * c);
-            if (!valid) v = u32x4{0u, 0u, 0u, 0u};
-            qreg[0][c] = __builtin_bit_cast(bf16x8, v);
-        }
-    } else {
-        // 32 rows x 16 chunks of 16 B = 512 chunks, two per thread; rows of heads beyond G are zero
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
+        for (int t = 0; t < HT; ++t) {
             const int idx = tid + 256 * t, row = idx >> 4, ch = idx & 15;
             u32x4 v = u32x4{0u, 0u, 0u, 0u};
             const bool skip = row >= G || (p.head_start != nullptr && (p.head_start[hbase + (row < G ? row : 0)] & kHeadDone));
             if (!skip) v = *reinterpret_cast<const u32x4*>(p.q_rope + (int64_t)(hbase + row) * kHeadDim + 8 * ch);
             *reinterpret_cast<u32x4*>(s_q + row * kQRowBytes + 16 * ch) = v;
         }
-        // this wave's accumulators of both tiles start at zero
-        char* acc_img = reinterpret_cast<char*>(&s_O[w][0]);
+        if constexpr (HT == 2) {
+            // this wave's accumulators of both tiles start at zero
+            char* acc_img = reinterpret_cast<char*>(&s_O[w][0]);
 #pragma unroll
-        for (int i = 0; i < 16; ++i) *reinterpret_cast<f32x4*>(acc_img + 1024 * i + 16 * l) = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int i = 0; i < 16; ++i) *reinterpret_cast<f32x4*>(acc_img + 1024 * i + 16 * l) = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
         __syncthreads();
     }
 
@@ -396,13 +415,14 @@ __device__ __forceinline__ void attn_item(const AttnParams& p, const int C, cons
         const bool need_mask = (t0 < maxstart) || (t0 + kTileTokens > hi);   // wave-uniform
 #pragma unroll
         for (int ht = 0; ht < HT; ++ht) {
-            // the tile's queries: registers, or shared memory (row = head, 16-byte chunk 4c + kg of k-step c)
+            // the tile's queries from shared memory (row = head, 16-byte chunk 4c + kg of k-step c), read again for
+            // every tile: 16 registers that the loop over work items has no room for
+            if constexpr (HT == 1) asm volatile("" ::: "memory");
             bf16x8 qop[4];
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                if constexpr (HT == 1) qop[c] = qreg[0][c];
-                else qop[c] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(
-                                  s_q + (ht * 16 + r16) * kQRowBytes + 64 * c + 16 * kg));
+                qop[c] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(
+                             s_q + (ht * 16 + r16) * kQRowBytes + 64 * c + 16 * kg));
             }
             char* const acc_img = reinterpret_cast<char*>(&s_O[w][0]) + 8192 * ht + 16 * l;
             if constexpr (HT == 2) {

@@ -82,7 +82,7 @@ int default_chunk(int64_t groups, int64_t max_kv_len, int heads_per_group) {
     return chunk;
 }
 
-constexpr int64_t kPlanBytes = 256;      // [0]: tokens per work item of the last launch; [16]: work-item counter (ints)
+constexpr int64_t kPlanBytes = 256;      // [0]: tokens per work item the attention kernel chose at its last launch
 
 struct Layout {            // derived sizes, pure host arithmetic
     int G, chunk_fixed, chunk_min, n_mid_slots, n_band_slots, n_slots, page_shift, max_split;
@@ -167,7 +167,7 @@ struct mac_attn_ctx {
     float* part_lse = nullptr;
     mac::MatchPartial* m_slices = nullptr; // [bh, n_split] nearest entry per window slice (group matcher only)
     mac::MatchPartial* m_part = nullptr;   // [bh] nearest entry of each head's window
-    int32_t* plan = nullptr;               // [0] tokens per work item of the last attention launch, [16] its work-item counter
+    int32_t* plan = nullptr;               // [0] tokens per work item of the last attention launch
     int32_t grid_attn = 512;               // work-groups of the attention kernel: two per compute unit
     int32_t fused_span = 0;                // largest fresh range the per-head matcher finishes itself (0 = none)
     int32_t* head_start = nullptr;         // [max_batch*Hq + 32] fresh-range start per head (| kHeadDone), written by the matchers
@@ -293,7 +293,6 @@ int launch_attention(mac_attn_ctx* ctx, const mac_attn_step_args* a, bool mac_mo
     p.max_kv_len = c.max_kv_len;
     p.scale_log2 = ctx->sm_scale * mac::kLog2e;
     p.step_chunk = ctx->plan;
-    p.work_counter = ctx->plan + 16;
     const int64_t bh = (int64_t)c.max_batch * c.num_q_heads;
     const int64_t bg = (int64_t)c.max_batch * c.num_kv_heads;
     p.st_read = mac_mode ? ctx->stats + 4 * bh : nullptr;
@@ -340,7 +339,6 @@ mac::MergeParams merge_params(mac_attn_ctx* ctx, const mac_attn_step_args* a, bo
     p.band = mac_mode ? c.band : 0;
     p.chunk_fixed = L.chunk_fixed;
     p.step_chunk = ctx->plan;
-    p.work_counter = ctx->plan + 16;
     p.n_mid_slots = L.n_mid_slots;
     p.n_slots = L.n_slots;
     p.max_kv_len = c.max_kv_len;
@@ -553,9 +551,8 @@ int mac_attn_full_decode_static(const mac_attn_static_geometry* geo, const mac_a
     tmp.grid_attn = 2 * (cus > 0 ? cus : 256);
     tmp.sm_scale = c.sm_scale > 0.f ? c.sm_scale : 1.0f / std::sqrt((float)c.head_dim);
     tmp.T2 = 0.0;
-    // Layout of the array: the attention kernel's work-item counter first, then the partials.  The counter must be
-    // zero when a call starts: it is zero when the library is loaded, and the merge kernel of every call clears it.
-    // Every partial the merge reads is written by this call's attention kernel first, so nothing else is cleared.
+    // Layout of the array: a word for the attention kernel's plan first (unused with fixed work items), then the
+    // partials.  Every partial the merge reads is written by this call's attention kernel first: nothing is cleared.
     tmp.plan = static_cast<int32_t*>(base);
     tmp.part_O = reinterpret_cast<float*>(static_cast<char*>(base) + kPlanBytes);
     tmp.part_lse = reinterpret_cast<float*>(static_cast<char*>(base) + kPlanBytes + part_O_bytes);
