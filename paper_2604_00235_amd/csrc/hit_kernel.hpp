@@ -33,6 +33,12 @@
 namespace mac {
 
 constexpr int kHitMaxSpan = 2048;            // largest fresh range finished here: its logits sit in shared memory
+constexpr int kMaxWindow = 4096;             // largest query ring
+// Error bound of the filter, relative to |q|^2 + |r|^2: the three dot products are sums of 128 exact bf16 x bf16 products
+// accumulated in fp32 (128 x 2^-23 each, against (|q| + |r|)^2 <= 2 (|q|^2 + |r|^2) in total: 3.1e-5), taken four
+// times over to be independent of how the matrix core orders and rounds its partial sums.
+constexpr float kFilterEps = 1.25e-4f;
+constexpr double kTieRel = 0x1p-40;          // two fp64 evaluations of one distance differ by far less than this
 
 struct HitParams {
     // match
@@ -84,7 +90,6 @@ template <int NT>      // threads per work-group: 256, or 1024 when there are fe
 __global__ __launch_bounds__(NT) void hit_kernel(const HitParams p) {
     constexpr int NW = NT / 64;
     constexpr int kRows = NT / 4;                              // ring rows (or K rows) per pass: a quad per 256-byte row
-    constexpr int kPasses = 2;                                 // passes in flight
     // Work-groups are dealt to the 8 XCDs in turn: the G heads of a KV group take ids that are 8 apart.
     const int id = blockIdx.x, xcd = id & 7, k = id >> 3;
     const int G = p.G, Hkv = p.Hq / G;
@@ -99,8 +104,10 @@ __global__ __launch_bounds__(NT) void hit_kernel(const HitParams p) {
     const int W = p.W;
     const int64_t ring_row0 = (slot * p.Hq + h) * W;
 
-    __shared__ double s_d2[NW];
+    __shared__ double s_d2[NW], s_second[NW];
     __shared__ int s_np[NW], s_j[NW];
+    __shared__ float s_lower[kMaxWindow];                      // lower bound of each ring row's distance; +inf = no candidate
+    __shared__ float s_u[NW];
     __shared__ float s_logit[kHitMaxSpan];
     __shared__ int s_pid[kHitMaxSpan / 16 + 2];
     __shared__ float s_red[2][NW][2];                          // [max | sum][wave][mid | band]
@@ -112,59 +119,144 @@ __global__ __launch_bounds__(NT) void hit_kernel(const HitParams p) {
         const int n_pages = ((n - 1) >> p.page_shift) - first_page + 1;
         for (int i = tid; i < n_pages; i += NT) s_pid[i] = p.block_table[(int64_t)b * p.bt_stride + first_page + i];
     }
-    double best_d2 = INFINITY;
-    int best_np = -1, best_j = -1;
+    // ---- 1. match, in three tiers (see the head of this file): matrix-core filter, fp64 evaluation of the candidates
+    // it leaves, and -- only for candidates that tie to rounding -- the sum in index order.
+    const uint16_t* ring_h = p.ring_q + ring_row0 * kHeadDim;
+    const uint16_t* q_h = p.q_pre + (int64_t)bh * kHeadDim;
+    const int32_t* npos = p.ring_npos + ring_row0;
+    const int np_lo = max(1, n - W), np_hi = n - 1;
+    float U = INFINITY;                                        // smallest upper bound of a candidate's distance
     {
-        // ---- 1. match (same scan as the one-slice case of the window-slice design: rows loaded without waiting for
-        // their n_p tag, several passes in flight)
-        double q[32];
-        load_query_f64(p.q_pre + (int64_t)bh * kHeadDim + 8 * sub, q);
-        const uint16_t* ring = p.ring_q + ring_row0 * kHeadDim + 8 * sub;
-        const int32_t* npos = p.ring_npos + ring_row0;
-        const int np_lo = max(1, n - W), np_hi = n - 1;
-        auto row_of = [&](int j0, int& j, int& np, u32x4 (&v)[4]) {
-            j = j0 + quad;
-            const int jc = j < W ? j : W - 1;                  // keep the speculative loads inside the ring
-            np = npos[jc];
-            const uint16_t* rp = ring + (int64_t)jc * kHeadDim;
+        const int r16 = lane & 15, kg = lane >> 4;
+        bf16x8 qb[4];                                          // B operand: the query in every column
+        float qq = 0.f;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) v[i] = *reinterpret_cast<const u32x4*>(rp + 32 * i);
-        };
-        auto take = [&](int j, int np, const u32x4 (&v)[4]) {
-            const bool valid = j < W && np >= np_lo && np <= np_hi;
-            double d2 = lane_sq_dist(q, v);
-            d2 += __shfl_xor(d2, 1);
-            d2 += __shfl_xor(d2, 2);
-            if (valid && better(d2, np, best_d2, best_np)) { best_d2 = d2; best_np = np; best_j = j; }
-        };
-        int j0 = 0;
-        for (; j0 + (kPasses - 1) * kRows < W; j0 += kPasses * kRows) {
-            int jj[kPasses], nn[kPasses];
-            u32x4 vv[kPasses][4];
+        for (int c = 0; c < 4; ++c) {
+            const u32x4 v = *reinterpret_cast<const u32x4*>(q_h + 32 * c + 8 * kg);
+            qb[c] = __builtin_bit_cast(bf16x8, v);
 #pragma unroll
-            for (int t = 0; t < kPasses; ++t) row_of(j0 + t * kRows, jj[t], nn[t], vv[t]);
-#pragma unroll
-            for (int t = 0; t < kPasses; ++t) take(jj[t], nn[t], vv[t]);
+            for (int e = 0; e < 4; ++e) {
+                const float lo = bf16_lo_to_f32(v[e]), hi = bf16_hi_to_f32(v[e]);
+                qq = fmaf(lo, lo, qq);
+                qq = fmaf(hi, hi, qq);
+            }
         }
-        for (; j0 < W; j0 += kRows) {
-            int ja, npa;
-            u32x4 va[4];
-            row_of(j0, ja, npa, va);
-            take(ja, npa, va);
+        qq += __shfl_xor(qq, 16);
+        qq += __shfl_xor(qq, 32);
+        const bool diag = kg == (r16 >> 2);                    // this lane holds row r16 of a tile: component r16 & 3
+        const int pick = r16 & 3;
+        const int n_tiles = (W + 15) >> 4;
+        constexpr int kInFlight = 4;                           // 16-row tiles requested per wave before the arithmetic
+        for (int t0 = w; t0 < n_tiles; t0 += NW * kInFlight) {
+            u32x4 a[kInFlight][4];
+            int tag[kInFlight];
+#pragma unroll
+            for (int u = 0; u < kInFlight; ++u) {
+                const int row = min(16 * (t0 + u * NW) + r16, W - 1);      // keeps the loads inside the ring
+                const uint16_t* rp = ring_h + (int64_t)row * kHeadDim + 8 * kg;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) a[u][c] = *reinterpret_cast<const u32x4*>(rp + 32 * c);
+                tag[u] = npos[row];
+            }
+#pragma unroll
+            for (int u = 0; u < kInFlight; ++u) {
+                const int t = t0 + u * NW;
+                if (t < n_tiles) {                             // wave-uniform
+                    f32x4 dot = f32x4{0.f, 0.f, 0.f, 0.f}, gram = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const bf16x8 ac = __builtin_bit_cast(bf16x8, a[u][c]);
+                        dot = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ac, qb[c], dot, 0, 0, 0);
+                        gram = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ac, ac, gram, 0, 0, 0);
+                    }
+                    const float sd = pick == 0 ? dot[0] : pick == 1 ? dot[1] : pick == 2 ? dot[2] : dot[3];
+                    const float rr = pick == 0 ? gram[0] : pick == 1 ? gram[1] : pick == 2 ? gram[2] : gram[3];
+                    const int row = 16 * t + r16;
+                    const bool valid = row < W && tag[u] >= np_lo && tag[u] <= np_hi;
+                    const float f = qq + rr - 2.f * sd, eps = kFilterEps * (qq + rr);
+                    float lower = f - eps, upper = f + eps;
+                    if (!(fabsf(f) < INFINITY)) { lower = -INFINITY; upper = INFINITY; }    // overflow: decided in fp64
+                    if (diag && row < W) s_lower[row] = valid ? lower : INFINITY;
+                    if (diag && valid) U = fminf(U, upper);
+                }
+            }
         }
 #pragma unroll
-        for (int off = 4; off < 64; off <<= 1) {               // all 4 lanes of a quad hold the same triple
-            const double od2 = __shfl_xor(best_d2, off);
-            const int onp = __shfl_xor(best_np, off);
-            const int oj = __shfl_xor(best_j, off);
-            if (better(od2, onp, best_d2, best_np)) { best_d2 = od2; best_np = onp; best_j = oj; }
-        }
-        if (lane == 0) { s_d2[w] = best_d2; s_np[w] = best_np; s_j[w] = best_j; }
+        for (int off = 1; off < 64; off <<= 1) U = fminf(U, __shfl_xor(U, off));
+        if (lane == 0) s_u[w] = U;
         __syncthreads();
-        best_d2 = s_d2[0]; best_np = s_np[0]; best_j = s_j[0];
+        U = s_u[0];
 #pragma unroll
-        for (int ww = 1; ww < NW; ++ww)
-            if (better(s_d2[ww], s_np[ww], best_d2, best_np)) { best_d2 = s_d2[ww]; best_np = s_np[ww]; best_j = s_j[ww]; }
+        for (int ww = 1; ww < NW; ++ww) U = fminf(U, s_u[ww]);
+    }
+    // tier 2: the rows the filter could not rule out, a quad per row, in fp64
+    double best_d2 = INFINITY, second_d2 = INFINITY;           // nearest candidate and the distance of the next one
+    int best_np = -1, best_j = -1;
+    auto row_d2 = [&](int r) {                                 // called by the four lanes of a quad together
+        double q[32];
+        load_query_f64(q_h + 8 * sub, q);
+        u32x4 v[4];
+        const uint16_t* rp = ring_h + (int64_t)r * kHeadDim + 8 * sub;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = *reinterpret_cast<const u32x4*>(rp + 32 * i);
+        double d2 = lane_sq_dist(q, v);
+        d2 += __shfl_xor(d2, 1);
+        d2 += __shfl_xor(d2, 2);
+        return d2;
+    };
+    auto reduce_best = [&](double& d2, int& np, int& j, double& second) {      // every thread gets the block's result
+#pragma unroll
+        for (int off = 4; off < 64; off <<= 1) {               // all 4 lanes of a quad hold the same values
+            const double od2 = __shfl_xor(d2, off), osec = __shfl_xor(second, off);
+            const int onp = __shfl_xor(np, off), oj = __shfl_xor(j, off);
+            if (better(od2, onp, d2, np)) { second = fmin(d2, osec); d2 = od2; np = onp; j = oj; }
+            else second = fmin(second, od2);
+        }
+        __syncthreads();                                       // the arrays may still be read from an earlier call
+        if (lane == 0) { s_d2[w] = d2; s_np[w] = np; s_j[w] = j; s_second[w] = second; }
+        __syncthreads();
+        d2 = s_d2[0]; np = s_np[0]; j = s_j[0]; second = s_second[0];
+#pragma unroll
+        for (int ww = 1; ww < NW; ++ww) {
+            if (better(s_d2[ww], s_np[ww], d2, np)) { second = fmin(d2, s_second[ww]); d2 = s_d2[ww]; np = s_np[ww]; j = s_j[ww]; }
+            else second = fmin(second, s_d2[ww]);
+        }
+    };
+    for (int r = quad; r < W; r += kRows) {
+        const float lw = s_lower[r];
+        if (lw <= U && lw < INFINITY) {
+            const double d2 = row_d2(r);
+            const int np = npos[r];
+            if (better(d2, np, best_d2, best_np)) { second_d2 = best_d2; best_d2 = d2; best_np = np; best_j = r; }
+            else second_d2 = fmin(second_d2, d2);
+        }
+    }
+    reduce_best(best_d2, best_np, best_j, second_d2);
+    // tier 3: two fp64 evaluations of one distance agree to ~2^-46 relative, so the order of two candidates, or of the
+    // nearest one and the threshold, can depend on the evaluation only if they lie closer than that.  Then the
+    // candidates in question are summed once more, one lane each, in index order without fused multiply-adds: the
+    // plain left-to-right sum that a reference evaluation of Eq. (accept) takes, so that the decision is the same bit
+    // for bit.  (Exact duplicates in the window come here too, and fall to the tie-break as before.)
+    if (best_np >= 0 && (second_d2 <= best_d2 * (1.0 + kTieRel) || fabs(best_d2 - p.mv.T2) <= kTieRel * p.mv.T2)) {
+        const double bound = best_d2 * (1.0 + kTieRel);
+        double e_d2 = INFINITY, e_second = INFINITY;
+        int e_np = -1, e_j = -1;
+        for (int r = quad; r < W; r += kRows) {
+            const float lw = s_lower[r];
+            if (lw <= U && lw < INFINITY && row_d2(r) <= bound) {
+                double e = 0.0;
+                const uint16_t* rp = ring_h + (int64_t)r * kHeadDim;
+                for (int i = 0; i < kHeadDim; ++i) {
+                    const double diff = __dsub_rn((double)bits_to_float((uint32_t)q_h[i] << 16), (double)bits_to_float((uint32_t)rp[i] << 16));
+                    e = __dadd_rn(e, __dmul_rn(diff, diff));
+                }
+                const int np = npos[r];
+                if (better(e, np, e_d2, e_np)) { e_second = e_d2; e_d2 = e; e_np = np; e_j = r; }
+                else e_second = fmin(e_second, e);
+            }
+        }
+        reduce_best(e_d2, e_np, e_j, e_second);
+        best_d2 = e_d2; best_np = e_np; best_j = e_j;
     }
 
     // ---- 2. decision (every thread holds the same values)
