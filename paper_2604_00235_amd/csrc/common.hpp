@@ -34,6 +34,60 @@ __device__ __forceinline__ uint16_t float_to_bf16_rne(float f) {
 
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }   // v_exp_f32; exp2(-inf) = 0
 
+// ---- cross-lane helpers (wave64).  Reductions inside a 16-lane row use DPP (no shared-memory round trip as a
+// bpermute-based shuffle has); rows are combined with v_readlane.  Lane-wise exchanges between rows use the
+// row-swap instructions of this chip: v_permlane16_swap exchanges the odd rows of its first operand with the even
+// rows of its second, v_permlane32_swap the upper half of the first with the lower half of the second.
+template <int kCtrl>
+__device__ __forceinline__ float dpp_f32(float v) {
+    return bits_to_float((uint32_t)__builtin_amdgcn_update_dpp((int)float_to_bits(v), (int)float_to_bits(v), kCtrl, 0xf, 0xf, false));
+}
+constexpr int kDppQuadSwap1 = 0xB1, kDppQuadSwap2 = 0x4E, kDppRowHalfMirror = 0x141, kDppRowMirror = 0x140;
+#define MAC_WAVE_REDUCE(NAME, OP)                                                                    \
+    __device__ __forceinline__ float NAME(float v) {                                                 \
+        v = OP(v, dpp_f32<kDppQuadSwap1>(v));                                                        \
+        v = OP(v, dpp_f32<kDppQuadSwap2>(v));                                                        \
+        v = OP(v, dpp_f32<kDppRowHalfMirror>(v));                                                    \
+        v = OP(v, dpp_f32<kDppRowMirror>(v));                      /* every lane: its row's result */ \
+        const float r0 = bits_to_float((uint32_t)__builtin_amdgcn_readlane((int)float_to_bits(v), 0));   \
+        const float r1 = bits_to_float((uint32_t)__builtin_amdgcn_readlane((int)float_to_bits(v), 16));  \
+        const float r2 = bits_to_float((uint32_t)__builtin_amdgcn_readlane((int)float_to_bits(v), 32));  \
+        const float r3 = bits_to_float((uint32_t)__builtin_amdgcn_readlane((int)float_to_bits(v), 48));  \
+        return OP(OP(r0, r1), OP(r2, r3));                                                           \
+    }
+__device__ __forceinline__ float op_add(float a, float b) { return a + b; }
+MAC_WAVE_REDUCE(wave_min_f32, fminf)
+MAC_WAVE_REDUCE(wave_max_f32, fmaxf)
+MAC_WAVE_REDUCE(wave_sum_f32, op_add)      // rows in fixed order: reproducible
+#undef MAC_WAVE_REDUCE
+
+// x[l] + x[l ^ 16] and x[l] + x[l ^ 32], lane-wise
+__device__ __forceinline__ float add_xor16(float x) {
+    const auto r = __builtin_amdgcn_permlane16_swap(float_to_bits(x), float_to_bits(x), false, false);
+    return bits_to_float(r[0]) + bits_to_float(r[1]);
+}
+__device__ __forceinline__ float add_xor32(float x) {
+    const auto r = __builtin_amdgcn_permlane32_swap(float_to_bits(x), float_to_bits(x), false, false);
+    return bits_to_float(r[0]) + bits_to_float(r[1]);
+}
+__device__ __forceinline__ double add_xor16(double x) {
+    const uint64_t u = __builtin_bit_cast(uint64_t, x);
+    const auto lo = __builtin_amdgcn_permlane16_swap((uint32_t)u, (uint32_t)u, false, false);
+    const auto hi = __builtin_amdgcn_permlane16_swap((uint32_t)(u >> 32), (uint32_t)(u >> 32), false, false);
+    return __builtin_bit_cast(double, ((uint64_t)hi[0] << 32) | lo[0]) + __builtin_bit_cast(double, ((uint64_t)hi[1] << 32) | lo[1]);
+}
+__device__ __forceinline__ double add_xor32(double x) {
+    const uint64_t u = __builtin_bit_cast(uint64_t, x);
+    const auto lo = __builtin_amdgcn_permlane32_swap((uint32_t)u, (uint32_t)u, false, false);
+    const auto hi = __builtin_amdgcn_permlane32_swap((uint32_t)(u >> 32), (uint32_t)(u >> 32), false, false);
+    return __builtin_bit_cast(double, ((uint64_t)hi[0] << 32) | lo[0]) + __builtin_bit_cast(double, ((uint64_t)hi[1] << 32) | lo[1]);
+}
+__device__ __forceinline__ double readlane_f64(double x, int l) {      // l uniform
+    const uint64_t u = __builtin_bit_cast(uint64_t, x);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)u, l), hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(u >> 32), l);
+    return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
+
 __device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
 // head_start[] holds, per (request, head), the first key of the head's fresh range; this flag is set when the per-head

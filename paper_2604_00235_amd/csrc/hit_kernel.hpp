@@ -33,7 +33,6 @@
 namespace mac {
 
 constexpr int kHitMaxSpan = 2048;            // largest fresh range finished here: its logits sit in shared memory
-constexpr int kMaxWindow = 4096;             // largest query ring
 // Error bound of the filter, relative to |q|^2 + |r|^2: the three dot products are sums of 128 exact bf16 x bf16 products
 // accumulated in fp32 (128 x 2^-23 each, against (|q| + |r|)^2 <= 2 (|q|^2 + |r|^2) in total: 3.1e-5), taken four
 // times over to be independent of how the matrix core orders and rounds its partial sums.
@@ -86,8 +85,27 @@ __device__ __forceinline__ void merge2(float oa, float la, float ob, float lb, f
     l = M + logf(Z);
 }
 
+// Partial squared distance of one lane in fp64: four 16-byte chunks of the query against the same chunks of a ring row,
+// both as packed bf16.  The query is widened here, per call, rather than once per work-group: 32 doubles would cost
+// 64 registers for the whole kernel (the empty asm statement keeps the compiler from doing just that).
+__device__ __forceinline__ double sq_dist_packed(const u32x4 (&q)[4], const u32x4 (&v)[4]) {
+    double s0 = 0.0, s1 = 0.0;
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            uint32_t qw = q[c][e];
+            asm volatile("" : "+v"(qw));
+            const double d0 = bf16_lo_to_f64(qw) - bf16_lo_to_f64(v[c][e]);
+            const double d1 = bf16_hi_to_f64(qw) - bf16_hi_to_f64(v[c][e]);
+            s0 = fma(d0, d0, s0);
+            s1 = fma(d1, d1, s1);
+        }
+    return s0 + s1;
+}
+
 template <int NT>      // threads per work-group: 256, or 1024 when there are few heads and a large window
-__global__ __launch_bounds__(NT) void hit_kernel(const HitParams p) {
+__global__ __launch_bounds__(NT, NT == 256 ? 4 : 1) void hit_kernel(const HitParams p) {
     constexpr int NW = NT / 64;
     constexpr int kRows = NT / 4;                              // ring rows (or K rows) per pass: a quad per 256-byte row
     // Work-groups are dealt to the 8 XCDs in turn: the G heads of a KV group take ids that are 8 apart.
@@ -106,8 +124,7 @@ __global__ __launch_bounds__(NT) void hit_kernel(const HitParams p) {
 
     __shared__ double s_d2[NW], s_second[NW];
     __shared__ int s_np[NW], s_j[NW];
-    __shared__ float s_lower[kMaxWindow];                      // lower bound of each ring row's distance; +inf = no candidate
-    __shared__ float s_u[NW];
+    __shared__ float s_u[2][NW];
     __shared__ float s_logit[kHitMaxSpan];
     __shared__ int s_pid[kHitMaxSpan / 16 + 2];
     __shared__ float s_red[2][NW][2];                          // [max | sum][wave][mid | band]
@@ -125,29 +142,31 @@ __global__ __launch_bounds__(NT) void hit_kernel(const HitParams p) {
     const uint16_t* q_h = p.q_pre + (int64_t)bh * kHeadDim;
     const int32_t* npos = p.ring_npos + ring_row0;
     const int np_lo = max(1, n - W), np_hi = n - 1;
-    float U = INFINITY;                                        // smallest upper bound of a candidate's distance
+    double best_d2 = INFINITY, second_d2 = INFINITY;           // nearest candidate and the distance of the next one
+    int best_np = -1, best_j = -1;
     {
         const int r16 = lane & 15, kg = lane >> 4;
-        bf16x8 qb[4];                                          // B operand: the query in every column
-        float qq = 0.f;
+        u32x4 qraw[4];                                         // this lane's 16-byte chunks kg, kg + 4, kg + 8, kg + 12 of the query:
+        float qq = 0.f;                                        // the B operand (the query in every column), and |q|^2
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            const u32x4 v = *reinterpret_cast<const u32x4*>(q_h + 32 * c + 8 * kg);
-            qb[c] = __builtin_bit_cast(bf16x8, v);
+            qraw[c] = *reinterpret_cast<const u32x4*>(q_h + 32 * c + 8 * kg);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const float lo = bf16_lo_to_f32(v[e]), hi = bf16_hi_to_f32(v[e]);
+                const float lo = bf16_lo_to_f32(qraw[c][e]), hi = bf16_hi_to_f32(qraw[c][e]);
                 qq = fmaf(lo, lo, qq);
                 qq = fmaf(hi, hi, qq);
             }
         }
-        qq += __shfl_xor(qq, 16);
-        qq += __shfl_xor(qq, 32);
-        const bool diag = kg == (r16 >> 2);                    // this lane holds row r16 of a tile: component r16 & 3
-        const int pick = r16 & 3;
+        qq = add_xor32(add_xor16(qq));
+        const int pick = r16 & 3;                              // component of a tile's result that belongs to row r16 ...
+        const bool diag = kg == (r16 >> 2);                    // ... in the lane that holds it
+        float U = INFINITY;                                    // smallest upper bound the work-group has seen so far
         const int n_tiles = (W + 15) >> 4;
-        constexpr int kInFlight = 4;                           // 16-row tiles requested per wave before the arithmetic
-        for (int t0 = w; t0 < n_tiles; t0 += NW * kInFlight) {
+        constexpr int kInFlight = NT == 256 ? 4 : 2;           // 16-row tiles requested per wave before the arithmetic
+        int parity = 0;
+        for (int base = 0; base < n_tiles; base += NW * kInFlight, parity ^= 1) {       // the same trip count in every wave
+            const int t0 = base + w;
             u32x4 a[kInFlight][4];
             int tag[kInFlight];
 #pragma unroll
@@ -158,104 +177,108 @@ __global__ __launch_bounds__(NT) void hit_kernel(const HitParams p) {
                 for (int c = 0; c < 4; ++c) a[u][c] = *reinterpret_cast<const u32x4*>(rp + 32 * c);
                 tag[u] = npos[row];
             }
+            float lower[kInFlight];
 #pragma unroll
             for (int u = 0; u < kInFlight; ++u) {
-                const int t = t0 + u * NW;
-                if (t < n_tiles) {                             // wave-uniform
-                    f32x4 dot = f32x4{0.f, 0.f, 0.f, 0.f}, gram = f32x4{0.f, 0.f, 0.f, 0.f};
+                const int row = 16 * (t0 + u * NW) + r16;
+                f32x4 dot = f32x4{0.f, 0.f, 0.f, 0.f}, gram = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                    for (int c = 0; c < 4; ++c) {
-                        const bf16x8 ac = __builtin_bit_cast(bf16x8, a[u][c]);
-                        dot = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ac, qb[c], dot, 0, 0, 0);
-                        gram = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ac, ac, gram, 0, 0, 0);
+                for (int c = 0; c < 4; ++c) {
+                    const bf16x8 ac = __builtin_bit_cast(bf16x8, a[u][c]);
+                    dot = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ac, __builtin_bit_cast(bf16x8, qraw[c]), dot, 0, 0, 0);
+                    gram = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ac, ac, gram, 0, 0, 0);
+                }
+                const float sd = pick == 0 ? dot[0] : pick == 1 ? dot[1] : pick == 2 ? dot[2] : dot[3];
+                const float rr = pick == 0 ? gram[0] : pick == 1 ? gram[1] : pick == 2 ? gram[2] : gram[3];
+                const bool valid = diag && row < W && tag[u] >= np_lo && tag[u] <= np_hi;
+                const float f = qq + rr - 2.f * sd, eps = kFilterEps * (qq + rr);
+                float up = f + eps;
+                lower[u] = f - eps;
+                if (!(fabsf(f) < INFINITY)) { lower[u] = -INFINITY; up = INFINITY; }        // overflow: decided in fp64
+                if (!valid) lower[u] = INFINITY;
+                else U = fminf(U, up);
+            }
+            U = wave_min_f32(U);
+            if (lane == 0) s_u[parity][w] = U;
+            __syncthreads();
+#pragma unroll
+            for (int ww = 0; ww < NW; ++ww) U = fminf(U, s_u[parity][ww]);
+            // tier 2: tiles with a row the filter cannot rule out are evaluated in fp64 where they sit (the lanes
+            // r16, r16 + 16, r16 + 32, r16 + 48 hold the four quarters of row r16, as a quad does in the other matchers)
+#pragma unroll
+            for (int u = 0; u < kInFlight; ++u) {
+                const bool cand = lower[u] <= U && lower[u] < INFINITY;
+                if (__builtin_amdgcn_ballot_w64(cand) != 0) {
+                    double d2 = sq_dist_packed(qraw, a[u]);
+                    d2 = add_xor32(add_xor16(d2));
+                    if (cand) {                                // (only the lane that holds the row's bound)
+                        const int row = 16 * (t0 + u * NW) + r16;
+                        if (better(d2, tag[u], best_d2, best_np)) { second_d2 = best_d2; best_d2 = d2; best_np = tag[u]; best_j = row; }
+                        else second_d2 = fmin(second_d2, d2);
                     }
-                    const float sd = pick == 0 ? dot[0] : pick == 1 ? dot[1] : pick == 2 ? dot[2] : dot[3];
-                    const float rr = pick == 0 ? gram[0] : pick == 1 ? gram[1] : pick == 2 ? gram[2] : gram[3];
-                    const int row = 16 * t + r16;
-                    const bool valid = row < W && tag[u] >= np_lo && tag[u] <= np_hi;
-                    const float f = qq + rr - 2.f * sd, eps = kFilterEps * (qq + rr);
-                    float lower = f - eps, upper = f + eps;
-                    if (!(fabsf(f) < INFINITY)) { lower = -INFINITY; upper = INFINITY; }    // overflow: decided in fp64
-                    if (diag && row < W) s_lower[row] = valid ? lower : INFINITY;
-                    if (diag && valid) U = fminf(U, upper);
                 }
             }
         }
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) U = fminf(U, __shfl_xor(U, off));
-        if (lane == 0) s_u[w] = U;
-        __syncthreads();
-        U = s_u[0];
-#pragma unroll
-        for (int ww = 1; ww < NW; ++ww) U = fminf(U, s_u[ww]);
     }
-    // tier 2: the rows the filter could not rule out, a quad per row, in fp64
-    double best_d2 = INFINITY, second_d2 = INFINITY;           // nearest candidate and the distance of the next one
-    int best_np = -1, best_j = -1;
-    auto row_d2 = [&](int r) {                                 // called by the four lanes of a quad together
-        double q[32];
-        load_query_f64(q_h + 8 * sub, q);
-        u32x4 v[4];
-        const uint16_t* rp = ring_h + (int64_t)r * kHeadDim + 8 * sub;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) v[i] = *reinterpret_cast<const u32x4*>(rp + 32 * i);
-        double d2 = lane_sq_dist(q, v);
-        d2 += __shfl_xor(d2, 1);
-        d2 += __shfl_xor(d2, 2);
-        return d2;
-    };
-    auto reduce_best = [&](double& d2, int& np, int& j, double& second) {      // every thread gets the block's result
-#pragma unroll
-        for (int off = 4; off < 64; off <<= 1) {               // all 4 lanes of a quad hold the same values
-            const double od2 = __shfl_xor(d2, off), osec = __shfl_xor(second, off);
-            const int onp = __shfl_xor(np, off), oj = __shfl_xor(j, off);
-            if (better(od2, onp, d2, np)) { second = fmin(d2, osec); d2 = od2; np = onp; j = oj; }
-            else second = fmin(second, od2);
+    // Block-wide (nearest, next) of the lanes' candidates: few lanes hold one, so a wave walks over those lanes with
+    // v_readlane instead of a 64-lane butterfly; the waves' results meet in shared memory.  Every thread gets the result.
+    auto reduce_best = [&](double& d2, int& np, int& j, double& second, bool holds) {
+        double bd = INFINITY, bs = INFINITY;
+        int bnp = -1, bj = -1;
+        unsigned long long mask = __builtin_amdgcn_ballot_w64(holds);
+        while (mask != 0) {                                    // wave-uniform
+            const int l = __builtin_ctzll(mask);
+            mask &= mask - 1;
+            const double od = readlane_f64(d2, l), os = readlane_f64(second, l);
+            const int onp = __builtin_amdgcn_readlane(np, l), oj = __builtin_amdgcn_readlane(j, l);
+            if (better(od, onp, bd, bnp)) { bs = fmin(bd, os); bd = od; bnp = onp; bj = oj; }
+            else bs = fmin(fmin(bs, os), od);
         }
         __syncthreads();                                       // the arrays may still be read from an earlier call
-        if (lane == 0) { s_d2[w] = d2; s_np[w] = np; s_j[w] = j; s_second[w] = second; }
+        if (lane == 0) { s_d2[w] = bd; s_np[w] = bnp; s_j[w] = bj; s_second[w] = bs; }
         __syncthreads();
         d2 = s_d2[0]; np = s_np[0]; j = s_j[0]; second = s_second[0];
 #pragma unroll
         for (int ww = 1; ww < NW; ++ww) {
             if (better(s_d2[ww], s_np[ww], d2, np)) { second = fmin(d2, s_second[ww]); d2 = s_d2[ww]; np = s_np[ww]; j = s_j[ww]; }
-            else second = fmin(second, s_d2[ww]);
+            else second = fmin(fmin(second, s_second[ww]), s_d2[ww]);
         }
     };
-    for (int r = quad; r < W; r += kRows) {
-        const float lw = s_lower[r];
-        if (lw <= U && lw < INFINITY) {
-            const double d2 = row_d2(r);
-            const int np = npos[r];
-            if (better(d2, np, best_d2, best_np)) { second_d2 = best_d2; best_d2 = d2; best_np = np; best_j = r; }
-            else second_d2 = fmin(second_d2, d2);
-        }
-    }
-    reduce_best(best_d2, best_np, best_j, second_d2);
+    reduce_best(best_d2, best_np, best_j, second_d2, best_np >= 0);
     // tier 3: two fp64 evaluations of one distance agree to ~2^-46 relative, so the order of two candidates, or of the
-    // nearest one and the threshold, can depend on the evaluation only if they lie closer than that.  Then the
-    // candidates in question are summed once more, one lane each, in index order without fused multiply-adds: the
-    // plain left-to-right sum that a reference evaluation of Eq. (accept) takes, so that the decision is the same bit
-    // for bit.  (Exact duplicates in the window come here too, and fall to the tie-break as before.)
+    // nearest one and the threshold, can depend on the evaluation only if they lie closer than that.  Then the window
+    // is scanned once more in fp64 (a quad per row) and the rows in question are summed, one lane each, in index order
+    // without fused multiply-adds: the plain left-to-right sum that a reference evaluation of Eq. (accept) takes, so
+    // that the decision is the same bit for bit.  (Exact duplicates in the window come here too, and fall to the
+    // tie-break as before.)
     if (best_np >= 0 && (second_d2 <= best_d2 * (1.0 + kTieRel) || fabs(best_d2 - p.mv.T2) <= kTieRel * p.mv.T2)) {
         const double bound = best_d2 * (1.0 + kTieRel);
         double e_d2 = INFINITY, e_second = INFINITY;
         int e_np = -1, e_j = -1;
-        for (int r = quad; r < W; r += kRows) {
-            const float lw = s_lower[r];
-            if (lw <= U && lw < INFINITY && row_d2(r) <= bound) {
+        u32x4 qs[4];                                           // the query in the quad layout: chunks sub, sub + 4, ...
+#pragma unroll
+        for (int i = 0; i < 4; ++i) qs[i] = *reinterpret_cast<const u32x4*>(q_h + 8 * sub + 32 * i);
+        for (int r0 = 0; r0 < W; r0 += kRows) {
+            const int r = r0 + quad, rc = min(r, W - 1);
+            u32x4 v[4];
+            const uint16_t* rp = ring_h + (int64_t)rc * kHeadDim;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v[i] = *reinterpret_cast<const u32x4*>(rp + 8 * sub + 32 * i);
+            const int np = npos[rc];
+            double d2 = sq_dist_packed(qs, v);
+            d2 += __shfl_xor(d2, 1);
+            d2 += __shfl_xor(d2, 2);
+            if (r < W && np >= np_lo && np <= np_hi && d2 <= bound) {
                 double e = 0.0;
-                const uint16_t* rp = ring_h + (int64_t)r * kHeadDim;
                 for (int i = 0; i < kHeadDim; ++i) {
                     const double diff = __dsub_rn((double)bits_to_float((uint32_t)q_h[i] << 16), (double)bits_to_float((uint32_t)rp[i] << 16));
                     e = __dadd_rn(e, __dmul_rn(diff, diff));
                 }
-                const int np = npos[r];
                 if (better(e, np, e_d2, e_np)) { e_second = e_d2; e_d2 = e; e_np = np; e_j = r; }
                 else e_second = fmin(e_second, e);
             }
         }
-        reduce_best(e_d2, e_np, e_j, e_second);
+        reduce_best(e_d2, e_np, e_j, e_second, sub == 0 && e_np >= 0);       // the 4 lanes of a quad hold the same values
         best_d2 = e_d2; best_np = e_np; best_j = e_j;
     }
 
@@ -349,11 +372,8 @@ __global__ __launch_bounds__(NT) void hit_kernel(const HitParams p) {
         const float l = s_logit[r];
         if (r < nbr) mx0 = fmaxf(mx0, l); else mx1 = fmaxf(mx1, l);
     }
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        mx0 = fmaxf(mx0, __shfl_xor(mx0, off));
-        mx1 = fmaxf(mx1, __shfl_xor(mx1, off));
-    }
+    mx0 = wave_max_f32(mx0);
+    mx1 = wave_max_f32(mx1);
     if (lane == 0) { s_red[0][w][0] = mx0; s_red[0][w][1] = mx1; }
     __syncthreads();
     float M0 = s_red[0][0][0], M1 = s_red[0][0][1];
@@ -366,11 +386,8 @@ __global__ __launch_bounds__(NT) void hit_kernel(const HitParams p) {
         s_logit[r] = pw;
         if (mid) z0 += pw; else z1 += pw;
     }
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        z0 += __shfl_xor(z0, off);
-        z1 += __shfl_xor(z1, off);
-    }
+    z0 = wave_sum_f32(z0);
+    z1 = wave_sum_f32(z1);
     if (lane == 0) { s_red[1][w][0] = z0; s_red[1][w][1] = z1; }
     __syncthreads();
     float Z0 = 0.f, Z1 = 0.f;
@@ -404,10 +421,8 @@ __global__ __launch_bounds__(NT) void hit_kernel(const HitParams p) {
         }
 #pragma unroll
         for (int j = 0; j < 8; ++j) {                          // lanes l, l^16, l^32, l^48 hold the same columns
-            a0[j] += __shfl_xor(a0[j], 16);
-            a0[j] += __shfl_xor(a0[j], 32);
-            a1[j] += __shfl_xor(a1[j], 16);
-            a1[j] += __shfl_xor(a1[j], 32);
+            a0[j] = add_xor32(add_xor16(a0[j]));
+            a1[j] = add_xor32(add_xor16(a1[j]));
         }
         if (lane < 16) {
 #pragma unroll
