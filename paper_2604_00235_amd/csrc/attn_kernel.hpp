@@ -65,6 +65,7 @@ struct AttnParams {
     int32_t n_mid_slots, n_slots;
     int32_t max_kv_len;
     float scale_log2;            // sm_scale * log2(e)
+    const int32_t* pending;      // [1] heads the matcher left to this kernel, or null: 0 = nothing to do, leave at once
     int32_t* step_chunk;         // [1] tokens per work item of this launch, for the merge kernel (chunk_fixed == 0)
     unsigned long long* st_read; // [batch*Hkv] KV tokens the method streams per group (from the smallest start of all
                                  // its heads); null for full decode
@@ -72,10 +73,8 @@ struct AttnParams {
     unsigned long long* st_split;   // [batch*Hkv] KV tokens this kernel streams (heads the matcher finished excluded)
 };
 
-struct KVTile {
-    u32x4 k[2][4];   // [sub-tile][k-step]  A operands of S = K Q^T
-    u32x4 v[8];      // [e = 4*sub-tile + i] 8 d-columns of token 16*sub + 4i + kg
-};
+// A K/V tile in registers: k[sub-tile][k-step] are the A operands of S = K Q^T; v[4*sub-tile + i] holds 8 d-columns of
+// token 16*sub + 4i + kg.
 
 // Fresh ranges of one KV group: n, band start, smallest / largest start among the heads this kernel serves (gs, gmax),
 // smallest start among all heads (gs_all: what the method streams per KV group, Sec. 5.8 -- a counter only).
@@ -162,6 +161,8 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnParams p) {
     __shared__ int s_prefix[kCap + 1];                       // work items before group q
     __shared__ int s_gs[kCap], s_n[kCap];                    // start of the group's range (-1: nothing to do), kv_len
     __shared__ long long s_sum[4];
+    // every head was finished by the matcher: only the first work-group stays, for the per-group counters
+    if (p.pending != nullptr && *p.pending == 0 && blockIdx.x != 0) return;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int Hkv = p.Hq / p.G, NG = p.batch * Hkv;
     const int P = gridDim.x;
@@ -377,23 +378,32 @@ __device__ __forceinline__ void attn_item(const AttnParams& p, const int C, cons
 #pragma unroll
     for (int i = 0; i < 4; ++i) v_row_b[i] = (uint32_t)(4 * i + kg) * tok_bytes;
     const uint32_t v_col_b = 16u * (uint32_t)r16;
-    auto load_tile = [&](int k, KVTile& T) {
+    // base address of sub-tile u of the wave's k-th tile (rows past the end fold back, see above) and its row limit
+    auto sub_tile = [&](int k, int u, uint32_t& lim_b) {
         const int t0 = (chunk_tile0 + w + 4 * k) * kTileTokens;
+        const bool past = t0 + 16 * u >= n;                   // then u == 1 and t0 < n: the tile intersects [lo, hi)
+        const int tb = past ? t0 : t0 + 16 * u;
+        lim_b = (uint32_t)min(15, n - 1 - tb) * tok_bytes;    // last valid row, in bytes
+        const int pid = __builtin_amdgcn_readlane(mypid, 2 * k + u);
+        return reinterpret_cast<const char*>(kv_g + (int64_t)pid * p.stride_page + (int64_t)(tb & page_mask) * p.stride_tok);
+    };
+    auto load_k = [&](int k, u32x4 (&K)[2][4]) {
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
-            const bool past = t0 + 16 * u >= n;                   // then u == 1 and t0 < n: the tile intersects [lo, hi)
-            const int tb = past ? t0 : t0 + 16 * u;
-            const uint32_t lim_b = (uint32_t)min(15, n - 1 - tb) * tok_bytes;                 // last valid row, in bytes
-            const int pid = __builtin_amdgcn_readlane(mypid, 2 * k + u);
-            const char* base = reinterpret_cast<const char*>(kv_g + (int64_t)pid * p.stride_page +
-                                                             (int64_t)(tb & page_mask) * p.stride_tok);
-            const char* kp = base + (min(k_row_b, lim_b) + k_col_b);
+            uint32_t lim_b;
+            const char* kp = sub_tile(k, u, lim_b) + (min(k_row_b, lim_b) + k_col_b);
 #pragma unroll
-            for (int c = 0; c < 4; ++c) T.k[u][c] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kp + 64 * c));
-            const char* vbase = base + 2 * p.stride_kv;
+            for (int c = 0; c < 4; ++c) K[u][c] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kp + 64 * c));
+        }
+    };
+    auto load_v = [&](int k, u32x4 (&V)[8]) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            uint32_t lim_b;
+            const char* vbase = sub_tile(k, u, lim_b) + 2 * p.stride_kv;
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                T.v[4 * u + i] = __builtin_nontemporal_load(
+                V[4 * u + i] = __builtin_nontemporal_load(
                     reinterpret_cast<const u32x4*>(vbase + (min(v_row_b[i], lim_b) + v_col_b)));
         }
     };
@@ -410,56 +420,61 @@ __device__ __forceinline__ void attn_item(const AttnParams& p, const int C, cons
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    auto compute_tile = [&](int k, const KVTile& T) {
+    // scores of the wave's k-th tile for every head tile: sc[ht][4u + i] = scale * q_head . K_token, log2 domain, masked
+    auto qk = [&](int k, const u32x4 (&K)[2][4], float (&sc)[HT][8]) {
         const int t0 = (chunk_tile0 + w + 4 * k) * kTileTokens;
         const bool need_mask = (t0 < maxstart) || (t0 + kTileTokens > hi);   // wave-uniform
+        // the queries come from shared memory (row = head, 16-byte chunk 4c + kg of k-step c), read again for every
+        // tile: 16 registers per head tile that the loop over work items has no room for
+        asm volatile("" ::: "memory");
 #pragma unroll
         for (int ht = 0; ht < HT; ++ht) {
-            // the tile's queries from shared memory (row = head, 16-byte chunk 4c + kg of k-step c), read again for
-            // every tile: 16 registers that the loop over work items has no room for
-            if constexpr (HT == 1) asm volatile("" ::: "memory");
             bf16x8 qop[4];
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 qop[c] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(
                              s_q + (ht * 16 + r16) * kQRowBytes + 64 * c + 16 * kg));
             }
-            char* const acc_img = reinterpret_cast<char*>(&s_O[w][0]) + 8192 * ht + 16 * l;
-            if constexpr (HT == 2) {
-#pragma unroll
-                for (int j = 0; j < 8; ++j) acc[j] = *reinterpret_cast<const f32x4*>(acc_img + 1024 * j);
-            }
-            float sc[8];
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
                 f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int c = 0; c < 4; ++c)
-                    s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, T.k[u][c]), qop[c], s, 0, 0, 0);
+                    s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, K[u][c]), qop[c], s, 0, 0, 0);
 #pragma unroll
-                for (int i = 0; i < 4; ++i) sc[4 * u + i] = s[i] * p.scale_log2;
+                for (int i = 0; i < 4; ++i) sc[ht][4 * u + i] = s[i] * p.scale_log2;
             }
             if (need_mask) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const int tok = t0 + 16 * (e >> 2) + 4 * (e & 3) + kg;
-                    if (tok < hstart[ht] || tok >= hi) sc[e] = -INFINITY;
+                    if (tok < hstart[ht] || tok >= hi) sc[ht][e] = -INFINITY;
                 }
             }
-            float tmax = sc[0];
+        }
+    };
+    // softmax update and O += P V of the wave's k-th tile, one head tile after the other
+    auto pv = [&](const u32x4 (&V)[8], const float (&sc)[HT][8]) {
 #pragma unroll
-            for (int e = 1; e < 8; ++e) tmax = fmaxf(tmax, sc[e]);
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        for (int ht = 0; ht < HT; ++ht) {
+            char* const acc_img = reinterpret_cast<char*>(&s_O[w][0]) + 8192 * ht + 16 * l;
+            if constexpr (HT == 2) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[j] = *reinterpret_cast<const f32x4*>(acc_img + 1024 * j);
+            }
+            float tmax = sc[ht][0];
+#pragma unroll
+            for (int e = 1; e < 8; ++e) tmax = fmaxf(tmax, sc[ht][e]);
+            tmax = max_xor32(max_xor16(tmax));
             const float m_new = fmaxf(m_run[ht], tmax);
             const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
             const float alpha = exp2_fast(m_run[ht] - m_safe);
-            float pv[8];
+            float pw[8];
             float psum = 0.f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                pv[e] = exp2_fast(sc[e] - m_safe);
-                psum += pv[e];
+                pw[e] = exp2_fast(sc[ht][e] - m_safe);
+                psum += pw[e];
             }
             l_run[ht] = l_run[ht] * alpha + psum;
             if (__builtin_amdgcn_ballot_w64(m_new > m_run[ht]) != 0) {     // some head's max moved: rescale O
@@ -475,24 +490,23 @@ __device__ __forceinline__ void attn_item(const AttnParams& p, const int C, cons
             uint32_t hb[8], lb[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const uint32_t bits = float_to_bits(pv[e]);
+                const uint32_t bits = float_to_bits(pw[e]);
                 hb[e] = bits;
-                lb[e] = float_to_bits(pv[e] - bits_to_float(bits & 0xffff0000u));
+                lb[e] = float_to_bits(pw[e] - bits_to_float(bits & 0xffff0000u));
             }
             u32x4 a_hi, a_lo;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                a_hi[q] = pack_hi16(hb[2 * q], hb[2 * q + 1]);
-                a_lo[q] = pack_hi16(lb[2 * q], lb[2 * q + 1]);
+            for (int q4 = 0; q4 < 4; ++q4) {
+                a_hi[q4] = pack_hi16(hb[2 * q4], hb[2 * q4 + 1]);
+                a_lo[q4] = pack_hi16(lb[2 * q4], lb[2 * q4 + 1]);
             }
-            // O += P V (with two head tiles the V operands are formed once per tile: registers are the scarcer resource)
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const int c = j >> 1;
                 u32x4 bj;
 #pragma unroll
-                for (int q = 0; q < 4; ++q)
-                    bj[q] = (j & 1) ? pack_hi16(T.v[2 * q][c], T.v[2 * q + 1][c]) : pack_lo16(T.v[2 * q][c], T.v[2 * q + 1][c]);
+                for (int q4 = 0; q4 < 4; ++q4)
+                    bj[q4] = (j & 1) ? pack_hi16(V[2 * q4][c], V[2 * q4 + 1][c]) : pack_lo16(V[2 * q4][c], V[2 * q4 + 1][c]);
                 const bf16x8 bop = __builtin_bit_cast(bf16x8, bj);
                 acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a_hi), bop, acc[j], 0, 0, 0);
                 acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a_lo), bop, acc[j], 0, 0, 0);
@@ -507,23 +521,50 @@ __device__ __forceinline__ void attn_item(const AttnParams& p, const int C, cons
         }
     };
 
-    // two-deep software pipeline: the next tile's loads are in flight while the current one is computed.
-    // The steady-state loop has no conditional loads; the last one or two tiles are peeled.
-    KVTile ta, tb;
+    float sc[HT][8];
     int k = k_first;
-    if (k < k_end) load_tile(k, ta);
-    for (; k + 2 < k_end; k += 2) {
-        load_tile(k + 1, tb);
-        compute_tile(k, ta);
-        load_tile(k + 2, ta);
-        compute_tile(k + 1, tb);
-    }
-    if (k_end - k == 2) {
-        load_tile(k + 1, tb);
-        compute_tile(k, ta);
-        compute_tile(k + 1, tb);
-    } else if (k_end - k == 1) {
-        compute_tile(k, ta);
+    if constexpr (HT == 1) {
+        // Two-deep software pipeline over whole tiles: the next tile's 16 loads are in flight while the current one
+        // is computed.  The steady-state loop has no conditional loads; the last one or two tiles are peeled.
+        u32x4 ka[2][4], va[8], kb[2][4], vb[8];
+        if (k < k_end) { load_k(k, ka); load_v(k, va); }
+        for (; k + 2 < k_end; k += 2) {
+            load_k(k + 1, kb); load_v(k + 1, vb);
+            qk(k, ka, sc); pv(va, sc);
+            load_k(k + 2, ka); load_v(k + 2, va);
+            qk(k + 1, kb, sc); pv(vb, sc);
+        }
+        if (k_end - k == 2) {
+            load_k(k + 1, kb); load_v(k + 1, vb);
+            qk(k, ka, sc); pv(va, sc);
+            qk(k + 1, kb, sc); pv(vb, sc);
+        } else if (k_end - k == 1) {
+            qk(k, ka, sc); pv(va, sc);
+        }
+    } else {
+        // Two head tiles leave no room for two whole K/V tiles: K and V are pipelined separately.  While the scores of
+        // tile k are formed from K(k), K(k+1) is in flight; its V(k+1) is requested when K(k)'s registers are free and
+        // arrives during the softmax and P V of tile k.  Three half-tiles are live at any time instead of four.
+        // (Loads past the wave's last tile re-read that tile: every load stays unconditional.)
+        u32x4 ka[2][4], va[8], kb[2][4], vb[8];
+        const int k_last = k_end - 1;
+        if (k < k_end) { load_k(k, ka); load_v(k, va); }
+        for (; k + 2 <= k_end; k += 2) {
+            load_k(k + 1, kb);
+            qk(k, ka, sc);
+            __builtin_amdgcn_sched_barrier(0);
+            load_v(k + 1, vb);
+            pv(va, sc);
+            load_k(min(k + 2, k_last), ka);
+            qk(k + 1, kb, sc);
+            __builtin_amdgcn_sched_barrier(0);
+            load_v(min(k + 2, k_last), va);
+            pv(vb, sc);
+        }
+        if (k < k_end) {
+            qk(k, ka, sc);
+            pv(va, sc);
+        }
     }
 
     // merge the 4 waves' states through LDS and write the normalised partial of every real head
@@ -542,8 +583,7 @@ __device__ __forceinline__ void attn_item(const AttnParams& p, const int C, cons
 #pragma unroll
     for (int ht = 0; ht < HT; ++ht) {
         float lsum = l_run[ht];
-        lsum += __shfl_xor(lsum, 16);
-        lsum += __shfl_xor(lsum, 32);
+        lsum = add_xor32(add_xor16(lsum));
         if (kg == 0) {
             s_m[w][ht * 16 + r16] = m_run[ht];
             s_l[w][ht * 16 + r16] = lsum;

@@ -70,6 +70,14 @@ __device__ __forceinline__ float add_xor32(float x) {
     const auto r = __builtin_amdgcn_permlane32_swap(float_to_bits(x), float_to_bits(x), false, false);
     return bits_to_float(r[0]) + bits_to_float(r[1]);
 }
+__device__ __forceinline__ float max_xor16(float x) {
+    const auto r = __builtin_amdgcn_permlane16_swap(float_to_bits(x), float_to_bits(x), false, false);
+    return fmaxf(bits_to_float(r[0]), bits_to_float(r[1]));
+}
+__device__ __forceinline__ float max_xor32(float x) {
+    const auto r = __builtin_amdgcn_permlane32_swap(float_to_bits(x), float_to_bits(x), false, false);
+    return fmaxf(bits_to_float(r[0]), bits_to_float(r[1]));
+}
 __device__ __forceinline__ double add_xor16(double x) {
     const uint64_t u = __builtin_bit_cast(uint64_t, x);
     const auto lo = __builtin_amdgcn_permlane16_swap((uint32_t)u, (uint32_t)u, false, false);

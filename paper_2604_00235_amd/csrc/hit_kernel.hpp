@@ -50,6 +50,7 @@ struct HitParams {
     int32_t* ring_npos;          // [slots, Hq, W]; 0 = empty entry
     MatchPartial* part;          // [batch*Hq] nearest entry of the head's window (one slice)
     int32_t* head_start;         // [batch*Hq] start of the head's fresh range, | kHeadDone if finished here
+    int32_t* pending;            // [1] number of heads of this step left to the split-K path (the merge kernel clears it)
     unsigned long long* st_steps;   // [2]: decode steps, head-steps
     unsigned long long* st_hits; // per (b, h) accumulators
     unsigned long long* st_gap;
@@ -295,6 +296,7 @@ __global__ __launch_bounds__(NT, NT == 256 ? 4 : 1) void hit_kernel(const HitPar
         }
         p.part[bh] = MatchPartial{best_d2, best_np, best_j};
         p.head_start[bh] = s | (fuse ? kHeadDone : 0);
+        if (!fuse) atomicAdd(p.pending, 1);
         if (p.out_match_pos) p.out_match_pos[bh] = hit ? best_np : -1;
         if (p.out_match_d2) p.out_match_d2[bh] = best_d2;
         if (hit) {                      // one writer per address and step: the atomics only make the adds fire-and-forget

@@ -82,7 +82,8 @@ int default_chunk(int64_t groups, int64_t max_kv_len, int heads_per_group) {
     return chunk;
 }
 
-constexpr int64_t kPlanBytes = 256;      // [0]: tokens per work item the attention kernel chose at its last launch
+constexpr int64_t kPlanBytes = 256;      // ints: [0] tokens per work item the attention kernel chose at its last launch,
+                                         // [16] heads of the current step that the matcher left to the split-K path
 
 struct Layout {            // derived sizes, pure host arithmetic
     int G, chunk_fixed, chunk_min, n_mid_slots, n_band_slots, n_slots, page_shift, max_split;
@@ -293,6 +294,7 @@ int launch_attention(mac_attn_ctx* ctx, const mac_attn_step_args* a, bool mac_mo
     p.max_kv_len = c.max_kv_len;
     p.scale_log2 = ctx->sm_scale * mac::kLog2e;
     p.step_chunk = ctx->plan;
+    p.pending = (mac_mode && !c.group_match) ? ctx->plan + 16 : nullptr;
     const int64_t bh = (int64_t)c.max_batch * c.num_q_heads;
     const int64_t bg = (int64_t)c.max_batch * c.num_kv_heads;
     p.st_read = mac_mode ? ctx->stats + 4 * bh : nullptr;
@@ -339,6 +341,7 @@ mac::MergeParams merge_params(mac_attn_ctx* ctx, const mac_attn_step_args* a, bo
     p.band = mac_mode ? c.band : 0;
     p.chunk_fixed = L.chunk_fixed;
     p.step_chunk = ctx->plan;
+    p.pending = (mac_mode && !c.group_match) ? ctx->plan + 16 : nullptr;
     p.n_mid_slots = L.n_mid_slots;
     p.n_slots = L.n_slots;
     p.max_kv_len = c.max_kv_len;
@@ -586,6 +589,7 @@ int mac_attn_decode_step(mac_attn_ctx* ctx, const mac_attn_step_args* args, void
         p.ring_npos = ctx->ring_npos;
         p.part = ctx->m_part;
         p.head_start = ctx->head_start;
+        p.pending = ctx->plan + 16;
         p.st_steps = st_steps;
         p.st_hits = ctx->stats;
         p.st_gap = ctx->stats + bh;

@@ -61,6 +61,7 @@ struct MergeParams {
     int32_t Hq, G, W, band, n_mid_slots, n_slots, max_kv_len;
     int32_t chunk_fixed;         // > 0: tokens per work item of the attention kernel, fixed by the caller;
     const int32_t* step_chunk;   // 0: read here what the attention kernel chose for this step
+    int32_t* pending;            // the matcher's count of heads left to the split-K path: cleared here for the next step; or null
 };
 
 // 256 threads per (request, head).  Thread (c = tid/32, q = tid%32) accumulates the partials
@@ -114,6 +115,7 @@ __device__ __forceinline__ void merge_head(const MergeParams& p, const Writeback
     const int tid = threadIdx.x;
     const int c = tid >> 5, q = tid & 31;
     const int bh = b * p.Hq + h;
+    if (bh == 0 && threadIdx.x == 0 && p.pending != nullptr) *p.pending = 0;
     if (p.head_start != nullptr && (p.head_start[bh] & kHeadDone)) return;     // the whole work-group: before any barrier
     const int n = clampi(p.kv_lens[b], 0, p.max_kv_len);
     const int nb = n - p.band > 0 ? n - p.band : 0;
