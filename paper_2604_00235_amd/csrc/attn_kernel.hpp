@@ -248,9 +248,12 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnParams p) {
     __syncthreads();
     total = __builtin_amdgcn_readfirstlane(s_prefix[NG]);
 
-    // ---- work items: item, item + gridDim.x, ...  (the items of a launch have the same size but for the ends of the
-    // groups' ranges, so a fixed assignment balances as well as handing them out one by one from a counter did:
-    // measured 433 vs 438 us on 32 groups of 131072 tokens)
+    // ---- work items: item, item + gridDim.x, ...  Handing the items out one by one from a counter (requested before
+    // an item's epilogue, so that its latency is hidden) was measured against this fixed assignment with 2 to 8 items
+    // per work-group: never faster (32 groups of 131072 tokens: 337 us at 2, 360 us at 8; fixed: 337 us; 64 groups of
+    // 32768: 182 us at best against 177 us; 16 groups of 65536 with 32 heads each: 133 us against 111 us).  Single
+    // work-groups do finish a third earlier than others, but because they share the memory system unevenly, not
+    // because work is left over: what counts is few, long items in whole rounds.
     for (int item = blockIdx.x; item < total; item += P) {
         int lo_q = 0, hi_q = NG;                             // the group: largest q with s_prefix[q] <= item
         while (hi_q - lo_q > 1) {
@@ -599,25 +602,32 @@ __device__ __forceinline__ void attn_item(const AttnParams& p, const int C, cons
         }
     }
     __syncthreads();
+    // weights of the four waves' states per head, once per head (thread h): s_l[w][h] <- 2^(m_w - M) / L, s_m[0][h] <- LSE
+    if (tid < HT * 16) {
+        const int h = tid;
+        const float M = fmaxf(fmaxf(s_m[0][h], s_m[1][h]), fmaxf(s_m[2][h], s_m[3][h]));
+        float f[4], L = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < 4; ++ww) {
+            f[ww] = M == -INFINITY ? 0.f : exp2_fast(s_m[ww][h] - M);
+            L += s_l[ww][h] * f[ww];
+        }
+        const float inv = L > 0.f ? 1.f / L : 0.f;
+#pragma unroll
+        for (int ww = 0; ww < 4; ++ww) s_l[ww][h] = f[ww] * inv;
+        s_m[0][h] = L > 0.f ? (M + __log2f(L)) * kLn2 : -INFINITY;
+    }
+    __syncthreads();
+#pragma unroll 4
     for (int idx = tid; idx < G * kHeadDim; idx += 256) {
         const int h = idx >> 7, dd = idx & (kHeadDim - 1);
         if (s_skip[h]) continue;
-        float M = fmaxf(fmaxf(s_m[0][h], s_m[1][h]), fmaxf(s_m[2][h], s_m[3][h]));
-        float o = 0.f, lse = -INFINITY;
-        if (M != -INFINITY) {
-            float L = 0.f, a = 0.f;
+        float o = 0.f;
 #pragma unroll
-            for (int ww = 0; ww < 4; ++ww) {
-                const float f = exp2_fast(s_m[ww][h] - M);
-                L += s_l[ww][h] * f;
-                a += s_O[ww][h * kHeadDim + dd] * f;
-            }
-            o = a / L;
-            lse = (M + __log2f(L)) * kLn2;
-        }
+        for (int ww = 0; ww < 4; ++ww) o += s_O[ww][h * kHeadDim + dd] * s_l[ww][h];
         const int64_t row = (int64_t)(hbase + h) * p.n_slots + slot;
         p.part_O[row * kHeadDim + dd] = o;
-        if (dd == 0) p.part_lse[row] = lse;
+        if (dd == 0) p.part_lse[row] = s_m[0][h];
     }
 }
 
