@@ -26,10 +26,23 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 KV_BYTES_PER_TOKEN_HEAD = 512   # K row + V row, bf16, d = 128
-# HBM bytes per attention-kernel launch from two rocprofv3 --pmc runs of this command with its default arguments
-# (FETCH_SIZE x 2.0000 + WRITE_SIZE x 1.0000, scale factors from a 1 GiB copy; profiles/attn_kernel_C3_128k_pmc_traffic.txt).
-# Only valid for exactly that workload and step range, so it is reported for no other.
-PROFILED_TRAFFIC = {("C3_rho97", 40, 8): {"mac": 2.03274e9, "full": 2.16283e9}}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "attn_kernel_hbm_traffic_ratios.txt")
+
+
+def traffic_ratios():
+    """(config, mode) -> measured HBM traffic / algorithmic bytes of the attention kernel, from the tracked rocprofv3
+    --pmc summary (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy kernel of known size; lines `ratio <config> <mode>
+    <value>`).  The counters cannot be read from inside this process, so the line reports traffic = ratio x the
+    algorithmic bytes of this run, names the file, and reports null for a config that was never profiled."""
+    out = {}
+    try:
+        for ln in open(TRAFFIC_FILE):
+            f = ln.split()
+            if len(f) == 4 and f[0] == "ratio":
+                out[(f[1], f[2])] = float(f[3])
+    except OSError:
+        pass
+    return out
 
 
 def log(msg: str):
@@ -97,29 +110,60 @@ def run_config(name: str, steps: int, warmup: int, torch, mb, wl_mod, keep_kv=No
     f_us, f_n = mb.mac_attn_kernel_us(mac.ctx)
     mb.mac_attn_set_timing(mac.ctx, False)
 
-    # --- the same MAC step replayed from one captured HIP graph (static input buffers refreshed by device copies,
-    # which are inside the timed region), to show what launch overhead is left in the eager figure
-    graph_us = None
+    # --- the same MAC steps replayed from ONE captured HIP graph.  The graph holds the whole step: three small device
+    # kernels that fetch step i's inputs from tensors preloaded with all steps (index_select by a device-side step
+    # counter, which the graph also advances) and the library's launches, so a replay needs no host work but
+    # hipGraphLaunch.  The eager figure beside it runs exactly the same device work launch by launch.
+    graph_us = eager_same_us = None
     if use_graph:
+        n_g = warmup + steps
+        all_qp = torch.stack([i[0] for i in inputs[:n_g]])
+        all_qr = torch.stack([i[1] for i in inputs[:n_g]])
+        all_kl = torch.stack([i[2] for i in inputs[:n_g]])
         qp_s, qr_s, kl_s = (t.clone() for t in inputs[0])
+        idx = torch.zeros(1, dtype=torch.int64, device="cuda:0")
         g_args = mac.make_args(kv_lens=kl_s, q_rope=qr_s, kv_pages=wl.kv_pages, strides=wl.strides,
                                block_table=wl.block_table, out=out, slot_ids=wl.slot_ids, q_pre=qp_s)
-        mac.reset()
-        for (qp, qr, kl) in inputs[:warmup]:
-            qp_s.copy_(qp); qr_s.copy_(qr); kl_s.copy_(kl)
-            mac.decode_step(g_args, stream)
-        torch.cuda.synchronize()
-        g = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g, stream=torch.cuda.Stream()):
-            mac.decode_step(g_args, torch.cuda.current_stream().cuda_stream)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for (qp, qr, kl) in inputs[warmup:warmup + steps]:
-            qp_s.copy_(qp); qr_s.copy_(qr); kl_s.copy_(kl)
-            g.replay()
-        torch.cuda.synchronize()
-        graph_us = 1e6 * (time.perf_counter() - t0) / steps
-        del g
+
+        def one_step(hs):
+            torch.index_select(all_qp, 0, idx, out=qp_s.unsqueeze(0))
+            torch.index_select(all_qr, 0, idx, out=qr_s.unsqueeze(0))
+            torch.index_select(all_kl, 0, idx, out=kl_s.unsqueeze(0))
+            mac.decode_step(g_args, hs)
+            idx.add_(1)
+
+        side = torch.cuda.Stream()
+        for mode in ("eager", "graph"):
+            mac.reset()
+            idx.zero_()
+            torch.cuda.synchronize()
+            with torch.cuda.stream(side):
+                hs = side.cuda_stream
+                for _ in range(warmup):
+                    one_step(hs)
+                side.synchronize()
+                if mode == "eager":
+                    t0 = time.perf_counter()
+                    for _ in range(steps):
+                        one_step(hs)
+                    side.synchronize()
+                    eager_same_us = 1e6 * (time.perf_counter() - t0) / steps
+            if mode == "graph":
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=side):
+                    one_step(torch.cuda.current_stream().cuda_stream)
+                torch.cuda.synchronize()
+                mac.stats(reset=True)
+                t0 = time.perf_counter()
+                for _ in range(steps):
+                    g.replay()
+                torch.cuda.synchronize()
+                graph_us = 1e6 * (time.perf_counter() - t0) / steps
+                st_g = mac.stats(reset=True)
+                assert st_g["steps"] == steps, st_g        # capture ran nothing, every replay ran one step
+                del g
+        log(f"[bench] {name}: one captured graph per step {graph_us:.1f} us/step; the same device work launched "
+            f"eagerly {eager_same_us:.1f} us/step")
     mac.close()
 
     n_mid = cfg.context + warmup + steps // 2
@@ -143,7 +187,7 @@ def run_config(name: str, steps: int, warmup: int, torch, mb, wl_mod, keep_kv=No
         "fused_kv_bytes_per_step": KV_BYTES_PER_TOKEN_HEAD * st2["kv_tokens_fused"] / k_n,
         "full_attn_bytes_per_launch": KV_BYTES_PER_TOKEN_HEAD * full_tokens / f_n,
         "kv_len_mid": n_mid,
-        "graph_us_per_step": graph_us,
+        "graph_us_per_step": graph_us, "eager_same_work_us_per_step": eager_same_us,
     }
     res["attn_GBps"] = res["attn_bytes_per_launch"] / (res["kernel_us"]["attention"] * 1e-6) / 1e9
     res["full_attn_GBps"] = res["full_attn_bytes_per_launch"] / (res["full_kernel_us"]["attention"] * 1e-6) / 1e9
@@ -348,8 +392,8 @@ def cpu_baseline(name: str, torch, wl_mod, sample_steps: int):
     dt = time.perf_counter() - t0
     hit = orc.stats.hits / max(1, orc.stats.head_steps)
     return {"value": 1e6 * dt / sample_steps, "unit": "us/step", "cores": num_threads(), "kind": "oracle",
-            "sample": f"first {sample_steps} MAC decode steps of {name} from empty rings (fp64, OpenMP over "
-                      f"(request, head)); hit rate in the sample {100 * hit:.0f}%"}
+            "sample": f"first {sample_steps} MAC decode steps of {name} from empty rings (plain C fp64 oracle built with "
+                      f"gcc -O2, no -march=native, OpenMP over (request, head)); hit rate in the sample {100 * hit:.0f}%"}
 
 
 def main():
@@ -374,8 +418,9 @@ def main():
                     help="also run the synthetic analogue of the rectification-error heat-map (error of MAC against full "
                          "attention over reuse gap x band width) and add it as 'err_table'")
     ap.add_argument("--graph", action="store_true",
-                    help="also time the headline config replayed from one captured HIP graph (off by default: on this "
-                         "ROCm a replay costs more than the three eager launches it replaces)")
+                    help="also time the headline config replayed from one captured HIP graph per step (input refresh, "
+                         "the library's launches and the step counter all inside the graph), beside the same device "
+                         "work launched eagerly")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (known traffic) so that a rocprofv3 --pmc run of this "
                          "command can scale FETCH_SIZE / WRITE_SIZE")
@@ -413,7 +458,10 @@ def main():
         del src, dst
 
     cfg = wl_mod.CONFIGS[a.config]
-    traffic = PROFILED_TRAFFIC.get((a.config, a.steps, a.warmup), {})
+    ratios = traffic_ratios()
+    r_mac, r_full = ratios.get((a.config, "mac")), ratios.get((a.config, "full"))
+    traffic_src = (os.path.relpath(TRAFFIC_FILE, ROOT) if r_mac is not None else
+                   f"null: {a.config} has no rocprofv3 --pmc record in {os.path.relpath(TRAFFIC_FILE, ROOT)}")
     line = {
         "metric": "decode_attention_us_per_step", "value": round(head["us_per_step"], 2), "unit": "us/step",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(head["us_per_step"] / 1e3, 5),
@@ -429,16 +477,21 @@ def main():
         "achieved_hbm_GBps": round(head["attn_GBps"], 1),
         "effective_hbm_GBps": round(head["effective_GBps"], 1),
         "graph_replay_us_per_step": None if head["graph_us_per_step"] is None else round(head["graph_us_per_step"], 2),
+        "eager_same_work_us_per_step": (None if head["eager_same_work_us_per_step"] is None
+                                        else round(head["eager_same_work_us_per_step"], 2)),
         "kernel_us": {k: round(v, 2) for k, v in head["kernel_us"].items()},
         "roofline": {
             "bound": "hbm", "kernel": "attn_kernel (band+tail / full split-K attention) inside mac_attn_decode_step",
             "achieved": round(head["attn_GBps"], 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-            "frac": round(head["attn_GBps"] / HBM_PEAK_GBPS, 4), "traffic": traffic.get("mac"),
+            "frac": round(head["attn_GBps"] / HBM_PEAK_GBPS, 4),
+            "traffic": None if r_mac is None else round(r_mac * head["attn_bytes_per_launch"]),
+            "traffic_over_algorithmic": r_mac, "traffic_source": traffic_src,
             "bytes_per_launch": round(head["attn_bytes_per_launch"]), "us_per_launch": round(head["kernel_us"]["attention"], 2),
         },
         "full_decode_roofline": {
             "achieved": round(head["full_attn_GBps"], 1), "frac": round(head["full_attn_GBps"] / HBM_PEAK_GBPS, 4),
-            "traffic": traffic.get("full"),
+            "traffic": None if r_full is None else round(r_full * head["full_attn_bytes_per_launch"]),
+            "traffic_over_algorithmic": r_full,
             "bytes_per_launch": round(head["full_attn_bytes_per_launch"]),
             "us_per_launch": round(head["full_kernel_us"]["attention"], 2),
         },
