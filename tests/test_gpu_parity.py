@@ -294,3 +294,64 @@ def test_memory_the_request_does_not_own_may_hold_nan(page_size, context):
         pages.copy_(clean)                                              # the poisoned rows are later tokens' data
     assert hits > 0
     run.mac.close()
+
+
+def test_candidates_that_tie_to_rounding_are_decided_as_the_index_order_sum_decides():
+    """Two window entries whose distances to the query are equal as real numbers (one is a permutation of the other, the
+    query is zero) or differ far below the rounding error of a 128-term fp64 sum (one small element nudged).  The
+    terms span ~2^60, so the fp64 value depends on the order of summation, and which entry is "nearest" is decided by
+    that rounding.  The reference takes the plain left-to-right sum; the library has to come to the same decision and
+    the same distance bit for bit (its matcher re-sums such candidates in index order), at every such step."""
+    from tests.gpu_harness import DeviceRun, check_rows
+    from tests.helpers import make_oracle
+    cfg = WorkloadConfig(name="neartie", batch=2, num_q_heads=4, num_kv_heads=2, context=50, steps=30, window=2, band=8,
+                         threshold=1e30, rho=0.9, seed=51)
+    wl = Workload(cfg, device="cuda:0")
+    run = DeviceRun(cfg, wl, chunk_tokens=32)
+    orc = make_oracle(cfg, wl)
+    kvp, bt, slots = bf16_bits(wl.kv_pages), wl.block_table.cpu().numpy(), wl.slot_ids.cpu().numpy()
+    rng = np.random.default_rng(7)
+
+    def seq_sum(row):                                  # the left-to-right fp64 sum of squares, as the reference forms it
+        acc = np.float64(0.0)
+        for x in row.astype(np.float64):
+            acc = acc + x * x
+        return acc
+
+    order_matters = decided_by_rounding = 0
+    base = None
+    for s, (q_pre, q_rope, kv_lens) in enumerate(wl):
+        shape = tuple(q_pre.shape)
+        if s % 3 == 0:                                 # bf16-exact values (8 significant bits) over 26 binades
+            e = rng.integers(-20, 7, size=shape)
+            m = rng.integers(0, 128, size=shape)
+            sign = rng.choice([-1.0, 1.0], size=shape)
+            base = sign * (1.0 + m / 128.0) * np.exp2(e)
+            rows = base
+        elif s % 3 == 1:                               # the same multiset in another order; every other head: one small element nudged
+            rows = np.stack([np.stack([rng.permutation(base[b, h]) for h in range(shape[1])]) for b in range(shape[0])])
+            for b in range(shape[0]):
+                for h in range(1, shape[1], 2):
+                    i = int(np.argmin(np.abs(rows[b, h])))
+                    x = rows[b, h, i]
+                    ulp = np.exp2(np.floor(np.log2(abs(x))) - 7)            # one step of the 8-bit significand
+                    rows[b, h, i] = x + np.sign(x) * ulp
+            for b in range(shape[0]):
+                for h in range(shape[1]):
+                    a, c = seq_sum(base[b, h]), seq_sum(rows[b, h])
+                    order_matters += int(a != seq_sum(np.sort(base[b, h])))
+                    decided_by_rounding += int(a != c and abs(a - c) <= 2.0 ** -44 * a)
+        else:
+            rows = np.zeros(shape)
+        q_pre = torch.tensor(rows, dtype=torch.float32).to(torch.bfloat16).to("cuda:0")
+        assert torch.equal(q_pre.float().cpu(), torch.tensor(rows, dtype=torch.float32)), "not exact in bf16"
+        lens = kv_lens.cpu().numpy()
+        g_out, g_lse, g_pos, g_d2 = run.mac_step(q_pre, q_rope, kv_lens)
+        ref = orc.mac_step(slots, lens, bf16_bits(q_pre), bf16_bits(q_rope), kvp, bt)
+        assert np.array_equal(g_pos, ref["match_pos"]), f"step {s}: {g_pos.tolist()} vs {ref['match_pos'].tolist()}"
+        if s % 3 == 2:
+            assert np.array_equal(g_d2, ref["d2"]), f"step {s}: distances differ in the last bits"
+            assert (g_pos >= 0).all()
+        check_rows(g_out, ref["out"], f"neartie step {s}")
+    assert order_matters > 0 and decided_by_rounding > 0, (order_matters, decided_by_rounding)
+    run.mac.close()
