@@ -60,7 +60,7 @@ struct AttnParams {
     int32_t page_shift;          // log2(page_size)
     int32_t band;                // B; 0 for full decode (no band work items)
     int32_t chunk_fixed;         // > 0: tokens per work item fixed by the caller (multiple of 32, <= 4096);
-                                 // 0: chosen per launch from the work the step has, within [chunk_min, 4096]
+                                 // 0: chosen per launch from the work the step has, within [chunk_min, 8192]
     int32_t chunk_min;           // multiple of 32; the partial slots are laid out for it
     int32_t n_mid_slots, n_slots;
     int32_t max_kv_len;
@@ -118,7 +118,7 @@ __device__ __forceinline__ GroupSpan group_span(const AttnParams& p, int b, int 
 __device__ __forceinline__ int mid_items(const GroupSpan& s, int C) { return s.nb > s.gs ? (s.nb + C - 1) / C - s.gs / C : 0; }
 __device__ __forceinline__ int band_items(const GroupSpan& s, int C) { return s.n > s.nb ? (s.n + C - 1) / C - s.nb / C : 0; }
 
-constexpr int kAttnChunkMax = 4096;      // tokens per work item at most (a wave's page ids sit one per lane: 32 tiles x 2)
+constexpr int kAttnChunkMax = 8192;      // tokens per work item at most (a wave's page ids sit one per lane in two registers)
 
 template <int HT> struct AttnCaps { static constexpr int kMaxGroups = HT == 1 ? 2048 : 256; };
 
@@ -298,15 +298,16 @@ __device__ __forceinline__ void attn_item(const AttnParams& p, const int C, cons
     const int slot = is_mid ? x : p.n_mid_slots + (item_k - n_mid);
     if (lo >= hi) return;                                    // (the plan lists no empty item)
 
-    // Page ids of this wave's 16-token sub-tiles, one per lane: lane i <-> (k = i/2, sub-tile i%2), where the
-    // wave's k-th tile of the chunk is chunk_tile0 + w + 4k.
+    // Page ids of this wave's 16-token sub-tiles, one per lane and register: lane i of register j <-> (k = 32j + i/2,
+    // sub-tile i%2), where the wave's k-th tile of the chunk is chunk_tile0 + w + 4k.
     const int pk = l >> 1, pu = l & 1;
     const int chunk_tile0 = x * tiles_per_chunk;
-    int mypid = 0;
-    {
-        const int tok = (chunk_tile0 + w + 4 * pk) * kTileTokens + 16 * pu;
-        if (w + 4 * pk < tiles_per_chunk)
-            mypid = p.block_table[(int64_t)b * p.bt_stride + min(tok >> p.page_shift, p.bt_stride - 1)];
+    int mypid[2] = {0, 0};
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int tok = (chunk_tile0 + w + 4 * (pk + 32 * j)) * kTileTokens + 16 * pu;
+        if (w + 4 * (pk + 32 * j) < tiles_per_chunk)
+            mypid[j] = p.block_table[(int64_t)b * p.bt_stride + min(tok >> p.page_shift, p.bt_stride - 1)];
     }
     int my_start[HT];                                        // start of the head this lane holds in each head tile,
 #pragma unroll                                               // | kHeadDone if the head needs nothing (or does not exist)
@@ -356,14 +357,15 @@ __device__ __forceinline__ void attn_item(const AttnParams& p, const int C, cons
     const int tt_lo = lo >> 5, tt_hi = (hi - 1) >> 5;
     const int d_lo = tt_lo - chunk_tile0 - w, d_hi = tt_hi - chunk_tile0 - w;
     const int k_first = d_lo > 0 ? (d_lo + 3) >> 2 : 0;
-    const int k_end = d_hi >= 0 ? (d_hi >> 2) + 1 : 0;        // one past the last; <= 32 because chunk <= 4096
+    const int k_end = d_hi >= 0 ? (d_hi >> 2) + 1 : 0;        // one past the last; <= 64 because chunk <= 8192
     // A sub-tile wholly past the end (only the second one of a request's last tile can be) has no table entry of its
     // own: it re-reads the tile's first sub-tile, whose rows are real data of this request (its scores are masked, but
     // its V rows still enter the P V product with weight 0, so they must be finite: no page the request does not own is
     // ever touched).
-    {
-        const int first_sub = __shfl(mypid, l & ~1);
-        if ((chunk_tile0 + w + 4 * pk) * kTileTokens + 16 * pu >= n) mypid = first_sub;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int first_sub = __shfl(mypid[j], l & ~1);
+        if ((chunk_tile0 + w + 4 * (pk + 32 * j)) * kTileTokens + 16 * pu >= n) mypid[j] = first_sub;
     }
     const int page_mask = (1 << p.page_shift) - 1;
     const uint16_t* kv_g = p.kv_pages + (int64_t)g * p.stride_head;
@@ -387,7 +389,7 @@ __device__ __forceinline__ void attn_item(const AttnParams& p, const int C, cons
         const bool past = t0 + 16 * u >= n;                   // then u == 1 and t0 < n: the tile intersects [lo, hi)
         const int tb = past ? t0 : t0 + 16 * u;
         lim_b = (uint32_t)min(15, n - 1 - tb) * tok_bytes;    // last valid row, in bytes
-        const int pid = __builtin_amdgcn_readlane(mypid, 2 * k + u);
+        const int pid = k < 32 ? __builtin_amdgcn_readlane(mypid[0], 2 * k + u) : __builtin_amdgcn_readlane(mypid[1], 2 * (k - 32) + u);
         return reinterpret_cast<const char*>(kv_g + (int64_t)pid * p.stride_page + (int64_t)(tb & page_mask) * p.stride_tok);
     };
     auto load_k = [&](int k, u32x4 (&K)[2][4]) {
@@ -423,20 +425,27 @@ __device__ __forceinline__ void attn_item(const AttnParams& p, const int C, cons
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+    bf16x8 qreg[4];                                           // HT == 1: this lane's B operands of S = K Q^T
+    if constexpr (HT == 1) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            qreg[c] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(s_q + r16 * kQRowBytes + 64 * c + 16 * kg));
+    }
     // scores of the wave's k-th tile for every head tile: sc[ht][4u + i] = scale * q_head . K_token, log2 domain, masked
     auto qk = [&](int k, const u32x4 (&K)[2][4], float (&sc)[HT][8]) {
         const int t0 = (chunk_tile0 + w + 4 * k) * kTileTokens;
         const bool need_mask = (t0 < maxstart) || (t0 + kTileTokens > hi);   // wave-uniform
-        // the queries come from shared memory (row = head, 16-byte chunk 4c + kg of k-step c), read again for every
-        // tile: 16 registers per head tile that the loop over work items has no room for
-        asm volatile("" ::: "memory");
+        // With two head tiles the queries come from shared memory (row = head, 16-byte chunk 4c + kg of k-step c), read
+        // again for every tile: 32 registers that are not to spare there.  One head tile keeps them in registers.
+        if constexpr (HT == 2) asm volatile("" ::: "memory");
 #pragma unroll
         for (int ht = 0; ht < HT; ++ht) {
             bf16x8 qop[4];
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                qop[c] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(
-                             s_q + (ht * 16 + r16) * kQRowBytes + 64 * c + 16 * kg));
+                if constexpr (HT == 1) qop[c] = qreg[c];
+                else qop[c] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(
+                                  s_q + (ht * 16 + r16) * kQRowBytes + 64 * c + 16 * kg));
             }
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
