@@ -1,17 +1,19 @@
 // Band+tail / full split-K decode attention over a paged bf16 KV cache (gfx950, wave64, MFMA).
 //
 // What it computes (paper Sec. 2 "Notation", Sec. 3.1, Eq. (rect-recomp)): for one KV group (request b,
-// kv head g) and one work item = a token range [lo, hi), for every query head h of the group the attention
-// summary of the keys [max(lo, s_h), hi) under the post-RoPE query:  O = sum_t p_t V_t / sum_t p_t,
+// kv head g) and one work item = a token range [lo, hi), for every query head h of the group that is served here the
+// attention summary of the keys [max(lo, s_h), hi) under the post-RoPE query:  O = sum_t p_t V_t / sum_t p_t,
 // LSE = ln sum_t e^{scale q.K_t}.  The summaries of all work items are merged by the merge kernel.
 // KV is streamed once per KV group, from the smallest start among the group's heads (Sec. 5.8); heads that
-// start later mask the tokens before their own start.
+// start later mask the tokens before their own start.  Heads the per-head matcher has already finished (hits with a
+// short fresh range, see hit_kernel.hpp) are not served: a group all of whose heads are finished has no work items.
 //
 // Work items.  The fresh range [gs, n) of a group is cut at n - B (the last-B band, whose summary must stay
-// separate because the stored rectified summary excludes it, Fig. 1(c)) and on a global grid of `chunk`
-// tokens.  blockIdx.x < n_mid_slots : "mid" chunk x  = [x*chunk, (x+1)*chunk) clipped to [gs, n-B)
-// blockIdx.x >= n_mid_slots: "band" chunk k = x - n_mid_slots, chunk index floor((n-B)/chunk) + k,
-//                            clipped to [n-B, n).  Empty work items exit at once.
+// separate because the stored rectified summary excludes it, Fig. 1(c)) and on a global grid of C tokens: "mid" items
+// are the chunks x = floor(gs/C) .. ceil((n-B)/C) - 1, [x C, (x+1) C) clipped to [gs, n-B); "band" items the chunks from
+// floor((n-B)/C) on, clipped to [n-B, n).  A mid item writes its partial to slot x of its heads' rows, the k-th band
+// item to slot n_mid_slots + k.  C and the list of items are derived on the device by the planner at the head of the
+// kernel (below); the grid is the set of resident work-groups, which take the items in turn.
 //
 // Mapping to the hardware.  A work-group is 4 waves; wave w takes the 32-token tiles w, w+4, ... of the chunk
 // (those that intersect the work item) and keeps its own online-softmax state; the 4 states are merged
@@ -31,7 +33,8 @@
 //       with load-only probes, that combination streams ~4 % slower at this occupancy.)
 //   P is fp32 on the VALU (max, exp2, sum) and enters the MFMA as two bf16 terms hi + lo (truncation split,
 //       relative error 2^-16), because a single bf16 P would cost ~1e-3 relative output error.
-// Heads beyond G in the 16-row head tile carry zero queries; their results are never stored.
+// Heads beyond G in the 16-row head tile, and heads that are not served, carry zero queries; their results are never
+// stored.  Cross-row maxima and sums use the row-swap instructions of this chip (v_permlane16_swap / v_permlane32_swap).
 //
 // Memory.  Every K/V byte is used once per KV group, so the tiles are read with non-temporal loads (the stream
 // then neither displaces the query ring from the last-level cache nor pays for allocating lines it will not reuse:
@@ -158,7 +161,7 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnParams p) {
     __shared__ __attribute__((aligned(16))) char s_q[HT * 16 * kQRowBytes];
     __shared__ int s_skip[HT * 16];
     constexpr int kCap = AttnCaps<HT>::kMaxGroups;
-    __shared__ int s_prefix[kCap + 1];                       // work items before group q
+    __shared__ int s_prefix[kCap + 1], s_bprefix[kCap + 1];  // mid / band work items before group q
     __shared__ int s_gs[kCap], s_n[kCap];                    // start of the group's range (-1: nothing to do), kv_len
     __shared__ long long s_sum[4];
     // every head was finished by the matcher: only the first work-group stays, for the per-group counters
@@ -175,11 +178,18 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnParams p) {
         __syncthreads();
         return v;
     };
-    auto items_of = [&](int q, int C) {
+    // work items of group q for C tokens per item: chunks of [gs, n-B) on the global grid ("mid"), and of the band [n-B, n)
+    auto mid_items_of = [&](int q, int C) {
         const int gs = s_gs[q], n = s_n[q];
         if (gs < 0) return 0;
         const int nb = n - p.band > 0 ? n - p.band : 0;
-        return (nb > gs ? (nb + C - 1) / C - gs / C : 0) + (n > nb ? (n + C - 1) / C - nb / C : 0);
+        return nb > gs ? (nb + C - 1) / C - gs / C : 0;
+    };
+    auto band_items_of = [&](int q, int C) {
+        const int gs = s_gs[q], n = s_n[q];
+        if (gs < 0) return 0;
+        const int nb = n - p.band > 0 ? n - p.band : 0;
+        return n > nb ? (n + C - 1) / C - nb / C : 0;
     };
 
     // ---- plan: the groups' ranges, the step's total span; the first work-group also keeps the per-group counters
@@ -212,7 +222,7 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnParams p) {
         for (int tries = 0; tries < 6; ++tries) {
             if (C > kAttnChunkMax) { ++R; C = chunk_for(R); }
             long long items = 0;
-            for (int q = tid; q < NG; q += 256) items += items_of(q, C);
+            for (int q = tid; q < NG; q += 256) items += mid_items_of(q, C);
             items = block_sum(items);
             if (items <= R * P || C >= kAttnChunkMax) break;
             // too many by `items - R P`: lengthen every item by its share of their tokens
@@ -222,31 +232,36 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnParams p) {
         if (C > kAttnChunkMax) C = kAttnChunkMax;
     }
     C = __builtin_amdgcn_readfirstlane(C);                   // uniform values in scalar registers: what derives from them stays there
-    // ---- plan: prefix sums of the groups' item counts
-    int total = 0;
-    for (int q0 = 0; q0 < NG; q0 += 256) {
-        const int q = q0 + tid;
-        const int items = q < NG ? items_of(q, C) : 0;
-        int incl = items;                                    // inclusive scan inside the wave
+    // ---- plan: prefix sums of the groups' item counts.  The list holds the mid items of all groups first, then the
+    // band items: those are short (at most B tokens), and at the end of the list they fill the last round instead of
+    // taking the place of a long item in an earlier one (which is also why only the mid items have to fit R rounds).
+    auto prefix_scan = [&](auto count, int* out) {
+        int total = 0;
+        for (int q0 = 0; q0 < NG; q0 += 256) {
+            const int q = q0 + tid;
+            const int items = q < NG ? count(q) : 0;
+            int incl = items;                                // inclusive scan inside the wave
 #pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const int v = __shfl_up(incl, off);
-            if (lane >= off) incl += v;
+            for (int off = 1; off < 64; off <<= 1) {
+                const int v = __shfl_up(incl, off);
+                if (lane >= off) incl += v;
+            }
+            if (lane == 63) s_sum[wv] = incl;
+            __syncthreads();
+            int before = total;
+            for (int ww = 0; ww < wv; ++ww) before += (int)s_sum[ww];
+            if (q < NG) out[q] = before + incl - items;
+            total += (int)(s_sum[0] + s_sum[1] + s_sum[2] + s_sum[3]);
+            __syncthreads();
         }
-        if (lane == 63) s_sum[wv] = incl;
-        __syncthreads();
-        int before = total;
-        for (int ww = 0; ww < wv; ++ww) before += (int)s_sum[ww];
-        if (q < NG) s_prefix[q] = before + incl - items;
-        total += (int)(s_sum[0] + s_sum[1] + s_sum[2] + s_sum[3]);
-        __syncthreads();
-    }
-    if (tid == 0) {
-        s_prefix[NG] = total;
-        if (blockIdx.x == 0 && p.step_chunk != nullptr) *p.step_chunk = C;
-    }
+        if (tid == 0) out[NG] = total;
+    };
+    prefix_scan([&](int q) { return mid_items_of(q, C); }, s_prefix);
+    prefix_scan([&](int q) { return band_items_of(q, C); }, s_bprefix);
+    if (tid == 0 && blockIdx.x == 0 && p.step_chunk != nullptr) *p.step_chunk = C;
     __syncthreads();
-    total = __builtin_amdgcn_readfirstlane(s_prefix[NG]);
+    const int total_mid = __builtin_amdgcn_readfirstlane(s_prefix[NG]);
+    const int total = total_mid + __builtin_amdgcn_readfirstlane(s_bprefix[NG]);
 
     // ---- work items: item, item + gridDim.x, ...  Handing the items out one by one from a counter (requested before
     // an item's epilogue, so that its latency is hidden) was measured against this fixed assignment with 2 to 8 items
@@ -255,13 +270,17 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnParams p) {
     // work-groups do finish a third earlier than others, but because they share the memory system unevenly, not
     // because work is left over: what counts is few, long items in whole rounds.
     for (int item = blockIdx.x; item < total; item += P) {
-        int lo_q = 0, hi_q = NG;                             // the group: largest q with s_prefix[q] <= item
+        const bool is_band = item >= total_mid;
+        const int* pre = is_band ? s_bprefix : s_prefix;
+        const int pos = is_band ? item - total_mid : item;
+        int lo_q = 0, hi_q = NG;                             // the group: largest q with pre[q] <= pos
         while (hi_q - lo_q > 1) {
             const int mid = (lo_q + hi_q) >> 1;
-            if (s_prefix[mid] <= item) lo_q = mid; else hi_q = mid;
+            if (pre[mid] <= pos) lo_q = mid; else hi_q = mid;
         }
         const int q = __builtin_amdgcn_readfirstlane(lo_q);
-        const int k = item - __builtin_amdgcn_readfirstlane(s_prefix[q]);
+        // index of the item inside its group: mid items first, then band items
+        const int k = pos - __builtin_amdgcn_readfirstlane(pre[q]) + (is_band ? __builtin_amdgcn_readfirstlane(mid_items_of(q, C)) : 0);
         const int n = __builtin_amdgcn_readfirstlane(s_n[q]), gs = __builtin_amdgcn_readfirstlane(s_gs[q]);
         attn_item<HT>(p, C, q, k, n, gs, s_O, s_m, s_l, s_q, s_skip);
         __syncthreads();

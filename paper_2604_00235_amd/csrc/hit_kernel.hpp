@@ -8,9 +8,21 @@
 // 25 us at a 1 % KV budget); its hit path is launch- and plan-bound.  Here one work-group per (request, query head)
 // does all of it for the common case:
 //
-//   1. match: scan the head's whole window of the query ring (fp64 differences and FMAs, see match_kernel.hpp for the
-//      arithmetic), argmin with ties to the larger n_p, threshold and optional distance cap.  The decision, the head's
-//      counters and the caller's match_pos / match_d2 are written here.
+//   1. match: the head's whole window of the query ring, in three tiers.
+//      (a) Filter on the matrix cores: a 16-row tile of ring rows is the A operand (16 rows x 64 contiguous bytes per
+//          load instruction: the natural access pattern of the ring), the query fills every column of B, and two
+//          v_mfma_f32_16x16x32_bf16 chains give q.r_j and the Gram diagonal |r_j|^2 of the tile, hence
+//          f_j = |q|^2 + |r_j|^2 - 2 q.r_j with a proven bound |f_j - d2_j| <= eps_j (bf16 products are exact in fp32; only
+//          the accumulation rounds).  U = min_j (f_j + eps_j) over the work-group bounds the nearest distance from above.
+//      (b) Rows with f_j - eps_j <= U -- typically one -- are evaluated in fp64 (exact differences, fp64 FMAs) in the
+//          registers they were loaded into; argmin with ties to the larger n_p.
+//      (c) Two fp64 evaluations of one distance agree to ~2^-46 relative.  If the runner-up, or the threshold, lies
+//          within 2^-40 of the winner, the rows in question are summed once more in index order without FMAs, the
+//          plain left-to-right sum a reference takes, so that the decision is the same bit for bit by construction.
+//      An fp64 scan of every row (the first version of this kernel) kept a compute unit's VALU busy for 5 us per 1024
+//      rows of one head; the filter leaves it idle and the scan is bound by how fast one compute unit pulls the ring
+//      (~30 GB/s: 256 KB in 8.5 us), which only spreading a head over several compute units would lift.
+//      The decision, the head's counters and the caller's match_pos / match_d2 are written here.
 //   2. if the head hits and its fresh range [s, n), s = max(0, n_p - B), has at most `fused_span` tokens, the same
 //      work-group computes the two summaries the method needs -- mid = [s, n-B) and band = [n-B, n) -- with plain
 //      fp32 VALU arithmetic (a few hundred tokens of one head: no matrix cores needed), forms
@@ -164,7 +176,7 @@ __global__ __launch_bounds__(NT, NT == 256 ? 4 : 1) void hit_kernel(const HitPar
         const bool diag = kg == (r16 >> 2);                    // ... in the lane that holds it
         float U = INFINITY;                                    // smallest upper bound the work-group has seen so far
         const int n_tiles = (W + 15) >> 4;
-        constexpr int kInFlight = NT == 256 ? 4 : 2;           // 16-row tiles requested per wave before the arithmetic
+        constexpr int kInFlight = 4;                           // 16-row tiles requested per wave before the arithmetic
         int parity = 0;
         for (int base = 0; base < n_tiles; base += NW * kInFlight, parity ^= 1) {       // the same trip count in every wave
             const int t0 = base + w;

@@ -10,7 +10,8 @@
 // Arithmetic.  The decision has to agree with an fp64 evaluation of the exact bf16 inputs, so each
 // difference is formed in fp64 (exact) and squared/accumulated with fp64 FMAs; the result is within a few
 // ulp(fp64) of the true real value, so decisions differ from any other fp64 evaluation only for candidates
-// that tie to ~1e-15 relative.  v_fma_f64 is full rate on this chip and the kernels stay bandwidth-bound.
+// that tie to ~1e-15 relative (the per-head matcher resolves those in index order, see hit_kernel.hpp; the group
+// matcher below does not: it is a variant beyond the paper's rule).
 //
 // Access pattern.  A head's window is contiguous in the ring ([slot][head][entry][d]).  A quad of 4 lanes owns one
 // 256-byte row per pass, lane `sub` reading the 16-byte chunks sub, sub+4, sub+8, sub+12, so each load instruction
