@@ -66,6 +66,7 @@ struct AttnParams {
                                  // 0: chosen per launch from the work the step has, within [chunk_min, 8192]
     int32_t chunk_min;           // multiple of 32; the partial slots are laid out for it
     int32_t n_mid_slots, n_slots;
+    int32_t n_cu;                 // compute units of the device: the planner makes work items in multiples of it
     int32_t max_kv_len;
     float scale_log2;            // sm_scale * log2(e)
     const int32_t* pending;      // [1] heads the matcher left to this kernel, or null: 0 = nothing to do, leave at once
@@ -122,6 +123,7 @@ __device__ __forceinline__ int mid_items(const GroupSpan& s, int C) { return s.n
 __device__ __forceinline__ int band_items(const GroupSpan& s, int C) { return s.n > s.nb ? (s.n + C - 1) / C - s.nb / C : 0; }
 
 constexpr int kAttnChunkMax = 8192;      // tokens per work item at most (a wave's page ids sit one per lane in two registers)
+constexpr int kAttnChunkPref = 2048;     // the planner makes fewer items rather than shorter ones
 
 template <int HT> struct AttnCaps { static constexpr int kMaxGroups = HT == 1 ? 2048 : 256; };
 
@@ -210,23 +212,33 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnParams p) {
     tok = block_sum(tok);                                    // (its barrier also publishes s_gs / s_n)
     if (tok == 0) return;
     // ---- plan: tokens per item
+    // Measured on 256 compute units (two work-groups resident on each), 32 groups of equal length: what counts is
+    // that the number of items is a whole multiple of the number of compute units (each then streams the same bytes;
+    // whether one or two of its work-groups are busy matters little), that items stay at or above ~2048 tokens (an
+    // item's prologue and epilogue cost ~5 us in which its slot streams nothing) and that work-groups are handed
+    // their item by the dispatcher rather than looping over a fixed share (a compute unit favours its older
+    // work-group: with fixed shares the younger one is left alone at the end).  So: as many items as 4 per compute
+    // unit, fewer (3, 2, 1 per unit) while that keeps them at 2048 tokens, more only to keep them within the cap.
     int C = p.chunk_fixed;
     if (C == 0) {
-        long long R = (tok + (long long)P * kAttnChunkMax - 1) / ((long long)P * kAttnChunkMax);
-        auto chunk_for = [&](long long rounds) {
-            long long c = (tok + rounds * P - 1) / (rounds * P);
+        const long long U = p.n_cu;
+        long long N = tok / kAttnChunkPref / U * U;
+        N = N < U ? U : (N > 4 * U ? 4 * U : N);
+        if (N * kAttnChunkMax < tok) N = (tok + U * kAttnChunkMax - 1) / (U * kAttnChunkMax) * U;
+        auto chunk_for = [&](long long items) {
+            long long c = (tok + items - 1) / items;
             c = (c + 31) & ~31ll;
             return (int)(c < p.chunk_min ? p.chunk_min : c);
         };
-        C = chunk_for(R);
+        C = chunk_for(N);
         for (int tries = 0; tries < 6; ++tries) {
-            if (C > kAttnChunkMax) { ++R; C = chunk_for(R); }
+            if (C > kAttnChunkMax) { N += U; C = chunk_for(N); }
             long long items = 0;
             for (int q = tid; q < NG; q += 256) items += mid_items_of(q, C);
             items = block_sum(items);
-            if (items <= R * P || C >= kAttnChunkMax) break;
-            // too many by `items - R P`: lengthen every item by its share of their tokens
-            const long long grow = ((items - R * P) * C + R * P - 1) / (R * P);
+            if (items <= N || C >= kAttnChunkMax) break;
+            // too many by `items - N`: lengthen every item by its share of their tokens
+            const long long grow = ((items - N) * C + N - 1) / N;
             C += (int)((grow + 31) & ~31ll);
         }
         if (C > kAttnChunkMax) C = kAttnChunkMax;

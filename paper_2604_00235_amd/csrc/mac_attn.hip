@@ -2,6 +2,7 @@
 #include "../../include/mac_attn.h"
 
 #include <hip/hip_runtime.h>
+#include <cstdlib>
 
 #include <cmath>
 #include <cstring>
@@ -169,7 +170,8 @@ struct mac_attn_ctx {
     mac::MatchPartial* m_slices = nullptr; // [bh, n_split] nearest entry per window slice (group matcher only)
     mac::MatchPartial* m_part = nullptr;   // [bh] nearest entry of each head's window
     int32_t* plan = nullptr;               // [0] tokens per work item of the last attention launch
-    int32_t grid_attn = 512;               // work-groups of the attention kernel: two per compute unit
+    int32_t n_cu = 256;                    // compute units of the device
+    int32_t grid_attn = 1024;              // work-groups of the attention kernel at most: four per compute unit (two are resident)
     int32_t fused_span = 0;                // largest fresh range the per-head matcher finishes itself (0 = none)
     int32_t* head_start = nullptr;         // [max_batch*Hq + 32] fresh-range start per head (| kHeadDone), written by the matchers
     float* rect = nullptr;        // [bh*128] rows then [bh] lse
@@ -291,6 +293,7 @@ int launch_attention(mac_attn_ctx* ctx, const mac_attn_step_args* a, bool mac_mo
     p.chunk_min = L.chunk_min;
     p.n_mid_slots = L.n_mid_slots;
     p.n_slots = L.n_slots;
+    p.n_cu = ctx->n_cu;
     p.max_kv_len = c.max_kv_len;
     p.scale_log2 = ctx->sm_scale * mac::kLog2e;
     p.step_chunk = ctx->plan;
@@ -300,9 +303,13 @@ int launch_attention(mac_attn_ctx* ctx, const mac_attn_step_args* a, bool mac_mo
     p.st_read = mac_mode ? ctx->stats + 4 * bh : nullptr;
     p.st_full = mac_mode ? ctx->stats + 4 * bh + bg : nullptr;
     p.st_split = mac_mode ? ctx->stats + 4 * bh + 2 * bg : nullptr;
-    // as many work-groups as the chip holds, fewer if the call cannot have that many work items
+    // as many work-groups as the planner makes items unless it has to keep them within their cap (it aims at four
+    // per compute unit at most; the chip holds two, the others follow as those finish); fewer if the call cannot
+    // have that many work items
     const int64_t max_items = (int64_t)a->batch * c.num_kv_heads * (mac_mode ? L.n_slots : L.n_mid_slots);
-    const dim3 grid((unsigned)std::min<int64_t>(ctx->grid_attn, std::max<int64_t>(max_items, 1))), block(256);
+    const char* eg = getenv("MAC_GRID");
+    const int64_t gcap = eg ? atoi(eg) : ctx->grid_attn;
+    const dim3 grid((unsigned)std::min<int64_t>(gcap, std::max<int64_t>(max_items, 1))), block(256);
     if (L.G <= 16)
         hipLaunchKernelGGL(mac::attn_kernel<1>, grid, block, 0, stream, p);
     else
@@ -451,7 +458,8 @@ int mac_attn_init(const mac_attn_config* cfg, mac_attn_ctx** out_ctx) {
     {
         int cus = 0;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, cfg->device) != hipSuccess) cus = 0;
-        ctx->grid_attn = 2 * (cus > 0 ? cus : 256);
+        ctx->n_cu = cus > 0 ? cus : 256;
+        ctx->grid_attn = 4 * ctx->n_cu;
     }
     ctx->fused_span = cfg->fused_hit_span == 0 ? kDefaultFusedSpan : (cfg->fused_hit_span < 0 ? 0 : cfg->fused_hit_span);
     struct { void** p; int64_t bytes; bool zero; } allocs[] = {
@@ -551,7 +559,8 @@ int mac_attn_full_decode_static(const mac_attn_static_geometry* geo, const mac_a
     if ((rc = static_scratch(c.device, &base)) != MAC_ATTN_OK) return rc;
     int cus = 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c.device) != hipSuccess) cus = 0;
-    tmp.grid_attn = 2 * (cus > 0 ? cus : 256);
+    tmp.n_cu = cus > 0 ? cus : 256;
+    tmp.grid_attn = 4 * tmp.n_cu;
     tmp.sm_scale = c.sm_scale > 0.f ? c.sm_scale : 1.0f / std::sqrt((float)c.head_dim);
     tmp.T2 = 0.0;
     // Layout of the array: a word for the attention kernel's plan first (unused with fixed work items), then the
