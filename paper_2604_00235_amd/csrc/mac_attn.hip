@@ -2,7 +2,6 @@
 #include "../../include/mac_attn.h"
 
 #include <hip/hip_runtime.h>
-#include <cstdlib>
 
 #include <cmath>
 #include <cstring>
@@ -307,9 +306,7 @@ int launch_attention(mac_attn_ctx* ctx, const mac_attn_step_args* a, bool mac_mo
     // per compute unit at most; the chip holds two, the others follow as those finish); fewer if the call cannot
     // have that many work items
     const int64_t max_items = (int64_t)a->batch * c.num_kv_heads * (mac_mode ? L.n_slots : L.n_mid_slots);
-    const char* eg = getenv("MAC_GRID");
-    const int64_t gcap = eg ? atoi(eg) : ctx->grid_attn;
-    const dim3 grid((unsigned)std::min<int64_t>(gcap, std::max<int64_t>(max_items, 1))), block(256);
+    const dim3 grid((unsigned)std::min<int64_t>(ctx->grid_attn, std::max<int64_t>(max_items, 1))), block(256);
     if (L.G <= 16)
         hipLaunchKernelGGL(mac::attn_kernel<1>, grid, block, 0, stream, p);
     else
