@@ -165,19 +165,14 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnParams p) {
     constexpr int kCap = AttnCaps<HT>::kMaxGroups;
     __shared__ int s_prefix[kCap + 1], s_bprefix[kCap + 1];  // mid / band work items before group q
     __shared__ int s_gs[kCap], s_n[kCap];                    // start of the group's range (-1: nothing to do), kv_len
-    __shared__ long long s_sum[4];
     // every head was finished by the matcher: only the first work-group stays, for the per-group counters
     if (p.pending != nullptr && *p.pending == 0 && blockIdx.x != 0) return;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int Hkv = p.Hq / p.G, NG = p.batch * Hkv;
     const int P = gridDim.x;
-    auto block_sum = [&](long long v) {                      // the same total in every thread
+    auto wave_sum = [&](long long v) {                       // the same total in every lane
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) v += __shfl_xor(v, off);
-        if (lane == 0) s_sum[wv] = v;
-        __syncthreads();
-        v = s_sum[0] + s_sum[1] + s_sum[2] + s_sum[3];
-        __syncthreads();
         return v;
     };
     // work items of group q for C tokens per item: chunks of [gs, n-B) on the global grid ("mid"), and of the band [n-B, n)
@@ -194,31 +189,37 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnParams p) {
         return n > nb ? (n + C - 1) / C - nb / C : 0;
     };
 
-    // ---- plan: the groups' ranges, the step's total span; the first work-group also keeps the per-group counters
-    long long tok = 0;
+    // ---- plan: the groups' ranges (one thread per group); the first work-group also keeps the per-group counters
     for (int q = tid; q < NG; q += 256) {
         const int b = q / Hkv, g = q - b * Hkv;
         const GroupSpan s = group_span(p, b, b * p.Hq + g * p.G);
         const bool work = s.any && s.n > s.gs;
         s_gs[q] = work ? s.gs : -1;
         s_n[q] = s.n;
-        if (work) tok += s.n - s.gs;
         if (blockIdx.x == 0 && p.st_read != nullptr) {       // one writer per address and step: fire-and-forget adds
             atomicAdd(&p.st_read[q], (unsigned long long)(s.n - s.gs_all));
             atomicAdd(&p.st_full[q], (unsigned long long)s.n);
             if (s.any) atomicAdd(&p.st_split[q], (unsigned long long)(s.n - s.gs));
         }
     }
-    tok = block_sum(tok);                                    // (its barrier also publishes s_gs / s_n)
+    __syncthreads();
+    // From here every wave derives the rest of the plan by itself from the ranges (sums and prefix sums over the
+    // groups with wave-wide shuffles, 64 groups per pass): the four waves store the same values to the same places,
+    // and each reads back what it stored itself, so no further barrier is needed.
+    long long tok = 0;
+    for (int q = lane; q < NG; q += 64)
+        if (s_gs[q] >= 0) tok += s_n[q] - s_gs[q];
+    tok = wave_sum(tok);
     if (tok == 0) return;
     // ---- plan: tokens per item
     // Measured on 256 compute units (two work-groups resident on each), 32 groups of equal length: what counts is
     // that the number of items is a whole multiple of the number of compute units (each then streams the same bytes;
     // whether one or two of its work-groups are busy matters little), that items stay at or above ~2048 tokens (an
-    // item's prologue and epilogue cost ~5 us in which its slot streams nothing) and that work-groups are handed
-    // their item by the dispatcher rather than looping over a fixed share (a compute unit favours its older
-    // work-group: with fixed shares the younger one is left alone at the end).  So: as many items as 4 per compute
-    // unit, fewer (3, 2, 1 per unit) while that keeps them at 2048 tokens, more only to keep them within the cap.
+    // item's prologue and epilogue cost several microseconds in which its slot streams nothing) and that work-groups
+    // are handed their item by the dispatcher rather than looping over a fixed share (a compute unit favours its
+    // older work-group: with fixed shares the younger one is left alone at the end).  So: as many items as 4 per
+    // compute unit, fewer (3, 2, 1 per unit) while that keeps them at 2048 tokens, more only to keep them within the
+    // cap.
     int C = p.chunk_fixed;
     if (C == 0) {
         const long long U = p.n_cu;
@@ -234,8 +235,8 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnParams p) {
         for (int tries = 0; tries < 6; ++tries) {
             if (C > kAttnChunkMax) { N += U; C = chunk_for(N); }
             long long items = 0;
-            for (int q = tid; q < NG; q += 256) items += mid_items_of(q, C);
-            items = block_sum(items);
+            for (int q = lane; q < NG; q += 64) items += mid_items_of(q, C);
+            items = wave_sum(items);
             if (items <= N || C >= kAttnChunkMax) break;
             // too many by `items - N`: lengthen every item by its share of their tokens
             const long long grow = ((items - N) * C + N - 1) / N;
@@ -245,12 +246,11 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnParams p) {
     }
     C = __builtin_amdgcn_readfirstlane(C);                   // uniform values in scalar registers: what derives from them stays there
     // ---- plan: prefix sums of the groups' item counts.  The list holds the mid items of all groups first, then the
-    // band items: those are short (at most B tokens), and at the end of the list they fill the last round instead of
-    // taking the place of a long item in an earlier one (which is also why only the mid items have to fit R rounds).
+    // band items (at most B tokens each).
     auto prefix_scan = [&](auto count, int* out) {
         int total = 0;
-        for (int q0 = 0; q0 < NG; q0 += 256) {
-            const int q = q0 + tid;
+        for (int q0 = 0; q0 < NG; q0 += 64) {
+            const int q = q0 + lane;
             const int items = q < NG ? count(q) : 0;
             int incl = items;                                // inclusive scan inside the wave
 #pragma unroll
@@ -258,22 +258,15 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnParams p) {
                 const int v = __shfl_up(incl, off);
                 if (lane >= off) incl += v;
             }
-            if (lane == 63) s_sum[wv] = incl;
-            __syncthreads();
-            int before = total;
-            for (int ww = 0; ww < wv; ++ww) before += (int)s_sum[ww];
-            if (q < NG) out[q] = before + incl - items;
-            total += (int)(s_sum[0] + s_sum[1] + s_sum[2] + s_sum[3]);
-            __syncthreads();
+            if (q < NG) out[q] = total + incl - items;
+            total += __shfl(incl, 63);
         }
-        if (tid == 0) out[NG] = total;
+        if (lane == 0) out[NG] = total;
+        return total;
     };
-    prefix_scan([&](int q) { return mid_items_of(q, C); }, s_prefix);
-    prefix_scan([&](int q) { return band_items_of(q, C); }, s_bprefix);
+    const int total_mid = __builtin_amdgcn_readfirstlane(prefix_scan([&](int q) { return mid_items_of(q, C); }, s_prefix));
+    const int total = total_mid + __builtin_amdgcn_readfirstlane(prefix_scan([&](int q) { return band_items_of(q, C); }, s_bprefix));
     if (tid == 0 && blockIdx.x == 0 && p.step_chunk != nullptr) *p.step_chunk = C;
-    __syncthreads();
-    const int total_mid = __builtin_amdgcn_readfirstlane(s_prefix[NG]);
-    const int total = total_mid + __builtin_amdgcn_readfirstlane(s_bprefix[NG]);
 
     // ---- work items: item, item + gridDim.x, ...  Handing the items out one by one from a counter (requested before
     // an item's epilogue, so that its latency is hidden) was measured against this fixed assignment with 2 to 8 items
@@ -365,15 +358,24 @@ __device__ __forceinline__ void attn_item(const AttnParams& p, const int C, cons
         hstart[ht] = skip ? lo : max(lo, min(my_start[ht], nb));
         if (w == 0 && kg == 0) s_skip[ht * 16 + r16] = skip ? 1 : 0;
     }
-    {
-        // queries to shared memory: HT * 16 rows x 16 chunks of 16 B, HT per thread; rows of heads that need nothing are zero
+    // Queries: HT * 16 rows x 16 chunks of 16 B, HT per thread; rows of heads that need nothing are zero.  The loads are
+    // issued here and stored to shared memory only after the first K/V tile has been requested (below), so that the
+    // wait for them overlaps that tile's latency.
+    u32x4 qv[HT];
+    int qflag[HT];
+#pragma unroll
+    for (int t = 0; t < HT; ++t) {
+        const int idx = tid + 256 * t, row = idx >> 4, ch = idx & 15;
+        const int rowc = row < G ? row : 0;
+        qflag[t] = p.head_start != nullptr ? p.head_start[hbase + rowc] : 0;
+        qv[t] = *reinterpret_cast<const u32x4*>(p.q_rope + (int64_t)(hbase + rowc) * kHeadDim + 8 * ch);
+    }
+    auto stage_queries = [&]() {
 #pragma unroll
         for (int t = 0; t < HT; ++t) {
             const int idx = tid + 256 * t, row = idx >> 4, ch = idx & 15;
-            u32x4 v = u32x4{0u, 0u, 0u, 0u};
-            const bool skip = row >= G || (p.head_start != nullptr && (p.head_start[hbase + (row < G ? row : 0)] & kHeadDone));
-            if (!skip) v = *reinterpret_cast<const u32x4*>(p.q_rope + (int64_t)(hbase + row) * kHeadDim + 8 * ch);
-            *reinterpret_cast<u32x4*>(s_q + row * kQRowBytes + 16 * ch) = v;
+            const bool skip = row >= G || (qflag[t] & kHeadDone);
+            *reinterpret_cast<u32x4*>(s_q + row * kQRowBytes + 16 * ch) = skip ? u32x4{0u, 0u, 0u, 0u} : qv[t];
         }
         if constexpr (HT == 2) {
             // this wave's accumulators of both tiles start at zero
@@ -382,7 +384,7 @@ __device__ __forceinline__ void attn_item(const AttnParams& p, const int C, cons
             for (int i = 0; i < 16; ++i) *reinterpret_cast<f32x4*>(acc_img + 1024 * i + 16 * l) = f32x4{0.f, 0.f, 0.f, 0.f};
         }
         __syncthreads();
-    }
+    };
 
     // this wave's tiles of the chunk that intersect [lo, hi): k = k_first .. k_last
     const int tt_lo = lo >> 5, tt_hi = (hi - 1) >> 5;
@@ -456,12 +458,7 @@ __device__ __forceinline__ void attn_item(const AttnParams& p, const int C, cons
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    bf16x8 qreg[4];                                           // HT == 1: this lane's B operands of S = K Q^T
-    if constexpr (HT == 1) {
-#pragma unroll
-        for (int c = 0; c < 4; ++c)
-            qreg[c] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(s_q + r16 * kQRowBytes + 64 * c + 16 * kg));
-    }
+    bf16x8 qreg[4];                                           // HT == 1: this lane's B operands of S = K Q^T (set below)
     // scores of the wave's k-th tile for every head tile: sc[ht][4u + i] = scale * q_head . K_token, log2 domain, masked
     auto qk = [&](int k, const u32x4 (&K)[2][4], float (&sc)[HT][8]) {
         const int t0 = (chunk_tile0 + w + 4 * k) * kTileTokens;
@@ -571,6 +568,10 @@ __device__ __forceinline__ void attn_item(const AttnParams& p, const int C, cons
         // is computed.  The steady-state loop has no conditional loads; the last one or two tiles are peeled.
         u32x4 ka[2][4], va[8], kb[2][4], vb[8];
         if (k < k_end) { load_k(k, ka); load_v(k, va); }
+        stage_queries();
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            qreg[c] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(s_q + r16 * kQRowBytes + 64 * c + 16 * kg));
         for (; k + 2 < k_end; k += 2) {
             load_k(k + 1, kb); load_v(k + 1, vb);
             qk(k, ka, sc); pv(va, sc);
@@ -592,6 +593,7 @@ __device__ __forceinline__ void attn_item(const AttnParams& p, const int C, cons
         u32x4 ka[2][4], va[8], kb[2][4], vb[8];
         const int k_last = k_end - 1;
         if (k < k_end) { load_k(k, ka); load_v(k, va); }
+        stage_queries();
         for (; k + 2 <= k_end; k += 2) {
             load_k(k + 1, kb);
             qk(k, ka, sc);

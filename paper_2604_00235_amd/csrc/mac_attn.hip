@@ -302,11 +302,22 @@ int launch_attention(mac_attn_ctx* ctx, const mac_attn_step_args* a, bool mac_mo
     p.st_read = mac_mode ? ctx->stats + 4 * bh : nullptr;
     p.st_full = mac_mode ? ctx->stats + 4 * bh + bg : nullptr;
     p.st_split = mac_mode ? ctx->stats + 4 * bh + 2 * bg : nullptr;
-    // as many work-groups as the planner makes items unless it has to keep them within their cap (it aims at four
-    // per compute unit at most; the chip holds two, the others follow as those finish); fewer if the call cannot
-    // have that many work items
-    const int64_t max_items = (int64_t)a->batch * c.num_kv_heads * (mac_mode ? L.n_slots : L.n_mid_slots);
-    const dim3 grid((unsigned)std::min<int64_t>(ctx->grid_attn, std::max<int64_t>(max_items, 1))), block(256);
+    // One work-group per work item the planner can make for this batch (its rule, applied to max_kv_len tokens per
+    // group: a step with less work makes fewer items, never more mid items), plus one per group for the band; the
+    // kernel loops should a fixed item size make more.  A grid much larger than the item list would cost: work-groups
+    // without an item still derive the plan before they leave, the last of them when everything else has finished.
+    const int64_t groups = (int64_t)a->batch * c.num_kv_heads;
+    int64_t max_items = groups * (mac_mode ? L.n_slots : L.n_mid_slots);
+    if (L.chunk_fixed == 0) {
+        const int64_t tok = groups * c.max_kv_len, U = ctx->n_cu;
+        int64_t N = tok / mac::kAttnChunkPref / U * U;
+        N = std::min<int64_t>(std::max<int64_t>(N, U), 4 * U);
+        if (N * mac::kAttnChunkMax < tok) N = (tok + U * mac::kAttnChunkMax - 1) / (U * mac::kAttnChunkMax) * U;
+        max_items = std::min(max_items, std::min<int64_t>(N, ctx->grid_attn) + (mac_mode ? groups : 0));
+    } else {
+        max_items = std::min<int64_t>(max_items, ctx->grid_attn);
+    }
+    const dim3 grid((unsigned)std::max<int64_t>(max_items, 1)), block(256);
     if (L.G <= 16)
         hipLaunchKernelGGL(mac::attn_kernel<1>, grid, block, 0, stream, p);
     else
