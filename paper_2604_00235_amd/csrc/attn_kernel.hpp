@@ -156,9 +156,9 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnParams p) {
     // accumulators in register layout ([tile][column block j][lane] x 16 B: conflict-free) and each tile is loaded,
     // updated and stored back per K/V tile.  The queries (B operands of S = K Q^T) sit in s_q, rows padded to 272 B
     // so that the 16 rows read by one instruction fall into different banks.
-    __shared__ float s_O[4][HT * 16 * kHeadDim];
-    __shared__ float s_m[4][HT * 16];
-    __shared__ float s_l[4][HT * 16];
+    __shared__ __attribute__((aligned(16))) float s_O[4][HT * 16 * kHeadDim];
+    __shared__ __attribute__((aligned(16))) float s_m[4][HT * 16];
+    __shared__ __attribute__((aligned(16))) float s_l[4][HT * 16];
     constexpr int kQRowBytes = 2 * kHeadDim + 16;
     __shared__ __attribute__((aligned(16))) char s_q[HT * 16 * kQRowBytes];
     __shared__ int s_skip[HT * 16];
@@ -612,64 +612,70 @@ __device__ __forceinline__ void attn_item(const AttnParams& p, const int C, cons
         }
     }
 
-    // merge the 4 waves' states through LDS and write the normalised partial of every real head
-    f32x4 fin[HT][8];
+    // ---- the four waves' states meet in shared memory and leave as one normalised partial per head.
+    // The accumulators are stored as they sit in the registers ("image" of a wave: [tile][j][lane] x 16 B, lane
+    // 16 kg + r16 holding O[heads 4kg .. 4kg+3][d = 8 r16 + j]; with two head tiles the images are there already).
+    // Then each wave takes blocks of four heads (tile ht, kg): lane (jq, r) sums the four images' entries
+    // (j = 2jq, 2jq+1; lane 16 kg + r) with the heads' weights, which gives it two adjacent columns of the four
+    // heads, so that the 64 lanes together store whole 512-byte rows.
     if constexpr (HT == 1) {
+        char* const img = reinterpret_cast<char*>(&s_O[w][0]) + 16 * l;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) fin[0][j] = acc[j];
-    } else {
-        // both tiles' accumulators leave the register-layout image before the same memory takes the merge layout
-        const char* const acc_img = reinterpret_cast<const char*>(&s_O[w][0]) + 16 * l;
-#pragma unroll
-        for (int ht = 0; ht < HT; ++ht)
-#pragma unroll
-            for (int j = 0; j < 8; ++j) fin[ht][j] = *reinterpret_cast<const f32x4*>(acc_img + 8192 * ht + 1024 * j);
+        for (int j = 0; j < 8; ++j) *reinterpret_cast<f32x4*>(img + 1024 * j) = acc[j];
     }
 #pragma unroll
     for (int ht = 0; ht < HT; ++ht) {
-        float lsum = l_run[ht];
-        lsum = add_xor32(add_xor16(lsum));
+        const float lsum = add_xor32(add_xor16(l_run[ht]));
         if (kg == 0) {
             s_m[w][ht * 16 + r16] = m_run[ht];
             s_l[w][ht * 16 + r16] = lsum;
         }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int head = ht * 16 + 4 * kg + i;
-            if (head < G) {
-                float* dst = &s_O[w][head * kHeadDim + 8 * r16];
-                *reinterpret_cast<f32x4*>(dst) = f32x4{fin[ht][0][i], fin[ht][1][i], fin[ht][2][i], fin[ht][3][i]};
-                *reinterpret_cast<f32x4*>(dst + 4) = f32x4{fin[ht][4][i], fin[ht][5][i], fin[ht][6][i], fin[ht][7][i]};
-            }
-        }
     }
     __syncthreads();
-    // weights of the four waves' states per head, once per head (thread h): s_l[w][h] <- 2^(m_w - M) / L, s_m[0][h] <- LSE
-    if (tid < HT * 16) {
-        const int h = tid;
-        const float M = fmaxf(fmaxf(s_m[0][h], s_m[1][h]), fmaxf(s_m[2][h], s_m[3][h]));
-        float f[4], L = 0.f;
+    for (int u = w; u < HT * 4; u += 4) {
+        const int ht = u >> 2, kgu = u & 3, h0 = ht * 16 + 4 * kgu;
+        if (h0 >= G) continue;
+        f32x4 mw[4], lw[4], wgt[4];
 #pragma unroll
         for (int ww = 0; ww < 4; ++ww) {
-            f[ww] = M == -INFINITY ? 0.f : exp2_fast(s_m[ww][h] - M);
-            L += s_l[ww][h] * f[ww];
+            mw[ww] = *reinterpret_cast<const f32x4*>(&s_m[ww][h0]);
+            lw[ww] = *reinterpret_cast<const f32x4*>(&s_l[ww][h0]);
         }
-        const float inv = L > 0.f ? 1.f / L : 0.f;
+        float lse[4];
 #pragma unroll
-        for (int ww = 0; ww < 4; ++ww) s_l[ww][h] = f[ww] * inv;
-        s_m[0][h] = L > 0.f ? (M + __log2f(L)) * kLn2 : -INFINITY;
-    }
-    __syncthreads();
-#pragma unroll 4
-    for (int idx = tid; idx < G * kHeadDim; idx += 256) {
-        const int h = idx >> 7, dd = idx & (kHeadDim - 1);
-        if (s_skip[h]) continue;
-        float o = 0.f;
+        for (int i = 0; i < 4; ++i) {
+            const float M = fmaxf(fmaxf(mw[0][i], mw[1][i]), fmaxf(mw[2][i], mw[3][i]));
+            float f[4], L = 0.f;
 #pragma unroll
-        for (int ww = 0; ww < 4; ++ww) o += s_O[ww][h * kHeadDim + dd] * s_l[ww][h];
-        const int64_t row = (int64_t)(hbase + h) * p.n_slots + slot;
-        p.part_O[row * kHeadDim + dd] = o;
-        if (dd == 0) p.part_lse[row] = s_m[0][h];
+            for (int ww = 0; ww < 4; ++ww) {
+                f[ww] = M == -INFINITY ? 0.f : exp2_fast(mw[ww][i] - M);
+                L += lw[ww][i] * f[ww];
+            }
+            const float inv = L > 0.f ? 1.f / L : 0.f;
+#pragma unroll
+            for (int ww = 0; ww < 4; ++ww) wgt[ww][i] = f[ww] * inv;
+            lse[i] = L > 0.f ? (M + __log2f(L)) * kLn2 : -INFINITY;
+        }
+        const int jq = l >> 4, r = l & 15;
+        f32x4 o[2];
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+            o[jj] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ww = 0; ww < 4; ++ww) {
+                const f32x4 v = *reinterpret_cast<const f32x4*>(reinterpret_cast<const char*>(&s_O[ww][0]) + 8192 * ht +
+                                                                1024 * (2 * jq + jj) + 16 * (16 * kgu + r));
+                o[jj] += v * wgt[ww];
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int h = h0 + i;
+            if (h >= G || s_skip[h]) continue;
+            const int64_t row = (int64_t)(hbase + h) * p.n_slots + slot;
+            *reinterpret_cast<f32x2*>(p.part_O + row * kHeadDim + 8 * r + 2 * jq) = f32x2{o[0][i], o[1][i]};
+            if (l == 0) p.part_lse[row] = lse[i];
+        }
     }
 }
 

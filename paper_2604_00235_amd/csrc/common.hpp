@@ -7,6 +7,7 @@ namespace mac {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 constexpr int kHeadDim = 128;      // d; a K or V row is 256 bytes = 16 chunks of 16 bytes
