@@ -312,6 +312,35 @@ def match_table(torch, mb, wl_mod, timed: int = 40):
     return rows
 
 
+def stream_probe(torch, mb, total_bytes: int = 2 << 30):
+    """What a kernel that only loads pulls out of HBM on this machine (include/mac_probe.h): 2 GiB read in segments of one
+    (page, K|V, head) block of the KV cache (4 KiB) and larger, in address order and in a seeded random order, with the
+    non-temporal hint the attention kernel uses and without.  The attention kernel's K/V stream has the random 4 KiB
+    pattern; its achieved bandwidth is to be held against that row (the roofline fraction stays against 8 TB/s)."""
+    buf = torch.ones(total_bytes // 4, dtype=torch.int32, device="cuda:0")
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda:0")
+    st = torch.cuda.current_stream().cuda_stream
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(1)
+    rows = []
+    for seg, shuffle, nt, wgs in ((4096, False, True, 512), (4096, True, True, 512), (4096, True, True, 1024),
+                                  (4096, True, False, 1024), (2048, True, True, 1024), (16384, True, True, 1024),
+                                  (16384, False, True, 256)):
+        n = total_bytes // seg
+        order = (torch.randperm(n, generator=gen) if shuffle else torch.arange(n)).to(torch.int32).to("cuda:0")
+        torch.cuda.synchronize()
+        us = mb.mac_probe_stream(buf.data_ptr(), order.data_ptr(), n, seg, nt, wgs, 10, sink.data_ptr(), st)
+        rows.append({"segment_bytes": seg, "order": "random" if shuffle else "linear", "non_temporal": nt,
+                     "work_groups": wgs, "us_per_2GiB": round(us, 1), "GBps": round(total_bytes / us / 1e3, 0)})
+        log(f"[stream-probe] {seg:6d}-byte segments, {rows[-1]['order']:6s} order, "
+            f"{'non-temporal' if nt else 'plain       '} loads, {wgs:5d} work-groups: {us:7.1f} us per 2 GiB = "
+            f"{total_bytes / us / 1e6:.2f} TB/s")
+        del order
+    del buf
+    torch.cuda.empty_cache()
+    return rows
+
+
 def err_table(torch, mb, wl_mod, align: float = 1.5, context: int = 32768, timed: int = 48):
     """Synthetic analogue of the paper's rectification-error heat-map (Sec. 5.4): the relative error of the MAC output
     against full attention of the same step, Err = |o_MAC - o_full| / |o_full|, averaged over the heads that hit, as a
@@ -421,6 +450,9 @@ def main():
                     help="also time the headline config replayed from one captured HIP graph per step (input refresh, "
                          "the library's launches and the step counter all inside the graph), beside the same device "
                          "work launched eagerly")
+    ap.add_argument("--stream-probe", action="store_true",
+                    help="also measure what a load-only kernel streams from HBM with the K/V access pattern (random 4 KiB "
+                         "blocks) and add it as 'stream_probe': the measured ceiling beside the published peak")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (known traffic) so that a rocprofv3 --pmc run of this "
                          "command can scale FETCH_SIZE / WRITE_SIZE")
@@ -523,6 +555,8 @@ def main():
         line["match_table"] = match_table(torch, mb, wl_mod)
     if a.err_table:
         line["err_table"] = err_table(torch, mb, wl_mod)
+    if a.stream_probe:
+        line["stream_probe"] = stream_probe(torch, mb)
     if not a.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(a.config, torch, wl_mod, a.cpu_steps)
     print(json.dumps(line), flush=True)

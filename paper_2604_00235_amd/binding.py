@@ -83,6 +83,37 @@ class MacAttnError(RuntimeError):
 _lib = None
 
 
+PROBE_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmacprobe.so")
+PROBE_EXPORTS = ("mac_probe_stream",)
+_probe_lib = None
+
+
+def load_probe_library() -> C.CDLL:
+    """Load libmacprobe.so (the read-only streaming probe of include/mac_probe.h) and declare its prototype."""
+    global _probe_lib
+    if _probe_lib is not None:
+        return _probe_lib
+    if not os.path.exists(PROBE_LIB_PATH):
+        raise FileNotFoundError(f"{PROBE_LIB_PATH} is missing: build it with `python -m paper_2604_00235_amd.build`")
+    lib = C.CDLL(PROBE_LIB_PATH)
+    lib.mac_probe_stream.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                     C.c_void_p, C.c_void_p, C.POINTER(C.c_float)]
+    lib.mac_probe_stream.restype = C.c_int
+    _probe_lib = lib
+    return lib
+
+
+def mac_probe_stream(buffer_ptr: int, order_ptr: int, n_segments: int, segment_bytes: int, non_temporal: bool,
+                     work_groups: int, iterations: int, sink_ptr: int, stream: int) -> float:
+    """include/mac_probe.h mac_probe_stream: microseconds per pass over n_segments x segment_bytes."""
+    us = C.c_float(0.0)
+    rc = load_probe_library().mac_probe_stream(buffer_ptr, order_ptr, n_segments, segment_bytes, int(non_temporal),
+                                               work_groups, iterations, sink_ptr, stream, C.byref(us))
+    if rc != 0:
+        raise RuntimeError(f"mac_probe_stream failed ({rc})")
+    return float(us.value)
+
+
 def load_library() -> C.CDLL:
     """Load libmacattn.so and declare the prototypes.  Raises if the library is not built."""
     global _lib

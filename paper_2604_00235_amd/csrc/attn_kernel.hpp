@@ -167,7 +167,7 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnParams p) {
     __shared__ int s_gs[kCap], s_n[kCap];                    // start of the group's range (-1: nothing to do), kv_len
     // every head was finished by the matcher: only the first work-group stays, for the per-group counters
     if (p.pending != nullptr && *p.pending == 0 && blockIdx.x != 0) return;
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
     const int Hkv = p.Hq / p.G, NG = p.batch * Hkv;
     const int P = gridDim.x;
     auto wave_sum = [&](long long v) {                       // the same total in every lane

@@ -37,6 +37,25 @@ def test_every_declared_symbol_is_exported(lib):
         assert hasattr(lib, name), name
 
 
+def test_probe_library_exports_its_header():
+    """The streaming probe (include/mac_probe.h) is a library of its own: it loads and exports what its header declares,
+    and rejects bad arguments before touching the GPU."""
+    header = open(os.path.join(ROOT, "include", "mac_probe.h")).read()
+    declared = set(re.findall(r"\b(mac_probe_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(mb.PROBE_EXPORTS)
+    if not os.path.exists(mb.PROBE_LIB_PATH):
+        from paper_2604_00235_amd.build import build_library
+        build_library()
+    plib = mb.load_probe_library()
+    for name in declared:
+        assert hasattr(plib, name), name
+    us = C.c_float()
+    assert plib.mac_probe_stream(None, None, 8, 4096, 1, 1, 1, None, None, C.byref(us)) == -1
+    assert plib.mac_probe_stream(16, 16, 8, 4000, 1, 1, 1, 16, None, C.byref(us)) == -1      # segment size
+    assert plib.mac_probe_stream(16, 16, 12, 4096, 1, 1, 1, 16, None, C.byref(us)) == -1     # not a multiple of 8 per work-group
+    assert plib.mac_probe_stream(8, 16, 8, 4096, 1, 1, 1, 16, None, C.byref(us)) == -1       # alignment
+
+
 def test_struct_layouts_match_header():
     """Field order/size of the ctypes mirrors: int32/float fields packed as in the C structs."""
     assert C.sizeof(mb.mac_attn_config) == 18 * 4
