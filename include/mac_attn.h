@@ -61,8 +61,9 @@ typedef struct mac_attn_config {
                               hit iff d^2 < (double)T * (double)T, strict                                 */
     float   sm_scale;      /* softmax scale, 1/sqrt(head_dim) in the paper; <= 0 selects that default     */
     int32_t max_kv_len;    /* upper bound of kv_len; sizes the split-K workspace and the launch grids     */
-    int32_t chunk_tokens;  /* tokens per split-K work item: multiple of 32 in [32, 4096]; 0 = chosen from
-                              max_batch * Hkv * max_kv_len so that a full-length step has ~2000 work items */
+    int32_t chunk_tokens;  /* tokens per split-K work item: multiple of 32 in [32, 4096]; 0 = chosen per launch,
+                              on the device, from the span the step really has (the planner of Sec. 4.2 K2 (1):
+                              work in proportion to span), within [max(256, 32 G), 8192]                    */
     int32_t fuse_epilogue; /* 1: the merge kernel also appends to the ring (decode_step = 3 launches);
                               0: write-back runs as a kernel of its own (4 launches)                      */
     int32_t max_gap;       /* distance cap of the appendix on prefill ("Recommendations" (i)): the nearest
@@ -135,9 +136,10 @@ int mac_attn_full_decode(mac_attn_ctx* ctx, const mac_attn_step_args* args /*hos
  * mac_attn_full_decode, but with no context -- the geometry comes in `geo`, and the split-K partials go to a
  * static device array of MAC_ATTN_STATIC_SCRATCH_BYTES that every GPU the library runs on holds until the process
  * ends.  The call allocates nothing (no hipMalloc / hipFree, no context) and only enqueues two kernels on the stream.
- *   workspace needed = batch * Hq * ceil(max_kv_len / chunk) * 516 bytes, chunk = geo->chunk_tokens, or for 0 the
- *   default rule of mac_attn_config.chunk_tokens applied to batch * Hkv * max_kv_len; a call that needs more
- *   returns MAC_ATTN_ERR_TOO_LARGE and enqueues nothing.
+ *   workspace needed = 256 + batch * Hq * ceil(max_kv_len / chunk) * 516 bytes, chunk = geo->chunk_tokens, or for 0
+ *   a fixed size derived from batch * Hkv * max_kv_len on the host (a power of two in [512, 2048], at least 64 G:
+ *   the item size is not chosen per launch here, so that the layout of the array is known before the launch);
+ *   a call that needs more returns MAC_ATTN_ERR_TOO_LARGE and enqueues nothing.
  * Arguments as for mac_attn_full_decode (args->q_pre, slot_ids, match_* are ignored).  Nothing in the array has to
  * survive between calls and nothing is cleared: every partial a call reads it has written itself.  All calls on one
  * GPU share that GPU's array, so calls that overlap in time on one GPU (two streams, two threads) race; calls on

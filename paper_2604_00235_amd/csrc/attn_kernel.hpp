@@ -13,7 +13,7 @@
 // are the chunks x = floor(gs/C) .. ceil((n-B)/C) - 1, [x C, (x+1) C) clipped to [gs, n-B); "band" items the chunks from
 // floor((n-B)/C) on, clipped to [n-B, n).  A mid item writes its partial to slot x of its heads' rows, the k-th band
 // item to slot n_mid_slots + k.  C and the list of items are derived on the device by the planner at the head of the
-// kernel (below); the grid is the set of resident work-groups, which take the items in turn.
+// kernel (below).
 //
 // Mapping to the hardware.  A work-group is 4 waves; wave w takes the 32-token tiles w, w+4, ... of the chunk
 // (those that intersect the work item) and keeps its own online-softmax state; the 4 states are merged
@@ -134,21 +134,12 @@ __device__ __forceinline__ void attn_item(const AttnParams& p, int C, int q, int
 
 // The planner of the paper (Sec. 4.2 K2 (1), App. B.2 "Load balancing": work-groups in proportion to span) runs inside
 // the kernel: every work-group derives the same list of work items from kv_lens and the heads' starts -- one thread
-// per KV group, a block-wide sum for the step's total span, from it the tokens per item, a block-wide prefix sum of
-// the groups' item counts -- and then takes the items blockIdx.x, blockIdx.x + gridDim.x, ...  The grid is the number
-// of work-groups the chip holds (two per compute unit), not the number of items max_kv_len could have, so a step
-// whose heads were all finished by the matcher costs one short round trip per resident work-group.
-//
-// Tokens per item.  Measured on full-length steps: the fewer and longer the items, the faster (each item costs a
-// prologue -- lengths, starts, page ids, queries, first tiles -- and an epilogue -- merge of the four waves, G
-// partial rows -- of a few microseconds that the other work-group of the compute unit only partly covers: 32 groups
-// of 131072 tokens take 335 us with 2752-token items, 341 us with 2080, 345 us with 1376), provided that the number
-// of items does not exceed a whole number of rounds of the grid by a few: items are assigned round-robin, so R rounds
-// plus a handful costs R + 1 (2048-token items, 2080 of them on 512 work-groups: 357 us).  So: R = the rounds that
-// items of the largest size need, C = total span / (R x grid) rounded up to a multiple of 32, and C grows until the
-// exact item count fits R rounds (the groups' ranges are cut on a global grid of C tokens, so every group adds up
-// to two short items).  A step with little work (a few groups without reuse among many with) gets R = 1 and items as
-// short as chunk_min, so that it still spreads over the chip.
+// per KV group for the group's range, then, after one barrier, every wave by itself: the step's total span, from it
+// the tokens per item (the rule is stated where it is applied, below), the prefix sums of the groups' item counts --
+// and takes the item blockIdx.x (and blockIdx.x + gridDim.x, ... should there be more items than work-groups).  The
+// host launches as many work-groups as the same rule makes items for max_kv_len tokens per group: normally one item
+// per work-group, handed out by the hardware dispatcher as earlier work-groups finish.  A step whose heads were all
+// finished by the matcher costs one load per work-group.
 template <int HT>   // number of 16-head tiles: 1 (G <= 16) or 2 (G <= 32)
 __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnParams p) {
     // Shared memory.  s_O carries the waves' states to the merge at the end.  With two head tiles (HT == 2) a wave
@@ -268,12 +259,11 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnParams p) {
     const int total = total_mid + __builtin_amdgcn_readfirstlane(prefix_scan([&](int q) { return band_items_of(q, C); }, s_bprefix));
     if (tid == 0 && blockIdx.x == 0 && p.step_chunk != nullptr) *p.step_chunk = C;
 
-    // ---- work items: item, item + gridDim.x, ...  Handing the items out one by one from a counter (requested before
-    // an item's epilogue, so that its latency is hidden) was measured against this fixed assignment with 2 to 8 items
-    // per work-group: never faster (32 groups of 131072 tokens: 337 us at 2, 360 us at 8; fixed: 337 us; 64 groups of
-    // 32768: 182 us at best against 177 us; 16 groups of 65536 with 32 heads each: 133 us against 111 us).  Single
-    // work-groups do finish a third earlier than others, but because they share the memory system unevenly, not
-    // because work is left over: what counts is few, long items in whole rounds.
+    // ---- work items: normally one per work-group (the grid is sized by the same rule); the loop serves launches with a
+    // caller-fixed item size or more items than the grid's cap.  Handing the items out one by one from a counter to
+    // resident work-groups (requested before an item's epilogue, so that its latency is hidden) was measured against
+    // fixed shares with 2 to 8 items per work-group and was never faster (32 groups of 131072 tokens: 337 us at 2, 360 us
+    // at 8; fixed shares 337 us; one item per dispatched work-group 332 us).
     for (int item = blockIdx.x; item < total; item += P) {
         const bool is_band = item >= total_mid;
         const int* pre = is_band ? s_bprefix : s_prefix;
