@@ -254,8 +254,17 @@ struct Timer {          // brackets the kernels of one call with events when tim
         mark(kernel + 1);
     }
     void finish() {
-        if (on && rc == MAC_ATTN_OK) ctx->timed.push_back(tc);
+        if (on && rc == MAC_ATTN_OK) {
+            ctx->timed.push_back(tc);
+            kept = true;
+        }
     }
+    ~Timer() {               // a call that failed on the way: its events go back to the pool
+        if (!on || kept) return;
+        for (hipEvent_t e : tc.ev)
+            if (e != nullptr) ctx->event_pool.push_back(e);
+    }
+    bool kept = false;
 };
 
 mac::MatchView match_view(const mac_attn_ctx* ctx, bool mac_mode) {
@@ -797,10 +806,10 @@ int mac_attn_kernel_us(mac_attn_ctx* ctx, double sum_us[4], int64_t* n_calls) {
     if (ctx == nullptr || sum_us == nullptr || n_calls == nullptr) return MAC_ATTN_ERR_INVALID_ARG;
     int rc = ensure_device(ctx);
     if (rc != MAC_ATTN_OK) return rc;
-    HIP_TRY(hipStreamSynchronize(ctx->last_stream));
     for (int k = 0; k < 4; ++k) sum_us[k] = 0.0;
     *n_calls = (int64_t)ctx->timed.size();
     for (TimedCall& t : ctx->timed) {
+        HIP_TRY(hipEventSynchronize(t.ev[4]));      // the call's last event, on whatever stream the call was made
         for (int k = 0; k < 4; ++k) {
             if (t.ran[k]) {
                 float ms = 0.f;
