@@ -115,6 +115,15 @@ def test_c3_long_context_128k_one_reuse_point_per_group():
     assert st["kv_tokens_read"] < 0.75 * st["kv_tokens_full"]
 
 
+def test_work_items_at_the_size_cap():
+    """128 KV groups of 70000 tokens (4.6 GB of K/V) are more than four work items of the largest size per compute unit:
+    the planner then makes more items (in multiples of the compute units) instead of longer ones, and the grid, capped,
+    loops.  Step 1 misses everywhere (all groups at full length), step 2 hits."""
+    cfg = scaled(CONFIGS["C2"], name="cap", batch=16, context=70000)
+    hits, st = run_fullsize(cfg, steps=2, full_every=1)
+    assert hits == st["head_steps"] - 16 * 32
+
+
 def test_c4_mqa_64k_full_size_all_miss_and_matched():
     hits, st = run_fullsize(CONFIGS["C4_miss"], steps=3, full_every=2)
     assert hits == 0 and st["kv_tokens_read"] == st["kv_tokens_full"]

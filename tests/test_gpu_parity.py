@@ -355,3 +355,13 @@ def test_candidates_that_tie_to_rounding_are_decided_as_the_index_order_sum_deci
         check_rows(g_out, ref["out"], f"neartie step {s}")
     assert order_matters > 0 and decided_by_rounding > 0, (order_matters, decided_by_rounding)
     run.mac.close()
+
+
+def test_more_work_items_than_work_groups():
+    """A caller-fixed item size of 32 tokens on 4 KV groups of ~9000 tokens makes ~1130 work items, more than the
+    attention grid's cap (four work-groups per compute unit): work-groups then loop over item, item + grid, ..."""
+    cfg = WorkloadConfig(name="many_items", batch=2, num_q_heads=8, num_kv_heads=2, context=9001, steps=5, window=8,
+                         band=40, threshold=3.2, rho=0.95, seed=31, ragged=77)
+    from tests.gpu_harness import run_parity
+    r = run_parity(cfg, chunk_tokens=32, fused_hit_span=-1)
+    assert 0 < r["hits"] < 5 * 16
