@@ -128,7 +128,7 @@ constexpr int kAttnChunkPref = 2048;     // the planner makes fewer items rather
 template <int HT> struct AttnCaps { static constexpr int kMaxGroups = HT == 1 ? 2048 : 256; };
 
 template <int HT>
-__device__ __forceinline__ void attn_item(const AttnParams& p, int C, int q, int item_k, int n, int gs,
+__device__ __forceinline__ void attn_item(const AttnParams& p, int C, int q, bool is_band, int item_k, int n, int gs,
                                           float (&s_O)[4][HT * 16 * kHeadDim], float (&s_m)[4][HT * 16],
                                           float (&s_l)[4][HT * 16], char* s_q, int (&s_skip)[HT * 16]);
 
@@ -154,30 +154,31 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnParams p) {
     __shared__ __attribute__((aligned(16))) char s_q[HT * 16 * kQRowBytes];
     __shared__ int s_skip[HT * 16];
     constexpr int kCap = AttnCaps<HT>::kMaxGroups;
-    __shared__ int s_prefix[kCap + 1], s_bprefix[kCap + 1];  // mid / band work items before group q
+    __shared__ int s_prefix[kCap], s_bprefix[kCap];          // mid / band work items before group q inside its block of 64 groups
+    __shared__ int s_blk[2][kCap / 64];                      // mid / band work items of each block of 64 groups
     __shared__ int s_gs[kCap], s_n[kCap];                    // start of the group's range (-1: nothing to do), kv_len
+    __shared__ double s_red[2][4];
     // every head was finished by the matcher: only the first work-group stays, for the per-group counters
     if (p.pending != nullptr && *p.pending == 0 && blockIdx.x != 0) return;
-    const int tid = threadIdx.x, lane = tid & 63;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int Hkv = p.Hq / p.G, NG = p.batch * Hkv;
     const int P = gridDim.x;
-    auto wave_sum = [&](long long v) {                       // the same total in every lane
+    // Up to 64 KV groups every wave derives the whole plan by itself (one group per lane, no barrier after the first);
+    // beyond that the four waves share the groups (thread t takes t, t + 256, ...: a wave always holds 64
+    // consecutive groups) and meet through shared memory.  Totals up to 2^41 tokens are exact in double precision.
+    const bool coop = NG > 64;
+    const int first = coop ? tid : lane, stride = coop ? 256 : 64;
+    int parity = 0;
+    auto total_of = [&](double v) {                          // the same total in every thread
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) v += __shfl_xor(v, off);
+        if (coop) {
+            if (lane == 0) s_red[parity][wv] = v;
+            __syncthreads();
+            v = (s_red[parity][0] + s_red[parity][1]) + (s_red[parity][2] + s_red[parity][3]);
+            parity ^= 1;
+        }
         return v;
-    };
-    // work items of group q for C tokens per item: chunks of [gs, n-B) on the global grid ("mid"), and of the band [n-B, n)
-    auto mid_items_of = [&](int q, int C) {
-        const int gs = s_gs[q], n = s_n[q];
-        if (gs < 0) return 0;
-        const int nb = n - p.band > 0 ? n - p.band : 0;
-        return nb > gs ? (nb + C - 1) / C - gs / C : 0;
-    };
-    auto band_items_of = [&](int q, int C) {
-        const int gs = s_gs[q], n = s_n[q];
-        if (gs < 0) return 0;
-        const int nb = n - p.band > 0 ? n - p.band : 0;
-        return n > nb ? (n + C - 1) / C - nb / C : 0;
     };
 
     // ---- plan: the groups' ranges (one thread per group); the first work-group also keeps the per-group counters
@@ -194,14 +195,12 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnParams p) {
         }
     }
     __syncthreads();
-    // From here every wave derives the rest of the plan by itself from the ranges (sums and prefix sums over the
-    // groups with wave-wide shuffles, 64 groups per pass): the four waves store the same values to the same places,
-    // and each reads back what it stored itself, so no further barrier is needed.
-    long long tok = 0;
-    for (int q = lane; q < NG; q += 64)
-        if (s_gs[q] >= 0) tok += s_n[q] - s_gs[q];
-    tok = wave_sum(tok);
-    if (tok == 0) return;
+    double tok = 0.0, busy = 0.0;                            // the step's span, and the groups that have any
+    for (int q = first; q < NG; q += stride)
+        if (s_gs[q] >= 0) { tok += (double)(s_n[q] - s_gs[q]); busy += 1.0; }
+    tok = total_of(tok);
+    busy = total_of(busy);
+    if (tok == 0.0) return;
     // ---- plan: tokens per item
     // Measured on 256 compute units (two work-groups resident on each), 32 groups of equal length: what counts is
     // that the number of items is a whole multiple of the number of compute units (each then streams the same bytes;
@@ -210,53 +209,80 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnParams p) {
     // are handed their item by the dispatcher rather than looping over a fixed share (a compute unit favours its
     // older work-group: with fixed shares the younger one is left alone at the end).  So: as many items as 4 per
     // compute unit, fewer (3, 2, 1 per unit) while that keeps them at 2048 tokens, more only to keep them within the
-    // cap.
+    // cap or because there are more groups with work than that (each has an item of its own anyway).
+    // (Divisions by C: exact, by a double-precision reciprocal and one correction step; an integer division costs ~40
+    // instructions here and the plan has four per group.)
+    auto div_by = [](int x, int c, double rc) {
+        const int qt = __double2int_rz(__int2double_rn(x) * rc);
+        const int r = x - qt * c;
+        return qt + (r >= c ? 1 : 0) - (r < 0 ? 1 : 0);
+    };
+    auto mid_items_of = [&](int q, int c, double rc) {       // chunks of [gs, n-B) on the global grid of c tokens
+        const int gs = s_gs[q], n = s_n[q];
+        const int nb = n - p.band > 0 ? n - p.band : 0;
+        return (gs >= 0 && nb > gs) ? div_by(nb + c - 1, c, rc) - div_by(gs, c, rc) : 0;
+    };
+    auto band_items_of = [&](int q, int c, double rc) {      // chunks of the band [n-B, n) on the same grid
+        const int gs = s_gs[q], n = s_n[q];
+        const int nb = n - p.band > 0 ? n - p.band : 0;
+        return (gs >= 0 && n > nb) ? div_by(n + c - 1, c, rc) - div_by(nb, c, rc) : 0;
+    };
     int C = p.chunk_fixed;
     if (C == 0) {
-        const long long U = p.n_cu;
-        long long N = tok / kAttnChunkPref / U * U;
-        N = N < U ? U : (N > 4 * U ? 4 * U : N);
-        if (N * kAttnChunkMax < tok) N = (tok + U * kAttnChunkMax - 1) / (U * kAttnChunkMax) * U;
-        auto chunk_for = [&](long long items) {
-            long long c = (tok + items - 1) / items;
-            c = (c + 31) & ~31ll;
-            return (int)(c < p.chunk_min ? p.chunk_min : c);
+        const double U = (double)p.n_cu;
+        double N = floor(tok / ((double)kAttnChunkPref * U)) * U;
+        N = N < U ? U : (N > 4.0 * U ? 4.0 * U : N);
+        if (N * kAttnChunkMax < tok) N = ceil(tok / (U * kAttnChunkMax)) * U;
+        if (N < busy) N = ceil(busy / U) * U;
+        auto chunk_for = [&](double items) {
+            const int c = ((int)ceil(tok / items) + 31) & ~31;
+            return c < p.chunk_min ? p.chunk_min : c;
         };
         C = chunk_for(N);
         for (int tries = 0; tries < 6; ++tries) {
             if (C > kAttnChunkMax) { N += U; C = chunk_for(N); }
-            long long items = 0;
-            for (int q = lane; q < NG; q += 64) items += mid_items_of(q, C);
-            items = wave_sum(items);
+            const double rc = 1.0 / (double)C;
+            double items = 0.0;
+            for (int q = first; q < NG; q += stride) items += (double)mid_items_of(q, C, rc);
+            items = total_of(items);
             if (items <= N || C >= kAttnChunkMax) break;
             // too many by `items - N`: lengthen every item by its share of their tokens
-            const long long grow = ((items - N) * C + N - 1) / N;
-            C += (int)((grow + 31) & ~31ll);
+            C += ((int)ceil((items - N) * (double)C / N) + 31) & ~31;
         }
         if (C > kAttnChunkMax) C = kAttnChunkMax;
     }
     C = __builtin_amdgcn_readfirstlane(C);                   // uniform values in scalar registers: what derives from them stays there
-    // ---- plan: prefix sums of the groups' item counts.  The list holds the mid items of all groups first, then the
-    // band items (at most B tokens each).
-    auto prefix_scan = [&](auto count, int* out) {
-        int total = 0;
-        for (int q0 = 0; q0 < NG; q0 += 64) {
-            const int q = q0 + lane;
-            const int items = q < NG ? count(q) : 0;
-            int incl = items;                                // inclusive scan inside the wave
+    const double rC = 1.0 / (double)C;
+    // ---- plan: the list of work items.  It holds the mid items of all groups first, then the band items (at most B
+    // tokens each).  Two levels of prefix sums: inside each block of 64 groups (shared memory, one entry per group),
+    // and over the blocks (at most 32: one per lane, kept in registers by every wave).
+    const int nblk = (NG + 63) >> 6;
+    for (int q0 = 0; q0 < NG; q0 += stride) {
+        const int q = q0 + first;                            // (64 consecutive groups in a wave)
+        const int cm = q < NG ? mid_items_of(q, C, rC) : 0, cb = q < NG ? band_items_of(q, C, rC) : 0;
+        int im = cm, ib = cb;                                // inclusive scans inside the wave
 #pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                const int v = __shfl_up(incl, off);
-                if (lane >= off) incl += v;
-            }
-            if (q < NG) out[q] = total + incl - items;
-            total += __shfl(incl, 63);
+        for (int off = 1; off < 64; off <<= 1) {
+            const int vm = __shfl_up(im, off), vb = __shfl_up(ib, off);
+            if (lane >= off) { im += vm; ib += vb; }
         }
-        if (lane == 0) out[NG] = total;
-        return total;
-    };
-    const int total_mid = __builtin_amdgcn_readfirstlane(prefix_scan([&](int q) { return mid_items_of(q, C); }, s_prefix));
-    const int total = total_mid + __builtin_amdgcn_readfirstlane(prefix_scan([&](int q) { return band_items_of(q, C); }, s_bprefix));
+        if (q < NG) { s_prefix[q] = im - cm; s_bprefix[q] = ib - cb; }
+        if (lane == 63) { s_blk[0][q >> 6] = im; s_blk[1][q >> 6] = ib; }
+    }
+    if (coop) __syncthreads();
+    int off_m = lane < nblk ? s_blk[0][lane] : 0, off_b = lane < nblk ? s_blk[1][lane] : 0;   // -> items before block `lane`
+    {
+        int im = off_m, ib = off_b;
+#pragma unroll
+        for (int off = 1; off < 32; off <<= 1) {
+            const int vm = __shfl_up(im, off), vb = __shfl_up(ib, off);
+            if (lane >= off) { im += vm; ib += vb; }
+        }
+        off_m = im - off_m;
+        off_b = ib - off_b;
+    }
+    const int total_mid = __builtin_amdgcn_readlane(off_m, nblk - 1) + __builtin_amdgcn_readfirstlane(s_blk[0][nblk - 1]);
+    const int total = total_mid + __builtin_amdgcn_readlane(off_b, nblk - 1) + __builtin_amdgcn_readfirstlane(s_blk[1][nblk - 1]);
     if (tid == 0 && blockIdx.x == 0 && p.step_chunk != nullptr) *p.step_chunk = C;
 
     // ---- work items: normally one per work-group (the grid is sized by the same rule); the loop serves launches with a
@@ -266,25 +292,25 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnParams p) {
     // at 8; fixed shares 337 us; one item per dispatched work-group 332 us).
     for (int item = blockIdx.x; item < total; item += P) {
         const bool is_band = item >= total_mid;
-        const int* pre = is_band ? s_bprefix : s_prefix;
         const int pos = is_band ? item - total_mid : item;
-        int lo_q = 0, hi_q = NG;                             // the group: largest q with pre[q] <= pos
-        while (hi_q - lo_q > 1) {
-            const int mid = (lo_q + hi_q) >> 1;
-            if (pre[mid] <= pos) lo_q = mid; else hi_q = mid;
-        }
-        const int q = __builtin_amdgcn_readfirstlane(lo_q);
-        // index of the item inside its group: mid items first, then band items
-        const int k = pos - __builtin_amdgcn_readfirstlane(pre[q]) + (is_band ? __builtin_amdgcn_readfirstlane(mid_items_of(q, C)) : 0);
+        // the block, then the group inside it: the last one whose items start at or before `pos`
+        const int off = is_band ? off_b : off_m;
+        const int j = __popcll(__builtin_amdgcn_ballot_w64(lane < nblk && off <= pos)) - 1;
+        const int qq = 64 * j + lane;
+        const int before = qq < NG ? (is_band ? s_bprefix[qq] : s_prefix[qq]) + __builtin_amdgcn_readlane(off, j) : 0x7fffffff;
+        const int r = __popcll(__builtin_amdgcn_ballot_w64(before <= pos)) - 1;
+        const int q = 64 * j + r;
+        const int k = pos - __builtin_amdgcn_readlane(before, r);      // index among the group's mid (or band) items
         const int n = __builtin_amdgcn_readfirstlane(s_n[q]), gs = __builtin_amdgcn_readfirstlane(s_gs[q]);
-        attn_item<HT>(p, C, q, k, n, gs, s_O, s_m, s_l, s_q, s_skip);
+        attn_item<HT>(p, C, q, is_band, k, n, gs, s_O, s_m, s_l, s_q, s_skip);
         __syncthreads();
     }
 }
 
-// One work item: item `item_k` of KV group q with C tokens per item.  Contains barriers: called by the whole work-group.
+// One work item: the `item_k`-th mid (or band) item of KV group q with C tokens per item.  Contains barriers: called by
+// the whole work-group.
 template <int HT>
-__device__ __forceinline__ void attn_item(const AttnParams& p, const int C, const int q, const int item_k, const int n,
+__device__ __forceinline__ void attn_item(const AttnParams& p, const int C, const int q, const bool is_band, const int item_k, const int n,
                                           const int gs, float (&s_O)[4][HT * 16 * kHeadDim], float (&s_m)[4][HT * 16],
                                           float (&s_l)[4][HT * 16], char* s_q, int (&s_skip)[HT * 16]) {
     constexpr int kQRowBytes = 2 * kHeadDim + 16;
@@ -301,15 +327,12 @@ __device__ __forceinline__ void attn_item(const AttnParams& p, const int C, cons
     const int tiles_per_chunk = C >> 5;
     const int hbase = b * p.Hq + g * G;
     const int nb = n - p.band > 0 ? n - p.band : 0;          // the band is [nb, n)
-    GroupSpan sp;
-    sp.n = n; sp.nb = nb; sp.gs = gs;
-    const int n_mid = mid_items(sp, C);
-    const bool is_mid = item_k < n_mid;
     // chunk index on the global grid of C tokens, the item's token range, and its partial slot
-    const int x = is_mid ? gs / C + item_k : nb / C + (item_k - n_mid);
+    const bool is_mid = !is_band;
+    const int x = (is_mid ? gs : nb) / C + item_k;
     const int lo = is_mid ? max(gs, x * C) : max(nb, x * C);
     const int hi = is_mid ? min(nb, (x + 1) * C) : min(n, (x + 1) * C);
-    const int slot = is_mid ? x : p.n_mid_slots + (item_k - n_mid);
+    const int slot = is_mid ? x : p.n_mid_slots + item_k;
     if (lo >= hi) return;                                    // (the plan lists no empty item)
 
     // Page ids of this wave's 16-token sub-tiles, one per lane and register: lane i of register j <-> (k = 32j + i/2,

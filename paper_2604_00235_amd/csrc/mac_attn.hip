@@ -322,7 +322,8 @@ int launch_attention(mac_attn_ctx* ctx, const mac_attn_step_args* a, bool mac_mo
         int64_t N = tok / mac::kAttnChunkPref / U * U;
         N = std::min<int64_t>(std::max<int64_t>(N, U), 4 * U);
         if (N * mac::kAttnChunkMax < tok) N = (tok + U * mac::kAttnChunkMax - 1) / (U * mac::kAttnChunkMax) * U;
-        max_items = std::min(max_items, std::min<int64_t>(N, ctx->grid_attn) + (mac_mode ? groups : 0));
+        N = std::max(std::min<int64_t>(N, ctx->grid_attn), groups);        // at least one work-group per KV group
+        max_items = std::min(max_items, N + (mac_mode ? groups : 0));
     } else {
         max_items = std::min<int64_t>(max_items, ctx->grid_attn);
     }
