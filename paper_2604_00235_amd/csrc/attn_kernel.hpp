@@ -170,8 +170,7 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnParams p) {
     const int first = coop ? tid : lane, stride = coop ? 256 : 64;
     int parity = 0;
     auto total_of = [&](double v) {                          // the same total in every thread
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) v += __shfl_xor(v, off);
+        v = wave_sum_f64(v);
         if (coop) {
             if (lane == 0) s_red[parity][wv] = v;
             __syncthreads();
@@ -260,27 +259,14 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnParams p) {
     for (int q0 = 0; q0 < NG; q0 += stride) {
         const int q = q0 + first;                            // (64 consecutive groups in a wave)
         const int cm = q < NG ? mid_items_of(q, C, rC) : 0, cb = q < NG ? band_items_of(q, C, rC) : 0;
-        int im = cm, ib = cb;                                // inclusive scans inside the wave
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const int vm = __shfl_up(im, off), vb = __shfl_up(ib, off);
-            if (lane >= off) { im += vm; ib += vb; }
-        }
+        const int im = wave_scan_incl_i32(cm, lane), ib = wave_scan_incl_i32(cb, lane);
         if (q < NG) { s_prefix[q] = im - cm; s_bprefix[q] = ib - cb; }
         if (lane == 63) { s_blk[0][q >> 6] = im; s_blk[1][q >> 6] = ib; }
     }
     if (coop) __syncthreads();
     int off_m = lane < nblk ? s_blk[0][lane] : 0, off_b = lane < nblk ? s_blk[1][lane] : 0;   // -> items before block `lane`
-    {
-        int im = off_m, ib = off_b;
-#pragma unroll
-        for (int off = 1; off < 32; off <<= 1) {
-            const int vm = __shfl_up(im, off), vb = __shfl_up(ib, off);
-            if (lane >= off) { im += vm; ib += vb; }
-        }
-        off_m = im - off_m;
-        off_b = ib - off_b;
-    }
+    off_m = wave_scan_incl_i32(off_m, lane) - off_m;
+    off_b = wave_scan_incl_i32(off_b, lane) - off_b;
     const int total_mid = __builtin_amdgcn_readlane(off_m, nblk - 1) + __builtin_amdgcn_readfirstlane(s_blk[0][nblk - 1]);
     const int total = total_mid + __builtin_amdgcn_readlane(off_b, nblk - 1) + __builtin_amdgcn_readfirstlane(s_blk[1][nblk - 1]);
     if (tid == 0 && blockIdx.x == 0 && p.step_chunk != nullptr) *p.step_chunk = C;
