@@ -44,6 +44,7 @@ __device__ __forceinline__ float dpp_f32(float v) {
     return bits_to_float((uint32_t)__builtin_amdgcn_update_dpp((int)float_to_bits(v), (int)float_to_bits(v), kCtrl, 0xf, 0xf, false));
 }
 constexpr int kDppQuadSwap1 = 0xB1, kDppQuadSwap2 = 0x4E, kDppRowHalfMirror = 0x141, kDppRowMirror = 0x140;
+constexpr int kDppRowRor8 = 0x128;        // lane ^ 8 inside a row of 16
 #define MAC_WAVE_REDUCE(NAME, OP)                                                                    \
     __device__ __forceinline__ float NAME(float v) {                                                 \
         v = OP(v, dpp_f32<kDppQuadSwap1>(v));                                                        \

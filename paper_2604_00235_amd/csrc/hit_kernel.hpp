@@ -49,6 +49,7 @@ constexpr int kHitMaxSpan = 2048;            // largest fresh range finished her
 // accumulated in fp32 (128 x 2^-23 each, against (|q| + |r|)^2 <= 2 (|q|^2 + |r|^2) in total: 3.1e-5), taken four
 // times over to be independent of how the matrix core orders and rounds its partial sums.
 constexpr float kFilterEps = 1.25e-4f;
+constexpr float kFilterTiny = 1e-30f;        // below this |q|^2 + |r|^2 single products may underflow: no bound claimed
 constexpr double kTieRel = 0x1p-40;          // two fp64 evaluations of one distance differ by far less than this
 
 struct HitParams {
@@ -117,6 +118,45 @@ __device__ __forceinline__ double sq_dist_packed(const u32x4 (&q)[4], const u32x
     return s0 + s1;
 }
 
+// Sum of eight products of bf16 pairs, accumulated in fp32 (v_dot2c_f32_bf16: two exact products and the accumulator
+// per instruction).  The pairs are taken out of the 8-element vector with shuffles: going through the 32-bit words
+// (bit_cast of x[e]) makes this compiler use the first word four times.
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+__device__ __forceinline__ float dot8_bf16(const u32x4& x, const u32x4& y) {
+    const bf16x8 vx = __builtin_bit_cast(bf16x8, x), vy = __builtin_bit_cast(bf16x8, y);
+    float acc = 0.f;
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(vx, vx, 0, 1), __builtin_shufflevector(vy, vy, 0, 1), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(vx, vx, 2, 3), __builtin_shufflevector(vy, vy, 2, 3), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(vx, vx, 4, 5), __builtin_shufflevector(vy, vy, 4, 5), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(vx, vx, 6, 7), __builtin_shufflevector(vy, vy, 6, 7), acc, false);
+    return acc;
+}
+// Sums over the 16 lanes of a row of the wave (DPP), the same in each of them
+__device__ __forceinline__ float row_sum_f32(float v) {
+    v += dpp_f32<kDppQuadSwap1>(v);
+    v += dpp_f32<kDppQuadSwap2>(v);
+    v += dpp_f32<kDppRowHalfMirror>(v);
+    return v + dpp_f32<kDppRowMirror>(v);
+}
+__device__ __forceinline__ double row_sum_f64(double v) {
+    v += dpp_f64<kDppQuadSwap1>(v);
+    v += dpp_f64<kDppQuadSwap2>(v);
+    v += dpp_f64<kDppRowHalfMirror>(v);
+    return v + dpp_f64<kDppRowMirror>(v);
+}
+// One lane's share of a squared distance in fp64: a 16-byte chunk of the query against the same chunk of a ring row
+__device__ __forceinline__ double sq_dist_chunk(const u32x4& q, const u32x4& v) {
+    double s0 = 0.0, s1 = 0.0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const double d0 = bf16_lo_to_f64(q[e]) - bf16_lo_to_f64(v[e]);
+        const double d1 = bf16_hi_to_f64(q[e]) - bf16_hi_to_f64(v[e]);
+        s0 = fma(d0, d0, s0);
+        s1 = fma(d1, d1, s1);
+    }
+    return s0 + s1;
+}
+
 template <int NT>      // threads per work-group: 256, or 1024 when there are few heads and a large window
 __global__ __launch_bounds__(NT, NT == 256 ? 4 : 1) void hit_kernel(const HitParams p) {
     constexpr int NW = NT / 64;
@@ -158,75 +198,64 @@ __global__ __launch_bounds__(NT, NT == 256 ? 4 : 1) void hit_kernel(const HitPar
     double best_d2 = INFINITY, second_d2 = INFINITY;           // nearest candidate and the distance of the next one
     int best_np = -1, best_j = -1;
     {
-        const int r16 = lane & 15, kg = lane >> 4;
-        u32x4 qraw[4];                                         // this lane's 16-byte chunks kg, kg + 4, kg + 8, kg + 12 of the query:
-        float qq = 0.f;                                        // the B operand (the query in every column), and |q|^2
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            qraw[c] = *reinterpret_cast<const u32x4*>(q_h + 32 * c + 8 * kg);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float lo = bf16_lo_to_f32(qraw[c][e]), hi = bf16_hi_to_f32(qraw[c][e]);
-                qq = fmaf(lo, lo, qq);
-                qq = fmaf(hi, hi, qq);
-            }
-        }
-        qq = add_xor32(add_xor16(qq));
-        const int pick = r16 & 3;                              // component of a tile's result that belongs to row r16 ...
-        const bool diag = kg == (r16 >> 2);                    // ... in the lane that holds it
+        // A load instruction takes four whole rows (1 KiB contiguous: lane = 16 x (row of the four) + 16-byte chunk of
+        // the row): the pattern one compute unit pulls fastest (~110 GB/s from the caches against ~36 GB/s with 16 rows
+        // x 64 bytes per instruction, the layout a matrix-core operand would need).  A wave holds a block of 64 rows
+        // in 16 such loads; each lane forms its chunk's share of |r|^2 - 2 q.r for the 16 rows it has a chunk of,
+        // and a butterfly over the 16 lanes of a row of the wave (partners lane ^ 8, ^ 7, ^ 2, ^ 1: the exchanges
+        // DPP offers) leaves every lane with the complete sum of one row -- the row it "owns" below.
+        const int rsub = lane >> 4, ch = lane & 15;
+        const bool bA = (ch & 8) != 0, bB = (ch & 4) != 0, bC = (((ch >> 1) ^ (ch >> 2)) & 1) != 0, bD = ((ch ^ (ch >> 2)) & 1) != 0;
+        const int own_i = 8 * (int)bA + 4 * (int)bB + 2 * (int)bC + (int)bD;    // load number of the row this lane owns
+        const u32x4 qc = *reinterpret_cast<const u32x4*>(q_h + 8 * ch);      // this lane's chunk of the query
+        const float qq = row_sum_f32(dot8_bf16(qc, qc));       // |q|^2 (the same in every lane)
         float U = INFINITY;                                    // smallest upper bound the work-group has seen so far
-        const int n_tiles = (W + 15) >> 4;
-        constexpr int kInFlight = 4;                           // 16-row tiles requested per wave before the arithmetic
+        const int n_blocks = (W + 63) >> 6;
         int parity = 0;
-        for (int base = 0; base < n_tiles; base += NW * kInFlight, parity ^= 1) {       // the same trip count in every wave
-            const int t0 = base + w;
-            u32x4 a[kInFlight][4];
-            int tag[kInFlight];
+        for (int base = 0; base < n_blocks; base += NW, parity ^= 1) {       // the same trip count in every wave
+            const int row0 = 64 * (base + w);
+            u32x4 a[16];
 #pragma unroll
-            for (int u = 0; u < kInFlight; ++u) {
-                const int row = min(16 * (t0 + u * NW) + r16, W - 1);      // keeps the loads inside the ring
-                const uint16_t* rp = ring_h + (int64_t)row * kHeadDim + 8 * kg;
-#pragma unroll
-                for (int c = 0; c < 4; ++c) a[u][c] = *reinterpret_cast<const u32x4*>(rp + 32 * c);
-                tag[u] = npos[row];
+            for (int i = 0; i < 16; ++i) {
+                const int row = min(row0 + 4 * i + rsub, W - 1);           // keeps the loads inside the ring
+                a[i] = *reinterpret_cast<const u32x4*>(ring_h + (int64_t)row * kHeadDim + 8 * ch);
             }
-            float lower[kInFlight];
+            const int own = row0 + 4 * own_i + rsub;
+            const int tag = npos[min(own, W - 1)];
+            float part[16];                                    // this lane's chunk of |r|^2 - 2 q.r, per load
 #pragma unroll
-            for (int u = 0; u < kInFlight; ++u) {
-                const int row = 16 * (t0 + u * NW) + r16;
-                f32x4 dot = f32x4{0.f, 0.f, 0.f, 0.f}, gram = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int i = 0; i < 16; ++i) part[i] = fmaf(-2.f, dot8_bf16(a[i], qc), dot8_bf16(a[i], a[i]));
+            float s8[8], s4[4], s2[2];
 #pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    const bf16x8 ac = __builtin_bit_cast(bf16x8, a[u][c]);
-                    dot = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ac, __builtin_bit_cast(bf16x8, qraw[c]), dot, 0, 0, 0);
-                    gram = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ac, ac, gram, 0, 0, 0);
-                }
-                const float sd = pick == 0 ? dot[0] : pick == 1 ? dot[1] : pick == 2 ? dot[2] : dot[3];
-                const float rr = pick == 0 ? gram[0] : pick == 1 ? gram[1] : pick == 2 ? gram[2] : gram[3];
-                const bool valid = diag && row < W && tag[u] >= np_lo && tag[u] <= np_hi;
-                const float f = qq + rr - 2.f * sd, eps = kFilterEps * (qq + rr);
-                float up = f + eps;
-                lower[u] = f - eps;
-                if (!(fabsf(f) < INFINITY)) { lower[u] = -INFINITY; up = INFINITY; }        // overflow: decided in fp64
-                if (!valid) lower[u] = INFINITY;
-                else U = fminf(U, up);
-            }
+            for (int k = 0; k < 8; ++k) s8[k] = (bA ? part[k + 8] : part[k]) + dpp_f32<kDppRowRor8>(bA ? part[k] : part[k + 8]);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) s4[k] = (bB ? s8[k + 4] : s8[k]) + dpp_f32<kDppRowHalfMirror>(bB ? s8[k] : s8[k + 4]);
+#pragma unroll
+            for (int k = 0; k < 2; ++k) s2[k] = (bC ? s4[k + 2] : s4[k]) + dpp_f32<kDppQuadSwap2>(bC ? s4[k] : s4[k + 2]);
+            const float rr2sd = (bD ? s2[1] : s2[0]) + dpp_f32<kDppQuadSwap1>(bD ? s2[0] : s2[1]);      // |r|^2 - 2 q.r of row `own`
+            const bool valid = own < W && tag >= np_lo && tag <= np_hi;
+            // |f - d2| <= kFilterEps (|q|^2 + |r|^2), and |r|^2 <= (sqrt(d2) + |q|)^2 <= 2 d2 + 2 |q|^2
+            const float f = qq + rr2sd, eps = 1.001f * kFilterEps * (2.f * fmaxf(f, 0.f) + 3.f * qq);
+            float up = f + eps, lower = f - eps;
+            // overflow, or magnitudes so small that products underflow: decided in fp64
+            if (!(fabsf(f) < INFINITY) || qq < kFilterTiny) { lower = -INFINITY; up = INFINITY; }
+            if (!valid) lower = INFINITY;
+            else U = fminf(U, up);
             U = wave_min_f32(U);
             if (lane == 0) s_u[parity][w] = U;
             __syncthreads();
 #pragma unroll
             for (int ww = 0; ww < NW; ++ww) U = fminf(U, s_u[parity][ww]);
-            // tier 2: tiles with a row the filter cannot rule out are evaluated in fp64 where they sit (the lanes
-            // r16, r16 + 16, r16 + 32, r16 + 48 hold the four quarters of row r16, as a quad does in the other matchers)
+            // tier 2: rows the filter cannot rule out are evaluated in fp64 where they sit (load i, the 16 lanes of the
+            // owner's row of the wave)
+            const bool cand = lower <= U && lower < INFINITY;
+            if (__builtin_amdgcn_ballot_w64(cand) != 0) {
 #pragma unroll
-            for (int u = 0; u < kInFlight; ++u) {
-                const bool cand = lower[u] <= U && lower[u] < INFINITY;
-                if (__builtin_amdgcn_ballot_w64(cand) != 0) {
-                    double d2 = sq_dist_packed(qraw, a[u]);
-                    d2 = add_xor32(add_xor16(d2));
-                    if (cand) {                                // (only the lane that holds the row's bound)
-                        const int row = 16 * (t0 + u * NW) + r16;
-                        if (better(d2, tag[u], best_d2, best_np)) { second_d2 = best_d2; best_d2 = d2; best_np = tag[u]; best_j = row; }
+                for (int i = 0; i < 16; ++i) {
+                    if (__builtin_amdgcn_ballot_w64(cand && own_i == i) == 0) continue;
+                    const double d2 = row_sum_f64(sq_dist_chunk(qc, a[i]));
+                    if (cand && own_i == i) {
+                        if (better(d2, tag, best_d2, best_np)) { second_d2 = best_d2; best_d2 = d2; best_np = tag; best_j = own; }
                         else second_d2 = fmin(second_d2, d2);
                     }
                 }
