@@ -365,46 +365,29 @@ __global__ __launch_bounds__(NT, NT == 256 ? 4 : 1) void hit_kernel(const HitPar
         pre_l = p.ring_lse[pre];
         pre_o = p.ring_O[pre * kHeadDim + tid];
     }
-    u32x4 qv[4];                                               // this lane's 32 elements of the post-RoPE query
-    {
-        const uint16_t* qp = p.q_rope + (int64_t)bh * kHeadDim + 8 * sub;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) qv[i] = *reinterpret_cast<const u32x4*>(qp + 32 * i);
-    }
-    // weighted sums of V rows: 16 lanes cover a 256-byte row, a wave takes 4 rows per load; the first kVPre rows of
-    // every thread are requested now
-    constexpr int kRowGroups = NT / 16, kVPre = 8;
+    // K and V rows are read alike: 16 lanes cover a 256-byte row, a wave takes 4 whole rows per load instruction (the
+    // pattern a compute unit pulls fastest, see the match above); the first kVPre V rows of every thread are requested
+    // together with its first K rows.
+    constexpr int kRowGroups = NT / 16, kKPass = NT == 256 ? 9 : 8, kVPre = kKPass;   // (256 threads: one pass for B + 1 = 129 rows)
     const int col = tid & 15, rg = tid >> 4;
+    const u32x4 qk = *reinterpret_cast<const u32x4*>(p.q_rope + (int64_t)bh * kHeadDim + 8 * col);    // this lane's chunk of the post-RoPE query
     u32x4 vpre[kVPre];
-    // logits (log2 domain), a quad per K row
-    for (int r0 = 0; r0 < cnt; r0 += 2 * kRows) {
-        u32x4 kk[2][4];
+    // logits (log2 domain): each lane its chunk's share (v_dot2c_f32_bf16), summed over the 16 lanes of the row
+    for (int r0 = 0; r0 < cnt; r0 += kKPass * kRowGroups) {
+        u32x4 kk[kKPass];
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const uint16_t* rp = row_ptr(min(r0 + u * kRows + quad, cnt - 1)) + 8 * sub;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) kk[u][i] = *reinterpret_cast<const u32x4*>(rp + 32 * i);
-        }
+        for (int u = 0; u < kKPass; ++u)
+            kk[u] = *reinterpret_cast<const u32x4*>(row_ptr(min(r0 + u * kRowGroups + rg, cnt - 1)) + 8 * col);
         if (r0 == 0) {
 #pragma unroll
             for (int u = 0; u < kVPre; ++u)
                 vpre[u] = *reinterpret_cast<const u32x4*>(row_ptr(min(u * kRowGroups + rg, cnt - 1)) + p.stride_kv + 8 * col);
         }
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            float d0 = 0.f, d1 = 0.f;
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    d0 = fmaf(bf16_lo_to_f32(qv[i][e]), bf16_lo_to_f32(kk[u][i][e]), d0);
-                    d1 = fmaf(bf16_hi_to_f32(qv[i][e]), bf16_hi_to_f32(kk[u][i][e]), d1);
-                }
-            float dot = d0 + d1;
-            dot += __shfl_xor(dot, 1);
-            dot += __shfl_xor(dot, 2);
-            const int r = r0 + u * kRows + quad;
-            if (sub == 0 && r < cnt) s_logit[r] = dot * p.scale_log2;
+        for (int u = 0; u < kKPass; ++u) {
+            const float dot = row_sum_f32(dot8_bf16(kk[u], qk));
+            const int r = r0 + u * kRowGroups + rg;
+            if (col == 0 && r < cnt) s_logit[r] = dot * p.scale_log2;
         }
     }
     __syncthreads();
