@@ -157,8 +157,11 @@ __device__ __forceinline__ double sq_dist_chunk(const u32x4& q, const u32x4& v) 
     return s0 + s1;
 }
 
-template <int NT>      // threads per work-group: 256, or 1024 when there are few heads and a large window
-__global__ __launch_bounds__(NT, NT == 256 ? 4 : 1) void hit_kernel(const HitParams p) {
+// NT = threads per work-group: 256, or 1024 when there are few heads and a large window.  kLean (256 threads only): fewer
+// loads in flight per wave (half a block of the window, five K/V rows), which fits five work-groups on a compute unit
+// instead of four: for launches with more heads than the chip holds work-groups.
+template <int NT, bool kLean>
+__global__ __launch_bounds__(NT, NT == 256 ? (kLean ? 5 : 4) : 1) void hit_kernel(const HitParams p) {
     constexpr int NW = NT / 64;
     constexpr int kRows = NT / 4;                              // ring rows (or K rows) per pass: a quad per 256-byte row
     // Work-groups are dealt to the 8 XCDs in turn: the G heads of a KV group take ids that are 8 apart.
@@ -206,34 +209,39 @@ __global__ __launch_bounds__(NT, NT == 256 ? 4 : 1) void hit_kernel(const HitPar
         // DPP offers) leaves every lane with the complete sum of one row -- the row it "owns" below.
         const int rsub = lane >> 4, ch = lane & 15;
         const bool bA = (ch & 8) != 0, bB = (ch & 4) != 0, bC = (((ch >> 1) ^ (ch >> 2)) & 1) != 0, bD = ((ch ^ (ch >> 2)) & 1) != 0;
-        const int own_i = 8 * (int)bA + 4 * (int)bB + 2 * (int)bC + (int)bD;    // load number of the row this lane owns
+        constexpr int kLoads = kLean ? 8 : 16;                 // loads (of four rows) per block of the window and wave
+        const int own_i = (kLean ? 0 : 8 * (int)bA) + 4 * (int)bB + 2 * (int)bC + (int)bD;    // load number of the row this lane owns
+        const bool owner = !kLean || !bA;                      // (with 8 loads per block each row's sum ends up in two lanes)
         const u32x4 qc = *reinterpret_cast<const u32x4*>(q_h + 8 * ch);      // this lane's chunk of the query
         const float qq = row_sum_f32(dot8_bf16(qc, qc));       // |q|^2 (the same in every lane)
         float U = INFINITY;                                    // smallest upper bound the work-group has seen so far
-        const int n_blocks = (W + 63) >> 6;
+        const int n_blocks = (W + 4 * kLoads - 1) / (4 * kLoads);
         int parity = 0;
         for (int base = 0; base < n_blocks; base += NW, parity ^= 1) {       // the same trip count in every wave
-            const int row0 = 64 * (base + w);
-            u32x4 a[16];
+            const int row0 = 4 * kLoads * (base + w);
+            u32x4 a[kLoads];
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
+            for (int i = 0; i < kLoads; ++i) {
                 const int row = min(row0 + 4 * i + rsub, W - 1);           // keeps the loads inside the ring
                 a[i] = *reinterpret_cast<const u32x4*>(ring_h + (int64_t)row * kHeadDim + 8 * ch);
             }
             const int own = row0 + 4 * own_i + rsub;
             const int tag = npos[min(own, W - 1)];
-            float part[16];                                    // this lane's chunk of |r|^2 - 2 q.r, per load
+            float part[kLoads];                                // this lane's chunk of |r|^2 - 2 q.r, per load
 #pragma unroll
-            for (int i = 0; i < 16; ++i) part[i] = fmaf(-2.f, dot8_bf16(a[i], qc), dot8_bf16(a[i], a[i]));
+            for (int i = 0; i < kLoads; ++i) part[i] = fmaf(-2.f, dot8_bf16(a[i], qc), dot8_bf16(a[i], a[i]));
             float s8[8], s4[4], s2[2];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) s8[k] = (bA ? part[k + 8] : part[k]) + dpp_f32<kDppRowRor8>(bA ? part[k] : part[k + 8]);
+            for (int k = 0; k < 8; ++k) {
+                if constexpr (kLean) s8[k] = part[k] + dpp_f32<kDppRowRor8>(part[k]);
+                else s8[k] = (bA ? part[k + 8] : part[k]) + dpp_f32<kDppRowRor8>(bA ? part[k] : part[k + 8]);
+            }
 #pragma unroll
             for (int k = 0; k < 4; ++k) s4[k] = (bB ? s8[k + 4] : s8[k]) + dpp_f32<kDppRowHalfMirror>(bB ? s8[k] : s8[k + 4]);
 #pragma unroll
             for (int k = 0; k < 2; ++k) s2[k] = (bC ? s4[k + 2] : s4[k]) + dpp_f32<kDppQuadSwap2>(bC ? s4[k] : s4[k + 2]);
             const float rr2sd = (bD ? s2[1] : s2[0]) + dpp_f32<kDppQuadSwap1>(bD ? s2[0] : s2[1]);      // |r|^2 - 2 q.r of row `own`
-            const bool valid = own < W && tag >= np_lo && tag <= np_hi;
+            const bool valid = owner && own < W && tag >= np_lo && tag <= np_hi;
             // |f - d2| <= kFilterEps (|q|^2 + |r|^2), and |r|^2 <= (sqrt(d2) + |q|)^2 <= 2 d2 + 2 |q|^2
             const float f = qq + rr2sd, eps = 1.001f * kFilterEps * (2.f * fmaxf(f, 0.f) + 3.f * qq);
             float up = f + eps, lower = f - eps;
@@ -251,7 +259,7 @@ __global__ __launch_bounds__(NT, NT == 256 ? 4 : 1) void hit_kernel(const HitPar
             const bool cand = lower <= U && lower < INFINITY;
             if (__builtin_amdgcn_ballot_w64(cand) != 0) {
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
+                for (int i = 0; i < kLoads; ++i) {
                     if (__builtin_amdgcn_ballot_w64(cand && own_i == i) == 0) continue;
                     const double d2 = row_sum_f64(sq_dist_chunk(qc, a[i]));
                     if (cand && own_i == i) {
@@ -368,7 +376,7 @@ __global__ __launch_bounds__(NT, NT == 256 ? 4 : 1) void hit_kernel(const HitPar
     // K and V rows are read alike: 16 lanes cover a 256-byte row, a wave takes 4 whole rows per load instruction (the
     // pattern a compute unit pulls fastest, see the match above); the first kVPre V rows of every thread are requested
     // together with its first K rows.
-    constexpr int kRowGroups = NT / 16, kKPass = NT == 256 ? 9 : 8, kVPre = kKPass;   // (256 threads: one pass for B + 1 = 129 rows)
+    constexpr int kRowGroups = NT / 16, kKPass = NT == 256 ? (kLean ? 5 : 9) : 8, kVPre = kKPass;   // (256 threads: one pass for B + 1 = 129 rows; lean: 65)
     const int col = tid & 15, rg = tid >> 4;
     const u32x4 qk = *reinterpret_cast<const u32x4*>(p.q_rope + (int64_t)bh * kHeadDim + 8 * col);    // this lane's chunk of the post-RoPE query
     u32x4 vpre[kVPre];

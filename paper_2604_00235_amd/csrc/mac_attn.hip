@@ -648,10 +648,13 @@ int mac_attn_decode_step(mac_attn_ctx* ctx, const mac_attn_step_args* args, void
         const int groups = args->batch * c.num_kv_heads;
         const int grid = ((groups + 7) / 8) * 8 * ctx->L.G;
         // few heads and a window of several 64-row passes: 1024-thread work-groups scan it in fewer round trips
-        if ((int64_t)args->batch * c.num_q_heads <= 128 && c.window > 256)
-            hipLaunchKernelGGL(mac::hit_kernel<1024>, dim3(grid), dim3(1024), 0, stream, p);
+        const int64_t heads = (int64_t)args->batch * c.num_q_heads;
+        if (heads <= 128 && c.window > 256)
+            hipLaunchKernelGGL((mac::hit_kernel<1024, false>), dim3(grid), dim3(1024), 0, stream, p);
+        else if (heads > 4 * (int64_t)ctx->n_cu)      // more heads than four work-groups per compute unit: the lean variant fits five
+            hipLaunchKernelGGL((mac::hit_kernel<256, true>), dim3(grid), dim3(256), 0, stream, p);
         else
-            hipLaunchKernelGGL(mac::hit_kernel<256>, dim3(grid), dim3(256), 0, stream, p);
+            hipLaunchKernelGGL((mac::hit_kernel<256, false>), dim3(grid), dim3(256), 0, stream, p);
         HIP_TRY(hipGetLastError());
         t.done(0);
     } else {
