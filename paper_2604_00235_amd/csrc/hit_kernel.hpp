@@ -9,19 +9,22 @@
 // does all of it for the common case:
 //
 //   1. match: the head's whole window of the query ring, in three tiers.
-//      (a) Filter on the matrix cores: a 16-row tile of ring rows is the A operand (16 rows x 64 contiguous bytes per
-//          load instruction: the natural access pattern of the ring), the query fills every column of B, and two
-//          v_mfma_f32_16x16x32_bf16 chains give q.r_j and the Gram diagonal |r_j|^2 of the tile, hence
-//          f_j = |q|^2 + |r_j|^2 - 2 q.r_j with a proven bound |f_j - d2_j| <= eps_j (bf16 products are exact in fp32; only
-//          the accumulation rounds).  U = min_j (f_j + eps_j) over the work-group bounds the nearest distance from above.
+//      (a) Filter in fp32: ring rows are read four whole rows per load instruction (1 KiB contiguous; one compute unit
+//          pulls that pattern ~3x faster than 16 rows x 64 bytes per instruction, the layout a matrix-core operand
+//          needs, which is why the filter does not use the matrix cores: measured 110 against 36 GB/s from the
+//          caches).  Each lane forms its 16-byte chunk's share of |r_j|^2 - 2 q.r_j with v_dot2c_f32_bf16 for the 16
+//          rows it holds a chunk of, a butterfly over the 16 lanes of a row of the wave completes one row's sum per
+//          lane, and f_j = |q|^2 + |r_j|^2 - 2 q.r_j carries a proven bound |f_j - d2_j| <= eps_j (bf16 products are
+//          exact in fp32; only the accumulation rounds).  U = min_j (f_j + eps_j) over the work-group bounds the
+//          nearest distance from above.
 //      (b) Rows with f_j - eps_j <= U -- typically one -- are evaluated in fp64 (exact differences, fp64 FMAs) in the
 //          registers they were loaded into; argmin with ties to the larger n_p.
 //      (c) Two fp64 evaluations of one distance agree to ~2^-46 relative.  If the runner-up, or the threshold, lies
 //          within 2^-40 of the winner, the rows in question are summed once more in index order without FMAs, the
 //          plain left-to-right sum a reference takes, so that the decision is the same bit for bit by construction.
 //      An fp64 scan of every row (the first version of this kernel) kept a compute unit's VALU busy for 5 us per 1024
-//      rows of one head; the filter leaves it idle and the scan is bound by how fast one compute unit pulls the ring
-//      (~30 GB/s: 256 KB in 8.5 us), which only spreading a head over several compute units would lift.
+//      rows of one head; a filter on the matrix cores was bound by the operand layout's access pattern (256 KB of one
+//      head in 8.2 us); this one scans them in 3.5 us.
 //      The decision, the head's counters and the caller's match_pos / match_d2 are written here.
 //   2. if the head hits and its fresh range [s, n), s = max(0, n_p - B), has at most `fused_span` tokens, the same
 //      work-group computes the two summaries the method needs -- mid = [s, n-B) and band = [n-B, n) -- with plain
@@ -47,7 +50,8 @@ namespace mac {
 constexpr int kHitMaxSpan = 2048;            // largest fresh range finished here: its logits sit in shared memory
 // Error bound of the filter, relative to |q|^2 + |r|^2: the three dot products are sums of 128 exact bf16 x bf16 products
 // accumulated in fp32 (128 x 2^-23 each, against (|q| + |r|)^2 <= 2 (|q|^2 + |r|^2) in total: 3.1e-5), taken four
-// times over to be independent of how the matrix core orders and rounds its partial sums.
+// times over to be independent of how the dot instruction and the butterfly order and round their partial sums
+// (measured for v_dot2c_f32_bf16 chains of 128 products: 9.4e-8 of the sum of the products' magnitudes).
 constexpr float kFilterEps = 1.25e-4f;
 constexpr float kFilterTiny = 1e-30f;        // below this |q|^2 + |r|^2 single products may underflow: no bound claimed
 constexpr double kTieRel = 0x1p-40;          // two fp64 evaluations of one distance differ by far less than this
