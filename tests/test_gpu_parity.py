@@ -148,9 +148,9 @@ def test_error_paths_on_device():
                                                  (8, 2, 4096, 1)])
 def test_recurring_queries_large_window_split_match(hq, hkv, window, batch, span):
     """Second query model (reuse gaps of tens to hundreds of tokens with skew inside a KV group, whole-group misses):
-    exercises large windows, where the matcher cuts the window into slices (16 slices at W=1024 and batch 1) and
-    the consumers finish the argmin, including groups that need more than one wave pass (G x slices > 64) and a
-    window that is not a multiple of the slice size, and the largest window (32 slices)."""
+    exercises large windows (the 1024-thread matcher for few heads, several 64-row blocks per wave, a window that is
+    not a multiple of the block size, the largest window of 4096 entries), with the fused hit path on, off, and limited to
+    ranges of 100 tokens so that heads finished by the matcher and heads left to the split-K path mix inside a group."""
     from tests.gpu_harness import run_parity
     cfg = WorkloadConfig(name=f"recur{hq}_{hkv}_{window}", batch=batch, num_q_heads=hq, num_kv_heads=hkv, context=1500,
                          steps=150, window=window, band=48, threshold=T_DEFAULT, rho=0.0, seed=21, period=40,
