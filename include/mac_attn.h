@@ -37,7 +37,7 @@ extern "C" {
 
 #define MAC_ATTN_OK               0
 #define MAC_ATTN_ERR_INVALID_ARG (-1)   /* null pointer, out-of-range size, inconsistent geometry        */
-#define MAC_ATTN_ERR_UNSUPPORTED (-2)   /* valid request this build cannot serve (e.g. head_dim != 128) */
+#define MAC_ATTN_ERR_UNSUPPORTED (-2)   /* valid request this build cannot serve (e.g. head_dim 256) */
 #define MAC_ATTN_ERR_HIP         (-3)   /* a HIP runtime call failed; see mac_attn_last_hip_error        */
 #define MAC_ATTN_ERR_OOM         (-4)   /* device allocation failed                                      */
 #define MAC_ATTN_ERR_CORRUPT     (-5)   /* mac_attn_check_guards found an overwritten guard zone         */
@@ -53,7 +53,9 @@ typedef struct mac_attn_config {
     int32_t max_batch;     /* largest batch of one call (1 .. max_slots)                                  */
     int32_t num_q_heads;   /* Hq                                                                          */
     int32_t num_kv_heads;  /* Hkv; Hq % Hkv == 0, group size G = Hq/Hkv in 1 .. 32                        */
-    int32_t head_dim;      /* must be 128                                                                 */
+    int32_t head_dim;      /* d: 32, 64, 96 or 128 (q, out and K/V rows have d elements; inside the library
+                              rows are widened to 128, so rings and workspace do not shrink with d); other
+                              values are MAC_ATTN_ERR_UNSUPPORTED                                          */
     int32_t page_size;     /* tokens per KV page: a power of two >= 16                                    */
     int32_t window;        /* W >= 1 (paper's K), at most 4096                                            */
     int32_t band;          /* B >= 0 (paper's r)                                                          */
@@ -149,7 +151,7 @@ typedef struct mac_attn_static_geometry {
     int32_t device;        /* HIP device ordinal (made current by the call), 0 .. 63                              */
     int32_t num_q_heads;   /* Hq                                                                                  */
     int32_t num_kv_heads;  /* Hkv; Hq % Hkv == 0, G = Hq/Hkv <= 32                                                */
-    int32_t head_dim;      /* must be 128                                                                         */
+    int32_t head_dim;      /* 32, 64, 96 or 128                                                                   */
     int32_t page_size;     /* tokens per KV page: a power of two >= 16                                            */
     float   sm_scale;      /* softmax scale; <= 0 selects 1/sqrt(head_dim)                                        */
     int32_t max_kv_len;    /* upper bound of kv_len: fixes the launch grid and the workspace layout               */
@@ -183,7 +185,9 @@ int mac_attn_ring_peek(mac_attn_ctx* ctx, int32_t slot, int32_t j, int32_t h,
 int mac_attn_check_guards(mac_attn_ctx* ctx);
 
 /* Bytes of ring state per (ring set, head, entry): bf16 query + fp32 summary row + fp32 ln-LSE
- * (Sec. 5.9 "Auxiliary HBM overhead").  Pure host arithmetic. */
+ * (Sec. 5.9 "Auxiliary HBM overhead").  Rows are stored 128 elements wide whatever head_dim is (772 bytes), so a
+ * head_dim below 128 pays for the padding; MAC_ATTN_ERR_UNSUPPORTED for a head_dim the library does not take.
+ * Pure host arithmetic. */
 int64_t mac_attn_ring_entry_bytes(int32_t head_dim);
 
 /* Device bytes a context with this configuration allocates (rings + workspace + counters), or a negative

@@ -52,7 +52,7 @@ struct AttnParams {
     const int32_t* kv_lens;      // [batch]
     const int32_t* head_start;   // [batch*Hq + 32] first key of each head's fresh range, | kHeadDone if the matcher has
                                  // finished the head; null = full decode (every head starts at 0)
-    const uint16_t* q_rope;      // [batch, Hq, 128] bf16
+    const uint16_t* q_rope;      // [batch, Hq, d] bf16
     const uint16_t* kv_pages;    // paged cache, bf16
     int64_t stride_page, stride_kv, stride_head, stride_tok;   // elements
     const int32_t* block_table;  // [batch, bt_stride]
@@ -60,6 +60,7 @@ struct AttnParams {
     float* part_O;               // [batch*Hq, n_slots, 128] normalised partial outputs
     float* part_lse;             // [batch*Hq, n_slots]      natural-log LSE of each partial
     int32_t batch, Hq, G;
+    int32_t head_dim;            // d of the caller's tensors: 32, 64, 96 or 128 (rows are widened to 128 in here)
     int32_t page_shift;          // log2(page_size)
     int32_t band;                // B; 0 for full decode (no band work items)
     int32_t chunk_fixed;         // > 0: tokens per work item fixed by the caller (multiple of 32, <= 4096);
@@ -127,7 +128,7 @@ constexpr int kAttnChunkPref = 2048;     // the planner makes fewer items rather
 
 template <int HT> struct AttnCaps { static constexpr int kMaxGroups = HT == 1 ? 2048 : 256; };
 
-template <int HT>
+template <int HT, bool kFullDim>
 __device__ __forceinline__ void attn_item(const AttnParams& p, int C, int q, bool is_band, int item_k, int n, int gs,
                                           float (&s_O)[4][HT * 16 * kHeadDim], float (&s_m)[4][HT * 16],
                                           float (&s_l)[4][HT * 16], char* s_q, int (&s_skip)[HT * 16]);
@@ -140,7 +141,11 @@ __device__ __forceinline__ void attn_item(const AttnParams& p, int C, int q, boo
 // host launches as many work-groups as the same rule makes items for max_kv_len tokens per group: normally one item
 // per work-group, handed out by the hardware dispatcher as earlier work-groups finish.  A step whose heads were all
 // finished by the matcher costs one load per work-group.
-template <int HT>   // number of 16-head tiles: 1 (G <= 16) or 2 (G <= 32)
+// HT = number of 16-head tiles: 1 (G <= 16) or 2 (G <= 32).  kFullDim = the head dimension is 128; otherwise (32, 64, 96)
+// the kernel works on rows widened to 128: the queries are padded with zeros, K loads of the missing k-steps and V loads of
+// the missing columns re-read the row's last valid 64 / 16 bytes (so that the loads of a tile stay the same in number), and
+// the columns d .. 127 of the partial results are never looked at by anyone.
+template <int HT, bool kFullDim>
 __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnParams p) {
     // Shared memory.  s_O carries the waves' states to the merge at the end.  With two head tiles (HT == 2) a wave
     // keeps only one tile's output accumulators in registers: during the stream s_O[w] holds both tiles'
@@ -288,14 +293,14 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnParams p) {
         const int q = 64 * j + r;
         const int k = pos - __builtin_amdgcn_readlane(before, r);      // index among the group's mid (or band) items
         const int n = __builtin_amdgcn_readfirstlane(s_n[q]), gs = __builtin_amdgcn_readfirstlane(s_gs[q]);
-        attn_item<HT>(p, C, q, is_band, k, n, gs, s_O, s_m, s_l, s_q, s_skip);
+        attn_item<HT, kFullDim>(p, C, q, is_band, k, n, gs, s_O, s_m, s_l, s_q, s_skip);
         __syncthreads();
     }
 }
 
 // One work item: the `item_k`-th mid (or band) item of KV group q with C tokens per item.  Contains barriers: called by
 // the whole work-group.
-template <int HT>
+template <int HT, bool kFullDim>
 __device__ __forceinline__ void attn_item(const AttnParams& p, const int C, const int q, const bool is_band, const int item_k, const int n,
                                           const int gs, float (&s_O)[4][HT * 16 * kHeadDim], float (&s_m)[4][HT * 16],
                                           float (&s_l)[4][HT * 16], char* s_q, int (&s_skip)[HT * 16]) {
@@ -367,13 +372,14 @@ __device__ __forceinline__ void attn_item(const AttnParams& p, const int C, cons
         const int idx = tid + 256 * t, row = idx >> 4, ch = idx & 15;
         const int rowc = row < G ? row : 0;
         qflag[t] = p.head_start != nullptr ? p.head_start[hbase + rowc] : 0;
-        qv[t] = *reinterpret_cast<const u32x4*>(p.q_rope + (int64_t)(hbase + rowc) * kHeadDim + 8 * ch);
+        const int chc = kFullDim ? ch : min(ch, (p.head_dim >> 3) - 1);
+        qv[t] = *reinterpret_cast<const u32x4*>(p.q_rope + (int64_t)(hbase + rowc) * (kFullDim ? kHeadDim : p.head_dim) + 8 * chc);
     }
     auto stage_queries = [&]() {
 #pragma unroll
         for (int t = 0; t < HT; ++t) {
             const int idx = tid + 256 * t, row = idx >> 4, ch = idx & 15;
-            const bool skip = row >= G || (qflag[t] & kHeadDone);
+            const bool skip = row >= G || (qflag[t] & kHeadDone) || (!kFullDim && 8 * ch >= p.head_dim);
             *reinterpret_cast<u32x4*>(s_q + row * kQRowBytes + 16 * ch) = skip ? u32x4{0u, 0u, 0u, 0u} : qv[t];
         }
         if constexpr (HT == 2) {
@@ -414,7 +420,8 @@ __device__ __forceinline__ void attn_item(const AttnParams& p, const int C, cons
     uint32_t v_row_b[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) v_row_b[i] = (uint32_t)(4 * i + kg) * tok_bytes;
-    const uint32_t v_col_b = 16u * (uint32_t)r16;
+    const uint32_t v_col_b = 16u * (uint32_t)(kFullDim ? r16 : min(r16, (p.head_dim >> 3) - 1));
+    const int k_steps = kFullDim ? 4 : p.head_dim >> 5;          // k-steps of 32 elements that the rows really have
     // base address of sub-tile u of the wave's k-th tile (rows past the end fold back, see above) and its row limit
     auto sub_tile = [&](int k, int u, uint32_t& lim_b) {
         const int t0 = (chunk_tile0 + w + 4 * k) * kTileTokens;
@@ -430,7 +437,8 @@ __device__ __forceinline__ void attn_item(const AttnParams& p, const int C, cons
             uint32_t lim_b;
             const char* kp = sub_tile(k, u, lim_b) + (min(k_row_b, lim_b) + k_col_b);
 #pragma unroll
-            for (int c = 0; c < 4; ++c) K[u][c] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kp + 64 * c));
+            for (int c = 0; c < 4; ++c)
+                K[u][c] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kp + 64 * (kFullDim ? c : min(c, k_steps - 1))));
         }
     };
     auto load_v = [&](int k, u32x4 (&V)[8]) {

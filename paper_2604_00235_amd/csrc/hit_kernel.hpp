@@ -60,7 +60,7 @@ struct HitParams {
     // match
     const int32_t* slot_ids;     // [batch]
     const int32_t* kv_lens;      // [batch]
-    const uint16_t* q_pre;       // [batch, Hq, 128] bf16
+    const uint16_t* q_pre;       // [batch, Hq, d] bf16
     uint16_t* ring_q;            // [slots, Hq, W, 128] bf16
     float* ring_O;               // [slots, Hq, W, 128]
     float* ring_lse;             // [slots, Hq, W]
@@ -77,9 +77,10 @@ struct HitParams {
     double* out_match_d2;
     MatchView mv;                // threshold, band, distance cap (part / n_split unused)
     int32_t batch, Hq, G, W, max_kv_len;
+    int32_t head_dim;            // d of the caller's tensors (32, 64, 96, 128); ring rows are 128 wide, zero beyond d
     int32_t fused_span;          // largest fresh range finished here, 0 = none, <= kHitMaxSpan
     // fused hit path
-    const uint16_t* q_rope;      // [batch, Hq, 128] bf16
+    const uint16_t* q_rope;      // [batch, Hq, d] bf16
     const uint16_t* kv_pages;
     int64_t stride_page, stride_kv, stride_head, stride_tok;
     const int32_t* block_table;
@@ -199,7 +200,9 @@ __global__ __launch_bounds__(NT, NT == 256 ? (kLean ? 5 : 4) : 1) void hit_kerne
     // ---- 1. match, in three tiers (see the head of this file): matrix-core filter, fp64 evaluation of the candidates
     // it leaves, and -- only for candidates that tie to rounding -- the sum in index order.
     const uint16_t* ring_h = p.ring_q + ring_row0 * kHeadDim;
-    const uint16_t* q_h = p.q_pre + (int64_t)bh * kHeadDim;
+    const int D = p.head_dim;                                  // the caller's rows; everything in here is 128 wide, zero beyond D
+    const uint16_t* q_h = p.q_pre + (int64_t)bh * D;
+    const u32x4 kZero4 = u32x4{0u, 0u, 0u, 0u};
     const int32_t* npos = p.ring_npos + ring_row0;
     const int np_lo = max(1, n - W), np_hi = n - 1;
     double best_d2 = INFINITY, second_d2 = INFINITY;           // nearest candidate and the distance of the next one
@@ -216,7 +219,7 @@ __global__ __launch_bounds__(NT, NT == 256 ? (kLean ? 5 : 4) : 1) void hit_kerne
         constexpr int kLoads = kLean ? 8 : 16;                 // loads (of four rows) per block of the window and wave
         const int own_i = (kLean ? 0 : 8 * (int)bA) + 4 * (int)bB + 2 * (int)bC + (int)bD;    // load number of the row this lane owns
         const bool owner = !kLean || !bA;                      // (with 8 loads per block each row's sum ends up in two lanes)
-        const u32x4 qc = *reinterpret_cast<const u32x4*>(q_h + 8 * ch);      // this lane's chunk of the query
+        const u32x4 qc = 8 * ch < D ? *reinterpret_cast<const u32x4*>(q_h + 8 * ch) : kZero4;      // this lane's chunk of the query
         const float qq = row_sum_f32(dot8_bf16(qc, qc));       // |q|^2 (the same in every lane)
         float U = INFINITY;                                    // smallest upper bound the work-group has seen so far
         const int n_blocks = (W + 4 * kLoads - 1) / (4 * kLoads);
@@ -311,7 +314,7 @@ __global__ __launch_bounds__(NT, NT == 256 ? (kLean ? 5 : 4) : 1) void hit_kerne
         int e_np = -1, e_j = -1;
         u32x4 qs[4];                                           // the query in the quad layout: chunks sub, sub + 4, ...
 #pragma unroll
-        for (int i = 0; i < 4; ++i) qs[i] = *reinterpret_cast<const u32x4*>(q_h + 8 * sub + 32 * i);
+        for (int i = 0; i < 4; ++i) qs[i] = 8 * sub + 32 * i < D ? *reinterpret_cast<const u32x4*>(q_h + 8 * sub + 32 * i) : kZero4;
         for (int r0 = 0; r0 < W; r0 += kRows) {
             const int r = r0 + quad, rc = min(r, W - 1);
             u32x4 v[4];
@@ -324,7 +327,7 @@ __global__ __launch_bounds__(NT, NT == 256 ? (kLean ? 5 : 4) : 1) void hit_kerne
             d2 += __shfl_xor(d2, 2);
             if (r < W && np >= np_lo && np <= np_hi && d2 <= bound) {
                 double e = 0.0;
-                for (int i = 0; i < kHeadDim; ++i) {
+                for (int i = 0; i < D; ++i) {
                     const double diff = __dsub_rn((double)bits_to_float((uint32_t)q_h[i] << 16), (double)bits_to_float((uint32_t)rp[i] << 16));
                     e = __dadd_rn(e, __dmul_rn(diff, diff));
                 }
@@ -382,18 +385,19 @@ __global__ __launch_bounds__(NT, NT == 256 ? (kLean ? 5 : 4) : 1) void hit_kerne
     // together with its first K rows.
     constexpr int kRowGroups = NT / 16, kKPass = NT == 256 ? (kLean ? 5 : 9) : 8, kVPre = kKPass;   // (256 threads: one pass for B + 1 = 129 rows; lean: 65)
     const int col = tid & 15, rg = tid >> 4;
-    const u32x4 qk = *reinterpret_cast<const u32x4*>(p.q_rope + (int64_t)bh * kHeadDim + 8 * col);    // this lane's chunk of the post-RoPE query
+    const u32x4 qk = 8 * col < D ? *reinterpret_cast<const u32x4*>(p.q_rope + (int64_t)bh * D + 8 * col) : kZero4;    // this lane's chunk of the post-RoPE query
+    const int colc = min(col, (D >> 3) - 1);                   // lanes past the end of a K/V row re-read its last 16 bytes
     u32x4 vpre[kVPre];
     // logits (log2 domain): each lane its chunk's share (v_dot2c_f32_bf16), summed over the 16 lanes of the row
     for (int r0 = 0; r0 < cnt; r0 += kKPass * kRowGroups) {
         u32x4 kk[kKPass];
 #pragma unroll
         for (int u = 0; u < kKPass; ++u)
-            kk[u] = *reinterpret_cast<const u32x4*>(row_ptr(min(r0 + u * kRowGroups + rg, cnt - 1)) + 8 * col);
+            kk[u] = *reinterpret_cast<const u32x4*>(row_ptr(min(r0 + u * kRowGroups + rg, cnt - 1)) + 8 * colc);
         if (r0 == 0) {
 #pragma unroll
             for (int u = 0; u < kVPre; ++u)
-                vpre[u] = *reinterpret_cast<const u32x4*>(row_ptr(min(u * kRowGroups + rg, cnt - 1)) + p.stride_kv + 8 * col);
+                vpre[u] = *reinterpret_cast<const u32x4*>(row_ptr(min(u * kRowGroups + rg, cnt - 1)) + p.stride_kv + 8 * colc);
         }
 #pragma unroll
         for (int u = 0; u < kKPass; ++u) {
@@ -453,7 +457,7 @@ __global__ __launch_bounds__(NT, NT == 256 ? (kLean ? 5 : 4) : 1) void hit_kerne
             u32x4 vv[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u)
-                vv[u] = *reinterpret_cast<const u32x4*>(row_ptr(min(r0 + u * kRowGroups + rg, cnt - 1)) + p.stride_kv + 8 * col);
+                vv[u] = *reinterpret_cast<const u32x4*>(row_ptr(min(r0 + u * kRowGroups + rg, cnt - 1)) + p.stride_kv + 8 * colc);
 #pragma unroll
             for (int u = 0; u < 4; ++u) add_row(r0 + u * kRowGroups + rg, vv[u]);
         }
@@ -481,16 +485,15 @@ __global__ __launch_bounds__(NT, NT == 256 ? (kLean ? 5 : 4) : 1) void hit_kerne
         float rect_o, rect_l, o, lse;
         merge2(pre_o, pre_l, o_mid, l_mid, rect_o, rect_l);    // this step's total without the last-B band
         merge2(rect_o, rect_l, o_band, l_band, o, lse);
-        if (p.out_bf16) {
-            static_cast<uint16_t*>(p.out)[(int64_t)bh * kHeadDim + d] = float_to_bf16_rne(o);
-        } else {
-            static_cast<float*>(p.out)[(int64_t)bh * kHeadDim + d] = o;
+        if (d < D) {
+            if (p.out_bf16) static_cast<uint16_t*>(p.out)[(int64_t)bh * D + d] = float_to_bf16_rne(o);
+            else static_cast<float*>(p.out)[(int64_t)bh * D + d] = o;
         }
         if (d == 0 && p.out_lse != nullptr) p.out_lse[bh] = lse;
         // rectify-append into entry (n - 1) mod W of this head
         const int jn = (n - 1) % W;
         const int64_t e = ring_row0 + jn;
-        p.ring_q[e * kHeadDim + d] = p.q_pre[(int64_t)bh * kHeadDim + d];
+        p.ring_q[e * kHeadDim + d] = d < D ? p.q_pre[(int64_t)bh * D + d] : (uint16_t)0;
         p.ring_O[e * kHeadDim + d] = rect_o;
         if (d == 0) {
             p.ring_lse[e] = rect_l;

@@ -107,7 +107,9 @@ int validate_config(const mac_attn_config* c, Layout* L) {
         return MAC_ATTN_ERR_INVALID_ARG;
     if (c->fused_hit_span < -1 || c->fused_hit_span > mac::kHitMaxSpan) return MAC_ATTN_ERR_INVALID_ARG;
     if (c->max_kv_len >= mac::kHeadDone) return MAC_ATTN_ERR_INVALID_ARG;
-    if (c->head_dim != mac::kHeadDim) return MAC_ATTN_ERR_UNSUPPORTED;
+    if (c->head_dim < 1) return MAC_ATTN_ERR_INVALID_ARG;
+    // rows are widened to 128 elements inside the library: d = 32, 64, 96 or 128
+    if (c->head_dim > mac::kHeadDim || c->head_dim % 32 != 0) return MAC_ATTN_ERR_UNSUPPORTED;
     const int G = c->num_q_heads / c->num_kv_heads;
     if (G > 32) return MAC_ATTN_ERR_UNSUPPORTED;
     if (c->page_size < 16 || (c->page_size & (c->page_size - 1)) != 0) return MAC_ATTN_ERR_UNSUPPORTED;
@@ -208,7 +210,7 @@ int validate_args(const mac_attn_ctx* ctx, const mac_attn_step_args* a, bool nee
     for (int64_t s : st)
         if (s <= 0 || (s % 8) != 0) return MAC_ATTN_ERR_INVALID_ARG;
     // the kernels form row offsets inside a 16-token sub-tile in 32 bits
-    if (a->stride_tok < mac::kHeadDim || a->stride_tok >= (1 << 26)) return MAC_ATTN_ERR_INVALID_ARG;
+    if (a->stride_tok < ctx->cfg.head_dim || a->stride_tok >= (1 << 26)) return MAC_ATTN_ERR_INVALID_ARG;
     // 16-byte vector loads: base pointers must be 16-byte aligned
     if ((reinterpret_cast<uintptr_t>(a->kv_pages) & 15u) || (reinterpret_cast<uintptr_t>(a->q_rope) & 15u)) return MAC_ATTN_ERR_INVALID_ARG;
     if (need_pre && (reinterpret_cast<uintptr_t>(a->q_pre) & 15u)) return MAC_ATTN_ERR_INVALID_ARG;
@@ -328,10 +330,15 @@ int launch_attention(mac_attn_ctx* ctx, const mac_attn_step_args* a, bool mac_mo
         max_items = std::min<int64_t>(max_items, ctx->grid_attn);
     }
     const dim3 grid((unsigned)std::max<int64_t>(max_items, 1)), block(256);
-    if (L.G <= 16)
-        hipLaunchKernelGGL(mac::attn_kernel<1>, grid, block, 0, stream, p);
-    else
-        hipLaunchKernelGGL(mac::attn_kernel<2>, grid, block, 0, stream, p);
+    p.head_dim = c.head_dim;
+    const bool full_dim = c.head_dim == mac::kHeadDim;
+    if (L.G <= 16) {
+        if (full_dim) hipLaunchKernelGGL((mac::attn_kernel<1, true>), grid, block, 0, stream, p);
+        else hipLaunchKernelGGL((mac::attn_kernel<1, false>), grid, block, 0, stream, p);
+    } else {
+        if (full_dim) hipLaunchKernelGGL((mac::attn_kernel<2, true>), grid, block, 0, stream, p);
+        else hipLaunchKernelGGL((mac::attn_kernel<2, false>), grid, block, 0, stream, p);
+    }
     HIP_TRY(hipGetLastError());
     return MAC_ATTN_OK;
 }
@@ -370,6 +377,7 @@ mac::MergeParams merge_params(mac_attn_ctx* ctx, const mac_attn_step_args* a, bo
     p.n_mid_slots = L.n_mid_slots;
     p.n_slots = L.n_slots;
     p.max_kv_len = c.max_kv_len;
+    p.head_dim = c.head_dim;
     return p;
 }
 
@@ -390,6 +398,7 @@ mac::WritebackParams writeback_params(mac_attn_ctx* ctx, const mac_attn_step_arg
     p.Hq = c.num_q_heads;
     p.W = c.window;
     p.max_kv_len = c.max_kv_len;
+    p.head_dim = c.head_dim;
     return p;
 }
 
@@ -430,7 +439,8 @@ const char* mac_attn_last_hip_error(void) { return g_last_hip_error.c_str(); }
 
 int64_t mac_attn_ring_entry_bytes(int32_t head_dim) {
     if (head_dim < 1) return MAC_ATTN_ERR_INVALID_ARG;
-    return (int64_t)head_dim * 2 + (int64_t)head_dim * 4 + 4;
+    if (head_dim > mac::kHeadDim || head_dim % 32 != 0) return MAC_ATTN_ERR_UNSUPPORTED;
+    return (int64_t)mac::kHeadDim * 2 + (int64_t)mac::kHeadDim * 4 + 4;      // rows are stored 128 wide whatever d is
 }
 
 int64_t mac_attn_device_bytes(const mac_attn_config* cfg) {
@@ -630,6 +640,7 @@ int mac_attn_decode_step(mac_attn_ctx* ctx, const mac_attn_step_args* args, void
         p.G = ctx->L.G;
         p.W = c.window;
         p.max_kv_len = c.max_kv_len;
+        p.head_dim = c.head_dim;
         p.fused_span = ctx->fused_span;
         p.q_rope = static_cast<const uint16_t*>(args->q_rope);
         p.kv_pages = static_cast<const uint16_t*>(args->kv_pages);
@@ -672,6 +683,7 @@ int mac_attn_decode_step(mac_attn_ctx* ctx, const mac_attn_step_args* args, void
         p.Hq = c.num_q_heads;
         p.W = c.window;
         p.max_kv_len = c.max_kv_len;
+        p.head_dim = c.head_dim;
         p.G = ctx->L.G;
         // window slices: a power of two, enough work-groups to fill the chip at small batch; a slice holds at most
         // kMatchGroupItems (row, head) pairs and at least 16 rows
@@ -793,8 +805,8 @@ int mac_attn_ring_peek(mac_attn_ctx* ctx, int32_t slot, int32_t j, int32_t h, ui
     if (rc != MAC_ATTN_OK) return rc;
     HIP_TRY(hipDeviceSynchronize());
     const int64_t e = ((int64_t)slot * c.num_q_heads + h) * c.window + j;
-    if (q_pre) HIP_TRY(hipMemcpy(q_pre, ctx->ring_q + e * mac::kHeadDim, mac::kHeadDim * 2, hipMemcpyDeviceToHost));
-    if (summary) HIP_TRY(hipMemcpy(summary, ctx->ring_O + e * mac::kHeadDim, mac::kHeadDim * 4, hipMemcpyDeviceToHost));
+    if (q_pre) HIP_TRY(hipMemcpy(q_pre, ctx->ring_q + e * mac::kHeadDim, (size_t)c.head_dim * 2, hipMemcpyDeviceToHost));
+    if (summary) HIP_TRY(hipMemcpy(summary, ctx->ring_O + e * mac::kHeadDim, (size_t)c.head_dim * 4, hipMemcpyDeviceToHost));
     if (lse) HIP_TRY(hipMemcpy(lse, ctx->ring_lse + e, 4, hipMemcpyDeviceToHost));
     if (n_p) HIP_TRY(hipMemcpy(n_p, ctx->ring_npos + e, 4, hipMemcpyDeviceToHost));
     return MAC_ATTN_OK;

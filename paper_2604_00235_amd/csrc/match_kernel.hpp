@@ -27,7 +27,7 @@ namespace mac {
 struct MatchParams {
     const int32_t* slot_ids;     // [batch]
     const int32_t* kv_lens;      // [batch]
-    const uint16_t* q_pre;       // [batch, Hq, 128] bf16
+    const uint16_t* q_pre;       // [batch, Hq, d] bf16
     const uint16_t* ring_q;      // [slots, Hq, W, 128] bf16
     const int32_t* ring_npos;    // [slots, Hq, W]; 0 = empty entry (the heads of a request carry the same tags)
     MatchPartial* slices;        // [batch*Hq, n_split] nearest entry of each window slice (group matcher)
@@ -35,6 +35,7 @@ struct MatchParams {
     int32_t* head_start;         // [batch*Hq] start of each head's fresh range (written by the finalize kernel)
     unsigned long long* st_steps;   // [2]: decode steps, head-steps (device-side so that graph replays count too)
     int32_t batch, Hq, W, max_kv_len;
+    int32_t head_dim;            // d of the caller's q_pre rows (ring rows are 128 wide, zero beyond d)
     int32_t n_split;             // window slices per group = gridDim.z of the group matcher (power of two <= 64)
     int32_t rows_per_split;      // multiple of 16 with rows_per_split * G <= kMatchGroupItems
     int32_t G;                   // heads per KV group
@@ -112,11 +113,11 @@ __global__ __launch_bounds__(kMatchThreads) void match_group_kernel(const MatchP
             const int i = i0 + t * kMatchRowsPerPass + quad;
             const int ic = i < items ? i : items - 1;            // keeps the loads of idle quads inside the slice
             const int r = ic / G, h = g * G + (ic - r * G);
-            const uint16_t* qp = p.q_pre + ((int64_t)b * p.Hq + h) * kHeadDim + 8 * sub;
+            const uint16_t* qp = p.q_pre + ((int64_t)b * p.Hq + h) * p.head_dim + 8 * sub;
             const uint16_t* rp = p.ring_q + ((slot * p.Hq + h) * W + j_begin + r) * (int64_t)kHeadDim + 8 * sub;
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                qv[t][k] = *reinterpret_cast<const u32x4*>(qp + 32 * k);
+                qv[t][k] = 8 * sub + 32 * k < p.head_dim ? *reinterpret_cast<const u32x4*>(qp + 32 * k) : u32x4{0u, 0u, 0u, 0u};
                 v[t][k] = *reinterpret_cast<const u32x4*>(rp + 32 * k);
             }
         }

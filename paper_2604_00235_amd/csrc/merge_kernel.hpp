@@ -27,7 +27,7 @@ namespace mac {
 struct WritebackParams {
     const int32_t* kv_lens;
     const int32_t* slot_ids;
-    const uint16_t* q_pre;       // [batch, Hq, 128] bf16
+    const uint16_t* q_pre;       // [batch, Hq, d] bf16
     const float* rect_O;         // staging [batch*Hq, 128] (separate-kernel mode only)
     const float* rect_lse;       // [batch*Hq]
     uint16_t* ring_q;            // [slots, Hq, W, 128]
@@ -36,6 +36,7 @@ struct WritebackParams {
     int32_t* ring_npos;          // [slots, Hq, W]: every head carries its own n_p tags
     const int32_t* head_start;   // [batch*Hq] or null: heads flagged kHeadDone were appended by the matcher already
     int32_t Hq, W, max_kv_len;
+    int32_t head_dim;            // d of the caller's q_pre rows; ring rows are 128 wide, zero beyond d
 };
 
 struct MergeParams {
@@ -53,8 +54,9 @@ struct MergeParams {
     const float* ring_lse;       // [slots, Hq, W]
     const float* part_O;         // [batch*Hq, n_slots, 128]
     const float* part_lse;       // [batch*Hq, n_slots]
-    void* out;                   // [batch, Hq, 128] fp32, or bf16 when out_bf16
+    void* out;                   // [batch, Hq, d] fp32, or bf16 when out_bf16
     int32_t out_bf16;
+    int32_t head_dim;            // d of `out` (the partials and the rings are 128 wide)
     float* out_lse;              // optional [batch, Hq]
     float* rect_O;               // staging for a separate write-back kernel [batch*Hq, 128]; may be null
     float* rect_lse;             // [batch*Hq]
@@ -100,7 +102,7 @@ __device__ __forceinline__ void writeback_head(const WritebackParams& p, int b, 
     const int64_t slot = p.slot_ids[b];
     const int j = (n - 1) % p.W;
     const int64_t e = (slot * p.Hq + h) * p.W + j;
-    p.ring_q[e * kHeadDim + d] = p.q_pre[(int64_t)bh * kHeadDim + d];
+    p.ring_q[e * kHeadDim + d] = d < p.head_dim ? p.q_pre[(int64_t)bh * p.head_dim + d] : (uint16_t)0;
     p.ring_O[e * kHeadDim + d] = rect_o;
     if (d == 0) {
         p.ring_lse[e] = rect_l;
@@ -195,10 +197,9 @@ __device__ __forceinline__ void merge_head(const MergeParams& p, const Writeback
             o = (fr * S_r + fb * S_b) / Z;
             lse = M_o + logf(Z);
         }
-        if (p.out_bf16) {
-            static_cast<uint16_t*>(p.out)[(int64_t)bh * kHeadDim + d] = float_to_bf16_rne(o);
-        } else {
-            static_cast<float*>(p.out)[(int64_t)bh * kHeadDim + d] = o;
+        if (d < p.head_dim) {
+            if (p.out_bf16) static_cast<uint16_t*>(p.out)[(int64_t)bh * p.head_dim + d] = float_to_bf16_rne(o);
+            else static_cast<float*>(p.out)[(int64_t)bh * p.head_dim + d] = o;
         }
         if (d == 0 && p.out_lse != nullptr) p.out_lse[bh] = lse;
         if (do_wb) writeback_head(wb, b, h, d, rect_o, rect_l);

@@ -49,7 +49,7 @@ class DeviceRun:
         dev = wl.device
         self.mac = mb.MacAttention(num_q_heads=cfg.num_q_heads, num_kv_heads=cfg.num_kv_heads, window=cfg.window,
                                    band=cfg.band, threshold=cfg.threshold, max_kv_len=max_kv_len or cfg.max_kv_len,
-                                   max_slots=cfg.batch, page_size=cfg.page_size, chunk_tokens=chunk_tokens,
+                                   max_slots=cfg.batch, page_size=cfg.page_size, head_dim=cfg.head_dim, chunk_tokens=chunk_tokens,
                                    fuse_epilogue=fuse_epilogue, max_gap=max_gap, group_match=group_match,
                                    out_bf16=out_bf16, fused_hit_span=fused_hit_span)
         self.kv_pages = wl.kv_pages if kv_pages is None else kv_pages

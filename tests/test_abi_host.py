@@ -73,6 +73,8 @@ def test_ring_entry_bytes_and_paper_overhead(lib):
     must land on the 5 % reference point and within one rounding step (0.1) of every printed figure."""
     e = mb.mac_attn_ring_entry_bytes(128)
     assert e == 772                                   # bf16 query + fp32 summary row + fp32 ln-LSE
+    assert mb.mac_attn_ring_entry_bytes(64) == 772    # rows are stored 128 wide whatever d is
+    assert mb.mac_attn_ring_entry_bytes(256) == mb.MAC_ATTN_ERR_UNSUPPORTED
     kv_per_token = 2 * 8 * 128 * 2
     rows = [l.split() for l in open(os.path.join(ROOT, "tests", "golden", "memory_overhead_table.txt"))
             if l.strip() and not l.startswith("#")]
@@ -100,13 +102,16 @@ def test_device_bytes_accounts_rings_and_workspace(lib):
     assert grouped - total == 4 * 32 * 64 * 16 - 16
     # chunk_tokens = 0: the partial slots are laid out for the smallest work item the kernel may choose (256 tokens
     # at 4 heads per KV head)
+    assert mb.mac_attn_device_bytes(_cfg(head_dim=64)) == total      # (no smaller: the padding)
     dyn = mb.mac_attn_device_bytes(_cfg(chunk_tokens=0))
     n_slots_dyn = (131200 + 255) // 256 + (128 + 255) // 256 + 1
     assert dyn - total == 4 * 32 * (n_slots_dyn - n_slots) * (128 + 1) * 4
 
 
 @pytest.mark.parametrize("kw,code", [
-    (dict(head_dim=64), mb.MAC_ATTN_ERR_UNSUPPORTED),
+    (dict(head_dim=256), mb.MAC_ATTN_ERR_UNSUPPORTED),
+    (dict(head_dim=48), mb.MAC_ATTN_ERR_UNSUPPORTED),
+    (dict(head_dim=0), mb.MAC_ATTN_ERR_INVALID_ARG),
     (dict(page_size=24), mb.MAC_ATTN_ERR_UNSUPPORTED),
     (dict(page_size=8), mb.MAC_ATTN_ERR_UNSUPPORTED),
     (dict(num_q_heads=66, num_kv_heads=1), mb.MAC_ATTN_ERR_UNSUPPORTED),

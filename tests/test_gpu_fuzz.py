@@ -1,5 +1,5 @@
 """Seeded random geometries through the whole path against the oracle (GPU).  Each case draws heads, group size,
-page size, window, band, chunking, ragged lengths, query model, threshold and the variants of the match rule from a
+page size, window, band, chunking, ragged lengths, query model, threshold, head dimension and the variants of the match rule from a
 seed; decisions must be bit-exact and outputs within the tolerance at every step."""
 from __future__ import annotations
 
@@ -39,10 +39,13 @@ def _draw(seed: int):
     fused = bool(rng.integers(0, 4) != 0)
     # largest fresh range the matcher finishes itself: default, never, and values that split the hits of one run
     variant["fused_hit_span"] = int(rng.choice([0, -1, 9, 40, 100, 2048]))
+    # head dimension (drawn last, so that the earlier draws of a seed stay what they were); thresholds scale with sqrt(d)
+    head_dim = int(rng.choice([128, 128, 64, 96, 32]))
+    kw.update(head_dim=head_dim, threshold=kw["threshold"] * math.sqrt(head_dim / 128.0))
     return WorkloadConfig(**kw), variant, chunk, fused
 
 
-@pytest.mark.parametrize("seed", list(range(16)))
+@pytest.mark.parametrize("seed", list(range(20)))
 def test_random_geometry(seed):
     from tests.gpu_harness import run_parity
     cfg, variant, chunk, fused = _draw(seed)

@@ -253,8 +253,9 @@ def test_group_sizes_between_17_and_31(group):
     assert 0 < r["hits"] < r["head_steps"]
 
 
-@pytest.mark.parametrize("page_size,context", [(16, 1024 + 3), (16, 2048 + 10), (64, 1024 + 9), (32, 777)])
-def test_memory_the_request_does_not_own_may_hold_nan(page_size, context):
+@pytest.mark.parametrize("page_size,context,head_dim", [(16, 1024 + 3, 128), (16, 2048 + 10, 128), (64, 1024 + 9, 128),
+                                                        (32, 777, 128), (16, 1024 + 5, 64)])
+def test_memory_the_request_does_not_own_may_hold_nan(page_size, context, head_dim):
     """Only the pages a request's block table lists, and of its last page only the rows below kv_len, are the
     request's data.  Here every other byte of the cache is a NaN / Inf pattern: physical page 0 belongs to nobody, and
     in each request's last page the rows past the end are poisoned before every step.  Lengths are chosen so that the
@@ -262,7 +263,8 @@ def test_memory_the_request_does_not_own_may_hold_nan(page_size, context):
     from tests.gpu_harness import DeviceRun, check_rows
     from tests.helpers import make_oracle
     cfg = WorkloadConfig(name="poison", batch=2, num_q_heads=8, num_kv_heads=2, context=context, steps=6, window=4, band=24,
-                         threshold=T_DEFAULT, rho=0.97, seed=41, page_size=page_size, ragged=32)
+                         threshold=0.5 * math.sqrt(float(head_dim)), rho=0.97, seed=41, page_size=page_size, ragged=32,
+                         head_dim=head_dim)
     wl = Workload(cfg, device="cuda:0")
     pages = torch.cat([torch.zeros_like(wl.kv_pages[:1]), wl.kv_pages]).contiguous()
     bad = torch.tensor([0x7FC0, 0x7F80, 0xFF80, 0xFFFF], dtype=torch.int32).to(torch.int16).to("cuda:0")
@@ -365,3 +367,17 @@ def test_more_work_items_than_work_groups():
     from tests.gpu_harness import run_parity
     r = run_parity(cfg, chunk_tokens=32, fused_hit_span=-1)
     assert 0 < r["hits"] < 5 * 16
+
+
+@pytest.mark.parametrize("head_dim,hq,hkv,span,group", [(64, 8, 2, 0, False), (64, 32, 1, 0, False), (32, 6, 2, -1, False),
+                                                        (96, 8, 8, 0, False), (64, 8, 2, 0, True), (96, 20, 1, 70, False)])
+def test_head_dims_below_128(head_dim, hq, hkv, span, group):
+    """d = 32, 64, 96: the caller's queries, outputs and K/V rows have d elements (the library widens rows to 128 inside);
+    per-head and per-group matching, the fused hit path on / off / limited, one and two head tiles, ragged requests,
+    full decode at every step."""
+    from tests.gpu_harness import run_parity
+    cfg = WorkloadConfig(name=f"d{head_dim}_{hq}_{hkv}", batch=3, num_q_heads=hq, num_kv_heads=hkv, context=1300, steps=24,
+                         window=16, band=40, threshold=math.sqrt(2 * (1 - 0.97) * head_dim),      # about half of the heads hit
+                         rho=0.97, seed=41, ragged=131, head_dim=head_dim)
+    r = run_parity(cfg, chunk_tokens=0 if hq != 6 else 96, fused_hit_span=span, group_match=group)
+    assert 0 < r["hits"] < r["head_steps"] - 3 * hq

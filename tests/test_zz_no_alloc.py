@@ -31,9 +31,9 @@ def test_static_full_decode_equals_context_full_decode_twice():
     from tests.gpu_harness import DeviceRun, check_rows, say
     from tests.helpers import make_oracle
     # first call: 3 requests x 32/8 heads near 5000 tokens (ragged), 20 work items per group; second: 2 requests of a
-    # different geometry (MQA-like 16/1 heads) near 700 tokens
+    # different geometry (MQA-like 16/1 heads, head dimension 64) near 700 tokens
     big = scaled(CONFIGS["C2"], name="static_big", batch=3, context=5000, steps=2, ragged=333)
-    small = scaled(CONFIGS["C4_hit"], name="static_small", batch=2, num_q_heads=16, context=700, steps=2, ragged=41)
+    small = scaled(CONFIGS["C4_hit"], name="static_small", batch=2, num_q_heads=16, context=700, steps=2, ragged=41, head_dim=64)
     for rep in range(2):                                   # the pair twice: the buffer is dirty from every earlier call
         for cfg, chunk in ((big, 256), (small, 128)):
             say(f"[static] rep {rep} {cfg.name}: batch={cfg.batch} Hq/Hkv={cfg.num_q_heads}/{cfg.num_kv_heads} "
@@ -72,7 +72,7 @@ def test_static_full_decode_rejects_what_does_not_fit():
                                  16 * 128, 128, bt.data_ptr(), 8200, out.data_ptr(), None, None, None)
     assert lib.mac_attn_full_decode_static(C.byref(geo), C.byref(args), None) == mb.MAC_ATTN_ERR_TOO_LARGE
     assert b"static" in lib.mac_attn_strerror(mb.MAC_ATTN_ERR_TOO_LARGE)
-    geo.head_dim = 64
+    geo.head_dim = 256
     assert lib.mac_attn_full_decode_static(C.byref(geo), C.byref(args), None) == mb.MAC_ATTN_ERR_UNSUPPORTED
     assert lib.mac_attn_full_decode_static(None, C.byref(args), None) == mb.MAC_ATTN_ERR_INVALID_ARG
     torch.cuda.synchronize()
