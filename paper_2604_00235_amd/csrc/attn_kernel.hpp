@@ -118,11 +118,6 @@ __device__ __forceinline__ GroupSpan group_span(const AttnParams& p, int b, int 
     return s;
 }
 
-// Work items of a group for C tokens per item: the range [gs, nb) cut on the global grid of C tokens ("mid" items, chunk
-// indices gs/C .. ceil(nb/C)-1) and the band [nb, n) cut on the same grid ("band" items).
-__device__ __forceinline__ int mid_items(const GroupSpan& s, int C) { return s.nb > s.gs ? (s.nb + C - 1) / C - s.gs / C : 0; }
-__device__ __forceinline__ int band_items(const GroupSpan& s, int C) { return s.n > s.nb ? (s.n + C - 1) / C - s.nb / C : 0; }
-
 constexpr int kAttnChunkMax = 8192;      // tokens per work item at most (a wave's page ids sit one per lane in two registers)
 constexpr int kAttnChunkPref = 2048;     // the planner makes fewer items rather than shorter ones
 

@@ -69,19 +69,6 @@ __device__ __forceinline__ double lane_sq_dist(const double (&q)[32], const u32x
     return s0 + s1;
 }
 
-// this lane's 32 elements of a 128-element bf16 row (16-byte chunks sub, sub + 4, sub + 8, sub + 12), widened
-__device__ __forceinline__ void load_query_f64(const uint16_t* row_plus_8sub, double (&q)[32]) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const u32x4 v = *reinterpret_cast<const u32x4*>(row_plus_8sub + 32 * i);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            q[8 * i + 2 * e] = bf16_lo_to_f64(v[e]);
-            q[8 * i + 2 * e + 1] = bf16_hi_to_f64(v[e]);
-        }
-    }
-}
-
 constexpr int kMatchThreads = 256;
 constexpr int kMatchRowsPerPass = kMatchThreads / 4;
 
