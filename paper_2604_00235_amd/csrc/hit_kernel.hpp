@@ -136,32 +136,6 @@ __device__ __forceinline__ float dot8_bf16(const u32x4& x, const u32x4& y) {
     acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(vx, vx, 6, 7), __builtin_shufflevector(vy, vy, 6, 7), acc, false);
     return acc;
 }
-// Sums over the 16 lanes of a row of the wave (DPP), the same in each of them
-__device__ __forceinline__ float row_sum_f32(float v) {
-    v += dpp_f32<kDppQuadSwap1>(v);
-    v += dpp_f32<kDppQuadSwap2>(v);
-    v += dpp_f32<kDppRowHalfMirror>(v);
-    return v + dpp_f32<kDppRowMirror>(v);
-}
-__device__ __forceinline__ double row_sum_f64(double v) {
-    v += dpp_f64<kDppQuadSwap1>(v);
-    v += dpp_f64<kDppQuadSwap2>(v);
-    v += dpp_f64<kDppRowHalfMirror>(v);
-    return v + dpp_f64<kDppRowMirror>(v);
-}
-// One lane's share of a squared distance in fp64: a 16-byte chunk of the query against the same chunk of a ring row
-__device__ __forceinline__ double sq_dist_chunk(const u32x4& q, const u32x4& v) {
-    double s0 = 0.0, s1 = 0.0;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        const double d0 = bf16_lo_to_f64(q[e]) - bf16_lo_to_f64(v[e]);
-        const double d1 = bf16_hi_to_f64(q[e]) - bf16_hi_to_f64(v[e]);
-        s0 = fma(d0, d0, s0);
-        s1 = fma(d1, d1, s1);
-    }
-    return s0 + s1;
-}
-
 // NT = threads per work-group: 256, or 1024 when there are few heads and a large window.  kLean (256 threads only): fewer
 // loads in flight per wave (half a block of the window, five K/V rows), which fits five work-groups on a compute unit
 // instead of four: for launches with more heads than the chip holds work-groups.

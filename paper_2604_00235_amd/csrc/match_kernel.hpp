@@ -53,24 +53,33 @@ __device__ __forceinline__ int head_start(const MatchView& mv, double d2, int np
 __device__ __forceinline__ double bf16_lo_to_f64(uint32_t pair) { return (double)bits_to_float(pair << 16); }
 __device__ __forceinline__ double bf16_hi_to_f64(uint32_t pair) { return (double)bits_to_float(pair & 0xffff0000u); }
 
-// Partial squared distance of one lane: its 32 query elements (already fp64) against the 4 x 16 bytes it loaded.
-__device__ __forceinline__ double lane_sq_dist(const double (&q)[32], const u32x4 (&v)[4]) {
+// Sums over the 16 lanes of a row of the wave (DPP), the same in each of them
+__device__ __forceinline__ float row_sum_f32(float v) {
+    v += dpp_f32<kDppQuadSwap1>(v);
+    v += dpp_f32<kDppQuadSwap2>(v);
+    v += dpp_f32<kDppRowHalfMirror>(v);
+    return v + dpp_f32<kDppRowMirror>(v);
+}
+__device__ __forceinline__ double row_sum_f64(double v) {
+    v += dpp_f64<kDppQuadSwap1>(v);
+    v += dpp_f64<kDppQuadSwap2>(v);
+    v += dpp_f64<kDppRowHalfMirror>(v);
+    return v + dpp_f64<kDppRowMirror>(v);
+}
+// One lane's share of a squared distance in fp64: a 16-byte chunk of the query against the same chunk of a ring row
+__device__ __forceinline__ double sq_dist_chunk(const u32x4& q, const u32x4& v) {
     double s0 = 0.0, s1 = 0.0;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const double d0 = q[8 * i + 2 * e] - bf16_lo_to_f64(v[i][e]);
-            const double d1 = q[8 * i + 2 * e + 1] - bf16_hi_to_f64(v[i][e]);
-            s0 = fma(d0, d0, s0);
-            s1 = fma(d1, d1, s1);
-        }
+    for (int e = 0; e < 4; ++e) {
+        const double d0 = bf16_lo_to_f64(q[e]) - bf16_lo_to_f64(v[e]);
+        const double d1 = bf16_hi_to_f64(q[e]) - bf16_hi_to_f64(v[e]);
+        s0 = fma(d0, d0, s0);
+        s1 = fma(d1, d1, s1);
     }
     return s0 + s1;
 }
 
 constexpr int kMatchThreads = 256;
-constexpr int kMatchRowsPerPass = kMatchThreads / 4;
 
 // One reuse point per KV group: candidates are ranked by D2_j = sum over the group's heads of d2_{h,j} (the squared
 // distance of the group's concatenated queries), summed in head order.  One work-group per (KV group, request,
@@ -81,7 +90,7 @@ constexpr int kMatchGroupItems = 4096;   // (row, head) pairs per work-group: 32
 
 __global__ __launch_bounds__(kMatchThreads) void match_group_kernel(const MatchParams p) {
     const int g = blockIdx.x, b = blockIdx.y, sp = blockIdx.z;
-    const int tid = threadIdx.x, quad = tid >> 2, sub = tid & 3;
+    const int tid = threadIdx.x;
     const int G = p.G, W = p.W;
     const int n = clampi(p.kv_lens[b], 0, p.max_kv_len);
     const int64_t slot = p.slot_ids[b];
@@ -92,37 +101,29 @@ __global__ __launch_bounds__(kMatchThreads) void match_group_kernel(const MatchP
     const int items = rows * G;                                  // <= kMatchGroupItems (host)
     __shared__ double s_pair[kMatchGroupItems];
 
-    // two pairs per quad and trip, their loads issued before the arithmetic (as in the per-head matcher)
-    for (int i0 = 0; i0 < items; i0 += 2 * kMatchRowsPerPass) {
-        u32x4 qv[2][4], v[2][4];
+    // 16 lanes per (row, head) pair, one 16-byte chunk of the ring row and of the head's query each, so that a load
+    // instruction takes four whole rows (the access pattern a compute unit pulls fastest); eight pairs per lane and
+    // trip, their loads issued before the arithmetic.  Pair i is (row i / G, head i % G): i < 4096 and G <= 32, so the
+    // quotient comes exactly out of a single-precision multiplication.
+    constexpr int kPairsPerPass = kMatchThreads / 16, kUnroll = 8;
+    const int pl = tid >> 4, ch = tid & 15;
+    const float inv_g = 1.0f / (float)G;
+    for (int i0 = 0; i0 < items; i0 += kUnroll * kPairsPerPass) {
+        u32x4 qv[kUnroll], v[kUnroll];
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            const int i = i0 + t * kMatchRowsPerPass + quad;
-            const int ic = i < items ? i : items - 1;            // keeps the loads of idle quads inside the slice
-            const int r = ic / G, h = g * G + (ic - r * G);
-            const uint16_t* qp = p.q_pre + ((int64_t)b * p.Hq + h) * p.head_dim + 8 * sub;
-            const uint16_t* rp = p.ring_q + ((slot * p.Hq + h) * W + j_begin + r) * (int64_t)kHeadDim + 8 * sub;
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                qv[t][k] = 8 * sub + 32 * k < p.head_dim ? *reinterpret_cast<const u32x4*>(qp + 32 * k) : u32x4{0u, 0u, 0u, 0u};
-                v[t][k] = *reinterpret_cast<const u32x4*>(rp + 32 * k);
-            }
+        for (int t = 0; t < kUnroll; ++t) {
+            const int i = i0 + t * kPairsPerPass + pl;
+            const int ic = i < items ? i : items - 1;            // keeps the loads of idle lanes inside the slice
+            const int r = (int)(((float)ic + 0.5f) * inv_g), h = g * G + (ic - r * G);
+            qv[t] = 8 * ch < p.head_dim ? *reinterpret_cast<const u32x4*>(p.q_pre + ((int64_t)b * p.Hq + h) * p.head_dim + 8 * ch)
+                                        : u32x4{0u, 0u, 0u, 0u};
+            v[t] = *reinterpret_cast<const u32x4*>(p.ring_q + ((slot * p.Hq + h) * W + j_begin + r) * (int64_t)kHeadDim + 8 * ch);
         }
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            const int i = i0 + t * kMatchRowsPerPass + quad;
-            double q[32];
-#pragma unroll
-            for (int k = 0; k < 4; ++k)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    q[8 * k + 2 * e] = bf16_lo_to_f64(qv[t][k][e]);
-                    q[8 * k + 2 * e + 1] = bf16_hi_to_f64(qv[t][k][e]);
-                }
-            double d2 = lane_sq_dist(q, v[t]);
-            d2 += __shfl_xor(d2, 1);
-            d2 += __shfl_xor(d2, 2);
-            if (i < items && sub == 0) s_pair[i] = d2;
+        for (int t = 0; t < kUnroll; ++t) {
+            const int i = i0 + t * kPairsPerPass + pl;
+            const double d2 = row_sum_f64(sq_dist_chunk(qv[t], v[t]));
+            if (i < items && ch == 0) s_pair[i] = d2;
         }
     }
     __syncthreads();
