@@ -13,12 +13,11 @@
 // that tie to ~1e-15 relative (the per-head matcher resolves those in index order, see hit_kernel.hpp; the group
 // matcher below does not: it is a variant beyond the paper's rule).
 //
-// Access pattern.  A head's window is contiguous in the ring ([slot][head][entry][d]).  A quad of 4 lanes owns one
-// 256-byte row per pass, lane `sub` reading the 16-byte chunks sub, sub+4, sub+8, sub+12, so each load instruction
-// of a wave fetches 16 rows x 64 contiguous bytes.  Rows are loaded without waiting for their n_p tag (the ring
-// memory always exists; an entry outside the window is simply discarded), which removes one dependent memory
-// round trip.  The 4 partial sums of a row are combined with two cross-lane adds, the per-lane running (d2, n_p)
-// minimum with a shuffle butterfly and one exchange through shared memory between the waves.
+// Access pattern.  A head's window is contiguous in the ring ([slot][head][entry][d]).  Sixteen lanes own one 256-byte
+// row, one 16-byte chunk each, so a load instruction of a wave fetches four whole rows.  Rows are loaded without
+// waiting for their n_p tag (the ring memory always exists; an entry outside the window is simply discarded), which
+// removes one dependent memory round trip.  The 16 partial sums of a row are combined with four cross-lane adds, the
+// per-lane running (d2, n_p) minimum with a shuffle butterfly and one exchange through shared memory between the waves.
 #pragma once
 #include "common.hpp"
 

@@ -381,3 +381,16 @@ def test_head_dims_below_128(head_dim, hq, hkv, span, group):
                          rho=0.97, seed=41, ragged=131, head_dim=head_dim)
     r = run_parity(cfg, chunk_tokens=0 if hq != 6 else 96, fused_hit_span=span, group_match=group)
     assert 0 < r["hits"] < r["head_steps"] - 3 * hq
+
+
+@pytest.mark.parametrize("batch,window,head_dim", [(1, 1024, 64), (40, 64, 64), (40, 300, 128), (36, 16, 96)])
+def test_matcher_variants_by_head_count(batch, window, head_dim):
+    """The per-head matcher has three builds: 1024 threads for few heads and a large window (batch 1 here), 256 threads, and
+    a lean 256-thread one for more heads than four work-groups per compute unit (batch 36 / 40 x 32 heads here).  Each with
+    head dimensions below 128 too, windows that are not a multiple of the 32- or 64-row blocks, mixed hits."""
+    from tests.gpu_harness import run_parity
+    cfg = WorkloadConfig(name=f"variants{batch}_{window}_{head_dim}", batch=batch, num_q_heads=32, num_kv_heads=8, context=700,
+                         steps=20 if batch > 1 else 60, window=window, band=24, threshold=math.sqrt(2 * (1 - 0.97) * head_dim),
+                         rho=0.97, seed=43, ragged=13 if batch > 1 else 0, head_dim=head_dim)
+    r = run_parity(cfg, check_full=False, check_ring_every=8)
+    assert 0 < r["hits"] < r["head_steps"]
