@@ -171,7 +171,7 @@ __global__ __launch_bounds__(NT, NT == 256 ? (kLean ? 5 : 4) : 1) void hit_kerne
         const int n_pages = ((n - 1) >> p.page_shift) - first_page + 1;
         for (int i = tid; i < n_pages; i += NT) s_pid[i] = p.block_table[(int64_t)b * p.bt_stride + first_page + i];
     }
-    // ---- 1. match, in three tiers (see the head of this file): matrix-core filter, fp64 evaluation of the candidates
+    // ---- 1. match, in three tiers (see the head of this file): fp32 filter, fp64 evaluation of the candidates
     // it leaves, and -- only for candidates that tie to rounding -- the sum in index order.
     const uint16_t* ring_h = p.ring_q + ring_row0 * kHeadDim;
     const int D = p.head_dim;                                  // the caller's rows; everything in here is 128 wide, zero beyond D
