@@ -95,7 +95,7 @@ typedef struct mac_attn_step_args {
                                           at p*stride_page + kv*stride_kv + g*stride_head + r*stride_tok + i */
     int64_t        stride_page, stride_kv, stride_head, stride_tok;   /* in elements; multiples of 8;
                                                                           the d elements of a row are contiguous;
-                                                                          128 <= stride_tok < 2^26                */
+                                                                          d <= stride_tok < 2^26                  */
     const int32_t* block_table;        /* device [batch, block_table_stride]: physical page of logical page */
     int32_t        block_table_stride; /* >= ceil(max_kv_len / page_size)                                 */
     void*          out;                /* device fp32 (or bf16, see out_dtype) [batch, Hq, d]: output     */
