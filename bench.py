@@ -312,6 +312,79 @@ def match_table(torch, mb, wl_mod, timed: int = 40):
     return rows
 
 
+def balance_table(torch, mb, wl_mod, steps: int = 100):
+    """Our analogue of the paper's load-balancing study (Sec. 5.7, kernel-breakdown figure, panel b: contexts 32K / 64K /
+    128K x reuse skew 0.1 / 0.2 / 0.3, planner against a naive assignment and a perfect schedule).  Eight requests of
+    Llama-3.1-8B geometry (64 KV groups), recurring queries (reuse gap ~400, K = 1024, r = 256); "skew" here is the
+    share of KV groups that miss in a step and stream their whole context while the others stream ~650 tokens.  Three
+    schedules for the split-K attention kernel on the same steps: work items sized on the device from the step's
+    real span (the default), work items of a fixed 2048 tokens dealt to the work-groups in turn (what a host that only
+    knows max_kv_len can do), and the time the bytes the step streams would take at the rate the same kernel reaches
+    on a uniform full stream of the same cache (measured beside it)."""
+    rows = []
+    period, pstd, W, B, batch = 400, 30.0, 1024, 256, 8
+    warm = period + int(4 * pstd) + 16
+    for ctx in (32768, 65536, 131072):
+        kv = None
+        for skew in (0.1, 0.2, 0.3):
+            # a jump makes its KV group miss at that step and, one period later, once per head of the group: 5 per jump
+            cfg = wl_mod.WorkloadConfig(name=f"L_{ctx}_{skew}", batch=batch, num_q_heads=32, num_kv_heads=8, context=ctx,
+                                        steps=warm + steps, window=W, band=B, threshold=0.5 * 128 ** 0.5, rho=0.0,
+                                        seed=17, period=period, period_std=pstd, query_noise=0.1, jump_prob=skew / 5)
+            if kv is None:
+                wl = wl_mod.Workload(cfg, device="cuda:0")
+                kv = wl
+            else:
+                wl = wl_mod.Workload(cfg, device="cuda:0", queries_only=True)
+                wl.kv_pages, wl.block_table = kv.kv_pages, kv.block_table
+            inputs = [wl.next_step() for _ in range(cfg.steps)]
+            out = torch.zeros((batch, 32, 128), dtype=torch.float32, device="cuda:0")
+            stream = torch.cuda.current_stream().cuda_stream
+            res = {}
+            for label, chunk in (("planner", 0), ("fixed", 2048)):
+                mac = mb.MacAttention(num_q_heads=32, num_kv_heads=8, window=W, band=B, threshold=cfg.threshold,
+                                      max_kv_len=cfg.max_kv_len, max_slots=batch, chunk_tokens=chunk)
+                args = [mac.make_args(kv_lens=kl, q_rope=qr, kv_pages=wl.kv_pages, strides=wl.strides,
+                                      block_table=wl.block_table, out=out, slot_ids=wl.slot_ids, q_pre=qp)
+                        for (qp, qr, kl) in inputs]
+                for a in args[:warm]:
+                    mac.decode_step(a, stream)
+                torch.cuda.synchronize()
+                mac.stats(reset=True)
+                mb.mac_attn_set_timing(mac.ctx, True)
+                for a in args[warm:]:
+                    mac.decode_step(a, stream)
+                k_us, k_n = mb.mac_attn_kernel_us(mac.ctx)
+                st = mac.stats(reset=True)
+                res[label] = (k_us[1] / k_n, st)
+                if label == "planner":          # the uniform full stream of the same cache, same kernel
+                    for a in args[warm:warm + 20]:
+                        mac.full_decode(a, stream)
+                    f_us, f_n = mb.mac_attn_kernel_us(mac.ctx)
+                    full_us = f_us[1] / f_n
+                mb.mac_attn_set_timing(mac.ctx, False)
+                mac.close()
+            st = res["planner"][1]
+            split_tok = st["kv_tokens_split"] / steps
+            full_tok = batch * 8 * (ctx + warm + 10)
+            perfect_us = full_us * split_tok / full_tok
+            planner_us, fixed_us = res["planner"][0], res["fixed"][0]
+            row = {"context": ctx, "miss_share": skew, "streamed_MB": round(split_tok * 512 / 1e6, 1),
+                   "groups_missing_per_step": round((st["kv_tokens_read"] / steps) / (ctx + warm) , 2),
+                   "planner_us": round(planner_us, 1), "fixed_items_us": round(fixed_us, 1),
+                   "perfect_us": round(perfect_us, 1), "full_stream_us": round(full_us, 1),
+                   "planner_over_perfect": round(planner_us / perfect_us, 3),
+                   "excess_recovered": round((fixed_us - planner_us) / max(1e-9, fixed_us - perfect_us), 3)}
+            rows.append(row)
+            log(f"[balance-table] ctx {ctx:6d} miss share {skew:.1f} ({row['streamed_MB']:7.1f} MB/step, "
+                f"~{row['groups_missing_per_step']:.1f} of 64 groups stream everything): planner {planner_us:6.1f} us, "
+                f"fixed 2048-token items {fixed_us:6.1f} us, perfect {perfect_us:6.1f} us "
+                f"(planner = {row['planner_over_perfect']:.2f} x perfect, recovers {100 * row['excess_recovered']:.0f} % of the excess)")
+        del kv
+        torch.cuda.empty_cache()
+    return rows
+
+
 def stream_probe(torch, mb, total_bytes: int = 2 << 30):
     """What a kernel that only loads pulls out of HBM on this machine (include/mac_probe.h): 2 GiB read in segments of one
     (page, K|V, head) block of the KV cache (4 KiB) and larger, in address order and in a seeded random order, with the
@@ -446,6 +519,10 @@ def main():
     ap.add_argument("--err-table", action="store_true",
                     help="also run the synthetic analogue of the rectification-error heat-map (error of MAC against full "
                          "attention over reuse gap x band width) and add it as 'err_table'")
+    ap.add_argument("--balance-table", action="store_true",
+                    help="also run the analogue of the paper's load-balancing study (32K / 64K / 128K x share of KV groups "
+                         "that miss 0.1 / 0.2 / 0.3: device planner against fixed-size items and a perfect schedule) and "
+                         "add it as 'balance_table'")
     ap.add_argument("--graph", action="store_true",
                     help="also time the headline config replayed from one captured HIP graph per step (input refresh, "
                          "the library's launches and the step counter all inside the graph), beside the same device "
@@ -555,6 +632,8 @@ def main():
         line["match_table"] = match_table(torch, mb, wl_mod)
     if a.err_table:
         line["err_table"] = err_table(torch, mb, wl_mod)
+    if a.balance_table:
+        line["balance_table"] = balance_table(torch, mb, wl_mod)
     if a.stream_probe:
         line["stream_probe"] = stream_probe(torch, mb)
     if not a.no_cpu_baseline:
