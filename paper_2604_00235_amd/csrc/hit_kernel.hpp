@@ -142,7 +142,7 @@ __device__ __forceinline__ float dot8_bf16(const u32x4& x, const u32x4& y) {
 template <int NT, bool kLean>
 __global__ __launch_bounds__(NT, NT == 256 ? (kLean ? 5 : 4) : 1) void hit_kernel(const HitParams p) {
     constexpr int NW = NT / 64;
-    constexpr int kRows = NT / 4;                              // ring rows (or K rows) per pass: a quad per 256-byte row
+    constexpr int kRows = NT / 4;                              // ring rows per pass of the near-tie scan: a quad per 256-byte row
     // Work-groups are dealt to the 8 XCDs in turn: the G heads of a KV group take ids that are 8 apart.
     const int id = blockIdx.x, xcd = id & 7, k = id >> 3;
     const int G = p.G, Hkv = p.Hq / G;
