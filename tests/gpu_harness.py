@@ -44,14 +44,14 @@ class DeviceRun:
 
     def __init__(self, cfg: WorkloadConfig, wl: Workload, chunk_tokens: int = 0, strides=None, kv_pages=None,
                  max_kv_len=None, fuse_epilogue: bool = True, max_gap: int = 0, group_match: bool = False,
-                 out_bf16: bool = False, fused_hit_span: int = 0):
+                 out_bf16: bool = False, fused_hit_span: int = 0, sm_scale: float = 0.0):
         self.cfg, self.wl = cfg, wl
         dev = wl.device
         self.mac = mb.MacAttention(num_q_heads=cfg.num_q_heads, num_kv_heads=cfg.num_kv_heads, window=cfg.window,
                                    band=cfg.band, threshold=cfg.threshold, max_kv_len=max_kv_len or cfg.max_kv_len,
                                    max_slots=cfg.batch, page_size=cfg.page_size, head_dim=cfg.head_dim, chunk_tokens=chunk_tokens,
                                    fuse_epilogue=fuse_epilogue, max_gap=max_gap, group_match=group_match,
-                                   out_bf16=out_bf16, fused_hit_span=fused_hit_span)
+                                   out_bf16=out_bf16, fused_hit_span=fused_hit_span, sm_scale=sm_scale)
         self.kv_pages = wl.kv_pages if kv_pages is None else kv_pages
         self.strides = wl.strides if strides is None else strides
         B, Hq, d = cfg.batch, cfg.num_q_heads, cfg.head_dim
@@ -104,7 +104,7 @@ class DeviceRun:
 
 def run_parity(cfg: WorkloadConfig, chunk_tokens: int = 0, check_full: bool = True, check_ring_every: int = 4,
                label: str = "", fuse_epilogue: bool = True, max_gap: int = 0, group_match: bool = False,
-               fused_hit_span: int = 0):
+               fused_hit_span: int = 0, sm_scale: float = 0.0):
     """All steps of `cfg` on both sides; returns summary dict.  Oracle inputs are host copies of the same bits."""
     say(f"[parity] {label or cfg.name}: batch={cfg.batch} Hq/Hkv={cfg.num_q_heads}/{cfg.num_kv_heads} "
         f"context={cfg.context} steps={cfg.steps} W={cfg.window} B={cfg.band} T={cfg.threshold:.4g} "
@@ -113,8 +113,8 @@ def run_parity(cfg: WorkloadConfig, chunk_tokens: int = 0, check_full: bool = Tr
         f"seed={cfg.seed}")
     wl = Workload(cfg, device="cuda:0")
     run = DeviceRun(cfg, wl, chunk_tokens, fuse_epilogue=fuse_epilogue, max_gap=max_gap, group_match=group_match,
-                    fused_hit_span=fused_hit_span)
-    orc = make_oracle(cfg, wl, max_gap=max_gap, group_match=group_match)
+                    fused_hit_span=fused_hit_span, sm_scale=sm_scale)
+    orc = make_oracle(cfg, wl, max_gap=max_gap, group_match=group_match, **({"sm_scale": sm_scale} if sm_scale > 0 else {}))
     kvp = bf16_bits(wl.kv_pages)
     bt = wl.block_table.cpu().numpy()
     slots = wl.slot_ids.cpu().numpy()

@@ -394,3 +394,27 @@ def test_matcher_variants_by_head_count(batch, window, head_dim):
                          rho=0.97, seed=43, ragged=13 if batch > 1 else 0, head_dim=head_dim)
     r = run_parity(cfg, check_full=False, check_ring_every=8)
     assert 0 < r["hits"] < r["head_steps"]
+
+
+@pytest.mark.parametrize("align,head_dim", [(1.5, 128), (3.0, 128), (2.0, 64)])
+def test_recency_weighted_logits(align, head_dim):
+    """Keys and queries share a per-KV-head direction, so that logits are large for recent keys and decay with
+    distance (the input model of the error table): peaked softmax rows with a wide dynamic range of the logits, on the
+    hit path, the split-K path and full decode."""
+    from tests.gpu_harness import run_parity
+    cfg = WorkloadConfig(name=f"recency{align}_{head_dim}", batch=3, num_q_heads=8, num_kv_heads=2, context=2500, steps=24, window=32,
+                         band=48, threshold=math.sqrt(2 * (1 - 0.97) * head_dim) * (1.0 + 0.0), rho=0.97, seed=47, ragged=9,
+                         align=align, head_dim=head_dim)
+    r = run_parity(cfg, check_full=True, check_ring_every=4)
+    assert r["head_steps"] == cfg.steps * cfg.batch * cfg.num_q_heads
+
+
+@pytest.mark.parametrize("sm_scale", [0.5, 0.01])
+def test_softmax_scale_given_by_the_caller(sm_scale):
+    """sm_scale other than 1/sqrt(d): 0.5 makes the logits of N(0, 1) rows ~5.7 wide (one key takes most of a row), 0.01
+    makes every row nearly uniform.  Both through the hit path, the split-K path and full decode."""
+    from tests.gpu_harness import run_parity
+    cfg = WorkloadConfig(name=f"scale{sm_scale}", batch=2, num_q_heads=8, num_kv_heads=2, context=1800, steps=20, window=16,
+                         band=40, threshold=math.sqrt(2 * (1 - 0.97) * 128), rho=0.97, seed=53, ragged=5)
+    r = run_parity(cfg, check_full=True, check_ring_every=4, sm_scale=sm_scale)
+    assert 0 < r["hits"] < r["head_steps"]
