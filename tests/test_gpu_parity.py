@@ -418,3 +418,50 @@ def test_softmax_scale_given_by_the_caller(sm_scale):
                          band=40, threshold=math.sqrt(2 * (1 - 0.97) * 128), rho=0.97, seed=53, ragged=5)
     r = run_parity(cfg, check_full=True, check_ring_every=4, sm_scale=sm_scale)
     assert 0 < r["hits"] < r["head_steps"]
+
+
+def test_requests_join_leave_and_change_places_in_the_batch():
+    """Continuous batching: four requests on ring sets 5, 0, 3, 2 of a context with six; every step serves a seeded
+    subset of them in a seeded order (2 to 4 requests: rows of kv_lens, queries, block table and slot_ids permuted
+    together), so a request's place in the batch changes from step to step and a request that sits out a step finds
+    its ring one entry short; at step 14 the request on ring set 3 leaves and a new one takes the set over (reset:
+    its first step misses).  Decisions and outputs against the oracle at every step (what the rings hold shows in the
+    later steps' decisions and merged outputs)."""
+    from paper_2604_00235_amd import binding as mb
+    from tests.gpu_harness import DeviceRun, check_rows
+    from tests.helpers import make_oracle
+    cfg = WorkloadConfig(name="batching", batch=4, num_q_heads=8, num_kv_heads=2, context=900, steps=28, window=8, band=24,
+                         threshold=math.sqrt(2 * (1 - 0.97) * 128), rho=0.97, seed=59, ragged=11)
+    wl = Workload(cfg, device="cuda:0")
+    n_sets = 6
+    run = DeviceRun(cfg, wl)
+    run.mac.close()
+    run.mac = mb.MacAttention(num_q_heads=cfg.num_q_heads, num_kv_heads=cfg.num_kv_heads, window=cfg.window, band=cfg.band,
+                              threshold=cfg.threshold, max_kv_len=cfg.max_kv_len, max_slots=n_sets, max_batch=cfg.batch)
+    orc = make_oracle(cfg, wl, max_slots=n_sets)
+    kvp = bf16_bits(wl.kv_pages)
+    set_of = torch.tensor([5, 0, 3, 2], dtype=torch.int32, device="cuda:0")
+    rng = np.random.default_rng(61)
+    hits = 0
+    for s, (q_pre, q_rope, kv_lens) in enumerate(wl):
+        if s == 14:
+            run.mac.reset([3])
+            orc.reset([3])
+        k = int(rng.integers(2, 5))
+        order = torch.from_numpy(rng.permutation(4)[:k].astype(np.int64)).to("cuda:0")
+        qp, qr = q_pre[order].contiguous(), q_rope[order].contiguous()
+        kl, bt, sl = kv_lens[order].contiguous(), wl.block_table[order].contiguous(), set_of[order].contiguous()
+        a = run.mac.make_args(kv_lens=kl, q_rope=qr, kv_pages=wl.kv_pages, strides=wl.strides, block_table=bt,
+                              out=run.out, slot_ids=sl, q_pre=qp, out_lse=run.lse, match_pos=run.pos, match_d2=run.d2)
+        run.mac.decode_step(a, run.stream)
+        torch.cuda.synchronize()
+        run.check_guards()
+        ref = orc.mac_step(sl.cpu().numpy(), kl.cpu().numpy(), bf16_bits(qp), bf16_bits(qr), kvp, bt.cpu().numpy())
+        pos = run.pos.cpu().numpy()[:k]
+        assert np.array_equal(pos, ref["match_pos"]), f"step {s}"
+        if s == 14 and 2 in order.tolist():
+            assert (pos[order.tolist().index(2)] == -1).all()          # the new request's first step
+        check_rows(run.out.cpu().numpy()[:k], ref["out"], f"batching step {s}")
+        hits += int((pos >= 0).sum())
+    assert hits > 0
+    run.mac.close()
