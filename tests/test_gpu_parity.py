@@ -465,3 +465,41 @@ def test_requests_join_leave_and_change_places_in_the_batch():
         hits += int((pos >= 0).sum())
     assert hits > 0
     run.mac.close()
+
+
+def test_optional_outputs_left_out_a_stream_of_the_callers_and_kernel_timing():
+    """The same steps on two contexts: one with every optional output (LSE, matched position, distance) on the default
+    stream, one with none of them, on a stream of the caller's, with per-kernel timing switched on.  The attention
+    outputs must be the same bits; the timing must report one record per call and times that are positive where a
+    kernel ran."""
+    from paper_2604_00235_amd import binding as mb
+    from tests.gpu_harness import DeviceRun
+    cfg = WorkloadConfig(name="optional", batch=2, num_q_heads=8, num_kv_heads=2, context=1200, steps=10, window=8, band=32,
+                         threshold=math.sqrt(2 * (1 - 0.97) * 128), rho=0.97, seed=67, ragged=3)
+    wl = Workload(cfg, device="cuda:0")
+    full = DeviceRun(cfg, wl)
+    bare = DeviceRun(cfg, wl)
+    side = torch.cuda.Stream()
+    mb.mac_attn_set_timing(bare.mac.ctx, True)
+    calls = 0
+    for s, (q_pre, q_rope, kv_lens) in enumerate(wl):
+        for mode in ("mac", "full"):
+            a = full.args(q_pre if mode == "mac" else None, q_rope, kv_lens)
+            (full.mac.decode_step if mode == "mac" else full.mac.full_decode)(a, full.stream)
+            b = bare.mac.make_args(kv_lens=kv_lens, q_rope=q_rope, kv_pages=wl.kv_pages, strides=wl.strides,
+                                   block_table=wl.block_table, out=bare.out, slot_ids=wl.slot_ids,
+                                   q_pre=q_pre if mode == "mac" else None)
+            side.wait_stream(torch.cuda.current_stream())
+            (bare.mac.decode_step if mode == "mac" else bare.mac.full_decode)(b, side.cuda_stream)
+            calls += 1
+            torch.cuda.synchronize()
+            full.check_guards()
+            bare.check_guards()
+            assert torch.equal(full.out, bare.out), f"step {s} {mode}"
+    us, n = mb.mac_attn_kernel_us(bare.mac.ctx)
+    assert n == calls
+    assert us[1] > 0 and us[2] > 0 and us[0] > 0          # attention and merge in every call, the matcher in the MAC steps
+    assert all(0 <= u < 1e6 for u in us)
+    mb.mac_attn_set_timing(bare.mac.ctx, False)
+    full.mac.close()
+    bare.mac.close()
