@@ -503,3 +503,53 @@ def test_optional_outputs_left_out_a_stream_of_the_callers_and_kernel_timing():
     mb.mac_attn_set_timing(bare.mac.ctx, False)
     full.mac.close()
     bare.mac.close()
+
+
+def test_invalid_step_arguments_are_refused_and_nothing_runs():
+    """Each of the step arguments the host can check, broken one at a time on an otherwise valid call: the call returns
+    MAC_ATTN_ERR_INVALID_ARG and enqueues nothing (the output keeps its sentinel, the counters do not move)."""
+    from paper_2604_00235_amd import binding as mb
+    from tests.gpu_harness import DeviceRun
+    cfg = WorkloadConfig(name="badargs", batch=2, num_q_heads=4, num_kv_heads=2, context=100, steps=2, window=4, band=8,
+                         threshold=1.0, rho=0.9, seed=71)
+    wl = Workload(cfg, device="cuda:0")
+    run = DeviceRun(cfg, wl)
+    q_pre, q_rope, kv_lens = wl.next_step()
+    good = run.args(q_pre, q_rope, kv_lens)
+    run.mac.decode_step(good, run.stream)                  # the valid call works
+    torch.cuda.synchronize()
+    run.mac.stats(reset=True)
+    run.out.fill_(-7.0)
+
+    def broken(**kw):
+        a = mb.mac_attn_step_args()
+        for f, _ in a._fields_:
+            setattr(a, f, getattr(good, f))
+        for k, v in kw.items():
+            setattr(a, k, v)
+        return a
+    cases = [("kv_lens", broken(kv_lens=None)), ("q_rope", broken(q_rope=None)), ("kv_pages", broken(kv_pages=None)),
+             ("block_table", broken(block_table=None)), ("out", broken(out=None)), ("batch 0", broken(batch=0)),
+             ("batch 3", broken(batch=3)), ("table stride", broken(block_table_stride=1)),
+             ("stride 0", broken(stride_head=0)), ("stride % 8", broken(stride_page=good.stride_page + 4)),
+             ("token stride below d", broken(stride_tok=64)), ("q_rope alignment", broken(q_rope=q_rope.data_ptr() + 2)),
+             ("kv_pages alignment", broken(kv_pages=wl.kv_pages.data_ptr() + 8))]
+    mac_only = [("q_pre", broken(q_pre=None)), ("slot_ids", broken(slot_ids=None)),
+                ("q_pre alignment", broken(q_pre=q_pre.data_ptr() + 2))]
+    for name, a in cases + mac_only:
+        with pytest.raises(mb.MacAttnError) as e:
+            mb.mac_attn_decode_step(run.mac.ctx, a, run.stream)
+        assert e.value.code == mb.MAC_ATTN_ERR_INVALID_ARG, name
+    for name, a in cases:
+        with pytest.raises(mb.MacAttnError) as e:
+            mb.mac_attn_full_decode(run.mac.ctx, a, run.stream)
+        assert e.value.code == mb.MAC_ATTN_ERR_INVALID_ARG, name
+    for name, a in mac_only[:2]:
+        mb.mac_attn_full_decode(run.mac.ctx, a, run.stream)      # full decode ignores them
+        torch.cuda.synchronize()
+        run.out.fill_(-7.0)
+    torch.cuda.synchronize()
+    assert bool((run.out == -7.0).all())
+    assert run.mac.stats()["steps"] == 0
+    run.check_guards()
+    run.mac.close()
