@@ -124,6 +124,18 @@ def test_work_items_at_the_size_cap():
     assert hits == st["head_steps"] - 16 * 32
 
 
+@pytest.mark.parametrize("batch,window", [(64, 1024), (32, 2048)])
+def test_query_rings_beyond_the_last_level_cache(batch, window):
+    """batch x 32 heads x W x 256 B = 537 MB of query rows scanned per step, twice the last-level cache (64 x 32 heads:
+    the lean 256-thread build of the matcher; 32 x 32: the plain one).  Short context, a few steps with hits and
+    misses, all heads against the oracle."""
+    from tests.gpu_harness import run_parity
+    cfg = WorkloadConfig(name=f"bigring{batch}_{window}", batch=batch, num_q_heads=32, num_kv_heads=8, context=150, steps=6,
+                         window=window, band=32, threshold=float(np.sqrt(2 * (1 - 0.97) * 128)), rho=0.97, seed=73, ragged=7)
+    r = run_parity(cfg, check_full=False, check_ring_every=3)
+    assert 0 < r["hits"] < r["head_steps"]
+
+
 def test_c4_mqa_64k_full_size_all_miss_and_matched():
     hits, st = run_fullsize(CONFIGS["C4_miss"], steps=3, full_every=2)
     assert hits == 0 and st["kv_tokens_read"] == st["kv_tokens_full"]
