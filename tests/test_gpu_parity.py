@@ -298,16 +298,21 @@ def test_memory_the_request_does_not_own_may_hold_nan(page_size, context, head_d
     run.mac.close()
 
 
-def test_candidates_that_tie_to_rounding_are_decided_as_the_index_order_sum_decides():
+@pytest.mark.parametrize("window,batch,hq,hkv", [(2, 2, 4, 2), (300, 1, 8, 2), (2, 40, 32, 8)])
+def test_candidates_that_tie_to_rounding_are_decided_as_the_index_order_sum_decides(window, batch, hq, hkv):
     """Two window entries whose distances to the query are equal as real numbers (one is a permutation of the other, the
     query is zero) or differ far below the rounding error of a 128-term fp64 sum (one small element nudged).  The
     terms span ~2^60, so the fp64 value depends on the order of summation, and which entry is "nearest" is decided by
     that rounding.  The reference takes the plain left-to-right sum; the library has to come to the same decision and
-    the same distance bit for bit (its matcher re-sums such candidates in index order), at every such step."""
+    the same distance bit for bit (its matcher re-sums such candidates in index order), at every such step.
+    Three shapes, one per build of the matcher: 256 threads, 1024 threads (few heads, window above 256) and the lean
+    one (more than 1024 heads); the latter two start every triple of steps from empty rings, so that the two entries
+    are the whole window."""
     from tests.gpu_harness import DeviceRun, check_rows
     from tests.helpers import make_oracle
-    cfg = WorkloadConfig(name="neartie", batch=2, num_q_heads=4, num_kv_heads=2, context=50, steps=30, window=2, band=8,
-                         threshold=1e30, rho=0.9, seed=51)
+    cfg = WorkloadConfig(name=f"neartie{window}_{batch}", batch=batch, num_q_heads=hq, num_kv_heads=hkv, context=50,
+                         steps=30 if batch < 8 else 12, window=window, band=8, threshold=1e30, rho=0.9, seed=51)
+    fresh_triples = (window, batch) != (2, 2)
     wl = Workload(cfg, device="cuda:0")
     run = DeviceRun(cfg, wl, chunk_tokens=32)
     orc = make_oracle(cfg, wl)
@@ -355,6 +360,9 @@ def test_candidates_that_tie_to_rounding_are_decided_as_the_index_order_sum_deci
             assert np.array_equal(g_d2, ref["d2"]), f"step {s}: distances differ in the last bits"
             assert (g_pos >= 0).all()
         check_rows(g_out, ref["out"], f"neartie step {s}")
+        if s % 3 == 2 and fresh_triples:
+            run.mac.reset()
+            orc.reset()
     assert order_matters > 0 and decided_by_rounding > 0, (order_matters, decided_by_rounding)
     run.mac.close()
 
