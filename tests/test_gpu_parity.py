@@ -561,3 +561,16 @@ def test_invalid_step_arguments_are_refused_and_nothing_runs():
     assert run.mac.stats()["steps"] == 0
     run.check_guards()
     run.mac.close()
+
+
+@pytest.mark.parametrize("batch,hq,hkv", [(1, 8, 2), (3, 16, 4)])
+def test_longest_fresh_ranges_the_matcher_finishes_itself(batch, hq, hkv):
+    """Reuse gaps of ~1500 tokens with a band of 256: fresh ranges of ~1760 tokens, finished inside the matcher's
+    work-group with fused_hit_span at its maximum of 2048 (several passes over the K and V rows per work-group, the
+    logits of a whole range in shared memory), in the 1024-thread build (batch 1) and the 256-thread one."""
+    from tests.gpu_harness import run_parity
+    cfg = WorkloadConfig(name=f"longfused{batch}", batch=batch, num_q_heads=hq, num_kv_heads=hkv, context=2600, steps=1590,
+                         window=2048, band=256, threshold=T_DEFAULT, rho=0.0, seed=79, period=1500, period_std=12.0,
+                         query_noise=0.1, jump_prob=0.0, ragged=5 if batch > 1 else 0)
+    r = run_parity(cfg, check_full=False, check_ring_every=200, fused_hit_span=2048)
+    assert r["hits"] > 0 and r["kv_tokens_fused"] > 1500 * r["hits"] // 2
