@@ -574,3 +574,14 @@ def test_longest_fresh_ranges_the_matcher_finishes_itself(batch, hq, hkv):
                          query_noise=0.1, jump_prob=0.0, ragged=5 if batch > 1 else 0)
     r = run_parity(cfg, check_full=False, check_ring_every=200, fused_hit_span=2048)
     assert r["hits"] > 0 and r["kv_tokens_fused"] > 1500 * r["hits"] // 2
+
+
+@pytest.mark.parametrize("page_size", [128, 1024])
+def test_large_pages(page_size):
+    """KV pages of 128 and 1024 tokens (a work item then lies inside one or two pages; a request of ~2600 tokens has
+    three pages of 1024), per-head matching with the fused hit path, the split-K path and full decode."""
+    from tests.gpu_harness import run_parity
+    cfg = WorkloadConfig(name=f"page{page_size}", batch=3, num_q_heads=8, num_kv_heads=2, context=2600, steps=16, window=16,
+                         band=40, threshold=math.sqrt(2 * (1 - 0.97) * 128), rho=0.97, seed=83, ragged=301, page_size=page_size)
+    r = run_parity(cfg, check_full=True, check_ring_every=4)
+    assert 0 < r["hits"] < r["head_steps"]
