@@ -585,3 +585,36 @@ def test_large_pages(page_size):
                          band=40, threshold=math.sqrt(2 * (1 - 0.97) * 128), rho=0.97, seed=83, ragged=301, page_size=page_size)
     r = run_parity(cfg, check_full=True, check_ring_every=4)
     assert 0 < r["hits"] < r["head_steps"]
+
+
+@pytest.mark.parametrize("head_dim", [128, 64])
+def test_separate_k_and_v_pools_with_padded_rows(head_dim):
+    """Another layout through the same strides: all K pages first, then all V pages ([2, page, head, tok, d + 32]), rows
+    padded by 32 elements that hold NaN and must never be read."""
+    from tests.gpu_harness import DeviceRun, check_rows
+    from tests.helpers import make_oracle
+    cfg = WorkloadConfig(name=f"pools{head_dim}", batch=2, num_q_heads=8, num_kv_heads=2, context=700, steps=8, window=8, band=24,
+                         threshold=math.sqrt(2 * (1 - 0.97) * head_dim), rho=0.97, seed=89, ragged=17, head_dim=head_dim)
+    wl = Workload(cfg, device="cuda:0")
+    ps, d, hkv = cfg.page_size, cfg.head_dim, cfg.num_kv_heads
+    pages = wl.kv_pages.shape[0]
+    dp = d + 32
+    pools = torch.full((2, pages, hkv, ps, dp), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    pools[..., :d] = wl.kv_pages.permute(1, 0, 2, 3, 4)
+    strides = (hkv * ps * dp, pages * hkv * ps * dp, ps * dp, dp)
+    run = DeviceRun(cfg, wl, strides=strides, kv_pages=pools)
+    orc = make_oracle(cfg, wl, strides=strides)
+    kvp, bt, slots = bf16_bits(pools), wl.block_table.cpu().numpy(), wl.slot_ids.cpu().numpy()
+    hits = 0
+    for s, (q_pre, q_rope, kv_lens) in enumerate(wl):
+        lens = kv_lens.cpu().numpy()
+        g_full, _ = run.full(q_rope, kv_lens)
+        o_full, _ = orc.full_decode(lens, bf16_bits(q_rope), kvp, bt)
+        check_rows(g_full, o_full, f"pools step {s} full decode")
+        g_out, _, g_pos, _ = run.mac_step(q_pre, q_rope, kv_lens)
+        ref = orc.mac_step(slots, lens, bf16_bits(q_pre), bf16_bits(q_rope), kvp, bt)
+        assert np.array_equal(g_pos, ref["match_pos"])
+        check_rows(g_out, ref["out"], f"pools step {s}")
+        hits += int((g_pos >= 0).sum())
+    assert hits > 0
+    run.mac.close()
