@@ -77,3 +77,22 @@ def test_static_full_decode_rejects_what_does_not_fit():
     assert lib.mac_attn_full_decode_static(None, C.byref(args), None) == mb.MAC_ATTN_ERR_INVALID_ARG
     torch.cuda.synchronize()
     assert float(out.abs().sum()) == 0.0                     # nothing was enqueued
+
+
+def test_static_full_decode_with_the_default_item_size():
+    """chunk_tokens = 0 in the geometry: the item size comes from the host rule the header states (a power of two in
+    [512, 2048] from batch * Hkv * max_kv_len / 2048, at least 64 G): 512 tokens for 3 x 8 groups of ~5300 tokens.  Same
+    bits as a context with that item size fixed."""
+    from paper_2604_00235_amd import binding as mb
+    from tests.gpu_harness import DeviceRun
+    cfg = scaled(CONFIGS["C2"], name="static_default", batch=3, context=5000, steps=2, ragged=333)
+    wl = Workload(cfg, device="cuda:0")
+    run = DeviceRun(cfg, wl, chunk_tokens=512)
+    out = torch.full((cfg.batch, cfg.num_q_heads, cfg.head_dim), float("nan"), device="cuda:0")
+    lse = torch.full((cfg.batch, cfg.num_q_heads), float("nan"), device="cuda:0")
+    for q_pre, q_rope, kv_lens in wl:
+        ref_out, ref_lse = run.full(q_rope, kv_lens)
+        _static_call(mb, cfg, wl, q_rope, kv_lens, out, lse, 0)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), ref_out) and np.array_equal(lse.cpu().numpy(), ref_lse)
+    run.mac.close()
