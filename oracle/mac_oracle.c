@@ -271,6 +271,7 @@ void oracle_mac_step(const oracle_params *P, const int32_t *slot_ids, const int3
     for (int b = 0; b < P->batch; ++b) {
         int64_t slot = slot_ids[b];
         int64_t n = kv_lens[b];
+        if (n < 1) continue;                 /* a request without tokens has no query position: entries are created at lengths n >= 1 */
         int64_t j = (n - 1) % W;
         for (int h = 0; h < Hq; ++h) {
             int bh = b * Hq + h;

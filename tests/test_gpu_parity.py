@@ -618,3 +618,47 @@ def test_separate_k_and_v_pools_with_padded_rows(head_dim):
         hits += int((g_pos >= 0).sum())
     assert hits > 0
     run.mac.close()
+
+
+def test_requests_without_tokens_and_lengths_out_of_range():
+    """kv_len = 0 (a padding row of a static batch): the output is the empty summary (0, -inf), every head misses and no
+    ring entry is written, while the other requests of the batch are served as usual.  Lengths outside [0, max_kv_len]
+    are clamped on the device: -5 acts as 0, max_kv_len + 100 as max_kv_len (the oracle is given the clamped values)."""
+    from tests.gpu_harness import DeviceRun, check_rows
+    from tests.helpers import make_oracle
+    cfg = WorkloadConfig(name="emptyreq", batch=4, num_q_heads=8, num_kv_heads=2, context=300, steps=14, window=8, band=24,
+                         threshold=math.sqrt(2 * (1 - 0.97) * 128), rho=0.97, seed=97, ragged=7)
+    wl = Workload(cfg, device="cuda:0")
+    run = DeviceRun(cfg, wl)
+    orc = make_oracle(cfg, wl)
+    kvp, bt, slots = bf16_bits(wl.kv_pages), wl.block_table.cpu().numpy(), wl.slot_ids.cpu().numpy()
+    hits = 0
+    for s, (q_pre, q_rope, kv_lens) in enumerate(wl):
+        given = kv_lens.clone()
+        given[0] = 0                                   # never has a token
+        if s % 3 == 1:
+            given[2] = -5                              # sits out every third step
+        if s == 9:
+            given[3] = cfg.max_kv_len + 100
+        lens = np.clip(given.cpu().numpy(), 0, cfg.max_kv_len)
+        g_full, g_flse = run.full(q_rope, given)
+        o_full, o_flse = orc.full_decode(lens, bf16_bits(q_rope), kvp, bt)
+        check_rows(g_full, o_full, f"emptyreq step {s} full decode")
+        assert np.array_equal(np.isinf(g_flse), np.isinf(o_flse))
+        g_out, g_lse, g_pos, g_d2 = run.mac_step(q_pre, q_rope, given)
+        ref = orc.mac_step(slots, lens, bf16_bits(q_pre), bf16_bits(q_rope), kvp, bt)
+        assert np.array_equal(g_pos, ref["match_pos"]), f"step {s}"
+        assert np.array_equal(np.isinf(g_d2), np.isinf(ref["d2"]))
+        check_rows(g_out, ref["out"], f"emptyreq step {s}")
+        for b in np.where(lens == 0)[0]:
+            assert (g_out[b] == 0).all() and (g_lse[b] == -np.inf).all() and (g_pos[b] == -1).all()
+            assert (g_full[b] == 0).all() and (g_flse[b] == -np.inf).all()
+        hits += int((g_pos >= 0).sum())
+    for j in range(cfg.window):                         # the ring set of the request that never had a token is still empty
+        for h in (0, cfg.num_q_heads - 1):
+            assert run.mac.ring_peek(0, j, h)[3] == 0
+    assert hits > 0
+    gst, ost = run.mac.stats(), orc.stats.as_dict()
+    for k in ("steps", "head_steps", "hits", "misses", "sum_gap", "kv_tokens_read", "kv_tokens_full"):
+        assert gst[k] == ost[k], k
+    run.mac.close()

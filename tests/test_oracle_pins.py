@@ -466,6 +466,38 @@ def test_writeback_holds_rectified_summary_of_this_step():
                 assert orc.ring_lse[b, j, h] == pytest.approx(exp_l, rel=1e-13) or (exp_l == -np.inf and orc.ring_lse[b, j, h] == -np.inf)
 
 
+def test_request_without_tokens_changes_nothing_and_gets_the_empty_summary():
+    """Sec. 4.1 / Fig. 1(c): ring entries are created at lengths n >= 1 (entry (n - 1) mod W carries the tag n, tag 0 means
+    empty).  A request with kv_len = 0 has no key to attend to and no query position to store: its output is the empty
+    summary (0, -inf) (Sec. 2: a sum over no keys), every head misses, no ring set changes, and the other requests of
+    the batch come out exactly as in a batch without it."""
+    cfg = small_cfg(threshold=3.5, band=3, window=4, steps=8)
+    wl, wl2 = Workload(cfg), Workload(cfg)
+    orc, alone = make_oracle(cfg, wl), make_oracle(cfg, wl2)
+    kvp, bt, slots = host_inputs(wl)
+    hits = 0
+    for q_pre, q_rope, kv_lens in wl:
+        lens = kv_lens.numpy().copy()
+        lens[0] = 0
+        before = [a.copy() for a in (orc.ring_q[0], orc.ring_O[0], orc.ring_lse[0], orc.ring_npos[0])]
+        r = orc.mac_step(slots, lens, bf16_bits(q_pre), bf16_bits(q_rope), kvp, bt)
+        assert (r["match_pos"][0] == -1).all() and np.isinf(r["d2"][0]).all()
+        assert (r["out"][0] == 0).all() and (r["lse"][0] == -np.inf).all()
+        for a, b_ in zip(before, (orc.ring_q[0], orc.ring_O[0], orc.ring_lse[0], orc.ring_npos[0])):
+            np.testing.assert_array_equal(a, b_)
+        assert (orc.ring_npos[0] == 0).all()
+        o_full, l_full = orc.full_decode(lens, bf16_bits(q_rope), kvp, bt)
+        assert (o_full[0] == 0).all() and (l_full[0] == -np.inf).all()
+        # the same step for requests 1.. alone
+        r2 = alone.mac_step(slots[1:], lens[1:], bf16_bits(q_pre)[1:], bf16_bits(q_rope)[1:], kvp, bt[1:])
+        np.testing.assert_array_equal(r["match_pos"][1:], r2["match_pos"])
+        np.testing.assert_array_equal(r["out"][1:], r2["out"])
+        hits += int((r2["match_pos"] >= 0).sum())
+    assert hits > 0
+    st = orc.stats.as_dict()
+    assert st["misses"] >= 8 * cfg.num_q_heads and st["kv_tokens_full"] == alone.stats.as_dict()["kv_tokens_full"]
+
+
 def test_error_falls_as_band_widens():
     """Sec. 5.2 "Insights" (sanity trend, not a pin): with recency-biased logits the error of reuse falls
     as the band grows, and vanishes once the band covers the context."""
