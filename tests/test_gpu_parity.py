@@ -662,3 +662,32 @@ def test_requests_without_tokens_and_lengths_out_of_range():
     for k in ("steps", "head_steps", "hits", "misses", "sum_gap", "kv_tokens_read", "kv_tokens_full"):
         assert gst[k] == ost[k], k
     run.mac.close()
+
+
+def test_a_request_rolls_back_some_tokens():
+    """The length of a request goes back by 6 tokens in mid-stream (rejected speculative tokens) and grows again from
+    there: its ring then holds entries created at lengths beyond the current one, which are no candidates (Eq. (accept):
+    n_p <= n - 1) until the stream overwrites them, entry by entry, with the new ones."""
+    from tests.gpu_harness import DeviceRun, check_rows
+    from tests.helpers import make_oracle
+    cfg = WorkloadConfig(name="rollback", batch=2, num_q_heads=8, num_kv_heads=2, context=200, steps=30, window=16, band=24,
+                         threshold=math.sqrt(2 * (1 - 0.97) * 128) * 1.3, rho=0.97, seed=101)
+    wl = Workload(cfg, device="cuda:0")
+    run = DeviceRun(cfg, wl)
+    orc = make_oracle(cfg, wl)
+    kvp, bt, slots = bf16_bits(wl.kv_pages), wl.block_table.cpu().numpy(), wl.slot_ids.cpu().numpy()
+    hits_after = 0
+    for s, (q_pre, q_rope, kv_lens) in enumerate(wl):
+        given = kv_lens.clone()
+        if s >= 12:
+            given[1] -= 6
+        lens = given.cpu().numpy()
+        g_out, g_lse, g_pos, g_d2 = run.mac_step(q_pre, q_rope, given)
+        ref = orc.mac_step(slots, lens, bf16_bits(q_pre), bf16_bits(q_rope), kvp, bt)
+        assert np.array_equal(g_pos, ref["match_pos"]), f"step {s}"
+        assert (g_pos[1] < lens[1]).all()
+        check_rows(g_out, ref["out"], f"rollback step {s}")
+        if s >= 12:
+            hits_after += int((g_pos[1] >= 0).sum())
+    assert hits_after > 0
+    run.mac.close()
